@@ -1,0 +1,171 @@
+/*
+ * libmq -- Matryoshka-sliced, group-dequantised linear layers on AMD MI355X (gfx950).
+ *
+ * The library executes the inference path of MatGPTQ (arXiv 2602.03537):
+ * a c = 8 bit "parent" integer checkpoint is sliced to r in {2,3,4,6,8} bits
+ * (Eq. 1, Section 2), packed so that an r-bit layer streams r bits per weight,
+ * and multiplied on the fly  y = x * W_D^T  with per-group scale / zero-offset
+ * (Section 3.2 item 1; Section 4), each layer with its own r (Section 3.3).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller unless the
+ *     argument is marked "host".  The library never allocates, frees or
+ *     synchronises; every call enqueues work on `stream` (a hipStream_t passed
+ *     as void*, NULL = the default stream) and returns.
+ *   - Arguments are validated on the host BEFORE anything is enqueued; a call
+ *     that returns anything but MQ_OK has enqueued nothing.  No exceptions, no
+ *     abort.  Launch failures reported by the HIP runtime map to MQ_ERR_HIP.
+ *   - Matrices are row-major.  W is [N, K] (torch.nn.Linear convention:
+ *     N output features, K input features), x is [M, K], y is [M, N].
+ *   - fp16 values are IEEE binary16 (uint16_t storage on the C side).
+ *   - c is fixed to 8 for packing and the linear kernels; mq_slice_codes
+ *     accepts any 1 <= r <= c <= 8.
+ *   - group must be 128 and must divide K.
+ */
+#ifndef MQ_H
+#define MQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MQ_OK = 0,
+    MQ_ERR_NULL = 1,          /* a required pointer is NULL */
+    MQ_ERR_BAD_R = 2,         /* bit-width not supported by this entry point */
+    MQ_ERR_BAD_SHAPE = 3,     /* M, N, K or a count is out of range */
+    MQ_ERR_BAD_GROUP = 4,     /* group != 128 or group does not divide K */
+    MQ_ERR_ALIGN = 5,         /* a pointer is not aligned as documented */
+    MQ_ERR_BUF_TOO_SMALL = 6, /* packed / meta / workspace buffer too small */
+    MQ_ERR_HIP = 7,           /* the HIP runtime refused a launch or a copy */
+    MQ_ERR_UNSUPPORTED = 8    /* valid request this build has no kernel for */
+} mq_status;
+
+typedef void *mq_stream; /* hipStream_t */
+typedef uint16_t mq_half; /* IEEE binary16 bits */
+
+/* Rows of W are processed in blocks of MQ_ROW_BLOCK; packed buffers pad N up. */
+#define MQ_ROW_BLOCK 64
+#define MQ_GROUP 128
+#define MQ_MAX_M 256
+
+const char *mq_status_str(int status);
+int mq_version(void);
+
+/* ---------------------------------------------------------------- sizes
+ * Pure host arithmetic, callable without a GPU.  All return 0 on invalid
+ * arguments.  With Npad = N rounded up to MQ_ROW_BLOCK:
+ *   mq_packed_bytes    = Npad * K * r / 8            (exactly r bits per weight)
+ *   mq_meta_bytes      = Npad * (K/group) * 2        (bytes of EACH of the two
+ *                                                     tiled arrays scales_t, zeros_t)
+ *   mq_workspace_bytes = bytes mq_linear needs in `ws` for this problem.
+ */
+size_t mq_packed_bytes(int64_t N, int64_t K, int r);
+size_t mq_meta_bytes(int64_t N, int64_t K, int group);
+size_t mq_workspace_bytes(int64_t M, int64_t N, int64_t K, int r);
+
+/* Zero the synchronisation counters at the start of a workspace.  Must be
+ * enqueued once on a fresh workspace before its first use by mq_linear; the
+ * kernels leave the counters zero when they finish, so it is not needed again.
+ * A workspace must not be shared by calls that may run concurrently.
+ * ws: device, 256-byte aligned. */
+mq_status mq_workspace_init(void *ws, size_t ws_bytes, mq_stream stream);
+
+/* ---------------------------------------------------------------- slicing
+ * Eq. 1 (Section 2): S = clamp(round(q / 2^(c-r)), 0, 2^r - 1) * 2^(c-r),
+ * rounding half up (Section 3.1 "Slicing": the next lower bit alone decides),
+ * r == c is the identity.  Elementwise over n codes.
+ *   parent : device, n bytes, c-bit codes (values >= 2^c are masked to c bits)
+ *   S_out  : device, n bytes, c-bit codes on the 2^(c-r) grid; may alias parent
+ * Errors: NULL, BAD_R (r or c out of 1 <= r <= c <= 8), BAD_SHAPE (n < 0).  n == 0 is a no-op. */
+mq_status mq_slice_codes(const uint8_t *parent, int64_t n, int c, int r, uint8_t *S_out,
+                         mq_stream stream);
+
+/* ---------------------------------------------------------------- packing
+ * Section 4 ("offline pre-processing"): reorder and pack sliced codes for the
+ * kernels.  The layout is this library's own (not the paper's three-buffer
+ * split): W is cut into tiles of MQ_ROW_BLOCK rows x one group of 128 columns;
+ * a tile is r consecutive 1 KiB lines, line i holding 16 bytes for each of the
+ * 64 rows, so that one wavefront reads a tile with r fully coalesced 16-byte
+ * loads and every lane owns one row's whole group.  Inside a lane's 4r dwords
+ * each 16-bit half holds bit-fields at fixed positions that are valid fp16
+ * subnormals after a mask (and at most one shift per dword).  Tiles are stored
+ * row-block major, group minor.
+ *
+ *   S        : device, uint8 [N, K], codes on the 2^(8-r) grid as written by
+ *              mq_slice_codes (the low 8-r bits are ignored)
+ *   packed   : device, 16-byte aligned, packed_bytes >= mq_packed_bytes(N,K,r);
+ *              rows N..Npad-1 are written as zero codes
+ * mq_unpack is the exact inverse (writes S = t << (8-r) for the N real rows).
+ * Errors: NULL, BAD_R (r not in {2,3,4,6,8} or c != 8), BAD_SHAPE (N < 1, K < 128),
+ * BAD_GROUP (K % 128), ALIGN, BUF_TOO_SMALL. */
+mq_status mq_pack(const uint8_t *S, int64_t N, int64_t K, int c, int r, void *packed,
+                  size_t packed_bytes, mq_stream stream);
+mq_status mq_unpack(const void *packed, int64_t N, int64_t K, int c, int r, uint8_t *S_out,
+                    mq_stream stream);
+
+/* Re-tile the per-group scale and zero-offset (Section 3.2 item 1: computed at
+ * the master width c and shared by every r) to match the weight tiles:
+ *   scales, zeros     : device, fp16 [N, K/group] row-major
+ *   scales_t, zeros_t : device, fp16 [Npad/64][K/group][64], each of
+ *                       meta_bytes >= mq_meta_bytes(N,K,group); pad rows get 0.
+ * Errors: NULL, BAD_SHAPE, BAD_GROUP, BUF_TOO_SMALL. */
+mq_status mq_pack_meta(const mq_half *scales, const mq_half *zeros, int64_t N, int64_t K,
+                       int group, mq_half *scales_t, mq_half *zeros_t, size_t meta_bytes,
+                       mq_stream stream);
+
+/* ---------------------------------------------------------------- linear
+ * Section 4:  y[m,n] = sum_k x[m,k] * scale[n,k/group] * (S[n,k] - zero[n,k/group])
+ * with S the r-bit slice of Eq. 1 in c-bit units, fp16 inputs, fp32
+ * accumulation, fp16 output (round to nearest even).
+ *   x        : device, fp16 [M, K], 4-byte aligned
+ *   packed_W : device, from mq_pack with the same N, K, r; 16-byte aligned
+ *   scales_t, zeros_t : device, from mq_pack_meta
+ *   y        : device, fp16 [M, N]; fully overwritten
+ *   ws       : device, 256-byte aligned, ws_bytes >= mq_workspace_bytes(M,N,K,r),
+ *              initialised once with mq_workspace_init
+ * 1 <= M <= MQ_MAX_M.  Results do not depend on the launch shape run to run
+ * (partial sums are combined in a fixed order).
+ * Errors: NULL, BAD_R, BAD_SHAPE, BAD_GROUP, ALIGN, BUF_TOO_SMALL, UNSUPPORTED, HIP. */
+mq_status mq_linear(const mq_half *x, int64_t M, const void *packed_W, const mq_half *scales_t,
+                    const mq_half *zeros_t, int64_t N, int64_t K, int r, int group, mq_half *y,
+                    void *ws, size_t ws_bytes, mq_stream stream);
+
+/* ---------------------------------------------------------------- stack
+ * Sections 3.3 / 5.5: a model is the sliced layers stitched together, one r per
+ * layer.  A stack is executed by ONE persistent launch that walks all layers.
+ * Layers are independent: each has its own x and y (the attention / activation
+ * code between Llama linears is outside this library). */
+typedef struct {
+    const void *packed_W;    /* device, mq_pack(N, K, r) */
+    const mq_half *scales_t; /* device, mq_pack_meta */
+    const mq_half *zeros_t;  /* device, mq_pack_meta */
+    const mq_half *x;        /* device, fp16 [M, K] */
+    mq_half *y;              /* device, fp16 [M, N] */
+    int64_t N, K;
+    int32_t r;     /* 2, 3, 4, 6 or 8 */
+    int32_t group; /* 128 */
+} mq_layer;
+
+/* Bytes of plan workspace for a stack of these layers (host arithmetic; 0 on
+ * invalid arguments).  layers: host. */
+size_t mq_stack_workspace_bytes(const mq_layer *layers, int n_layers, int64_t M);
+
+/* Validate the layers, build the device-side schedule inside `plan` (one
+ * host-to-device copy enqueued on `stream`; the host array may be reused as
+ * soon as the call returns) and zero its counters.  Done once per stack, like
+ * packing.  plan: device, 256-byte aligned, plan_bytes >= mq_stack_workspace_bytes. */
+mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *plan,
+                        size_t plan_bytes, mq_stream stream);
+
+/* Run every layer of a planned stack: one launch, asynchronous on `stream`.
+ * `plan` must not be used by two calls that may run concurrently. */
+mq_status mq_linear_stack(void *plan, mq_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MQ_H */

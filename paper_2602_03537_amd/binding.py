@@ -1,1 +1,222 @@
-__all__ = []
+"""Thin ctypes binding of libmq (include/mq.h).  Argument marshalling only:
+PyTorch supplies device memory and streams, every step runs in the library's
+HIP kernels.  There is no fallback: if libmq.so is missing, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+__all__ = [
+    "MqError", "lib", "lib_path", "MQ_ROW_BLOCK", "MQ_GROUP", "MQ_MAX_M", "STATUS",
+    "mq_status_str", "mq_version", "mq_packed_bytes", "mq_meta_bytes", "mq_workspace_bytes",
+    "mq_workspace_init", "mq_slice_codes", "mq_pack", "mq_unpack", "mq_pack_meta", "mq_linear",
+    "mq_stack_workspace_bytes", "mq_stack_plan", "mq_linear_stack", "MqLayer",
+    "new_workspace", "prepare_layer",
+]
+
+MQ_ROW_BLOCK = 64
+MQ_GROUP = 128
+MQ_MAX_M = 256
+STATUS = {
+    0: "MQ_OK", 1: "MQ_ERR_NULL", 2: "MQ_ERR_BAD_R", 3: "MQ_ERR_BAD_SHAPE", 4: "MQ_ERR_BAD_GROUP",
+    5: "MQ_ERR_ALIGN", 6: "MQ_ERR_BUF_TOO_SMALL", 7: "MQ_ERR_HIP", 8: "MQ_ERR_UNSUPPORTED",
+}
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmq.so")
+_lib = None
+
+
+class MqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {STATUS.get(status, status)} ({mq_status_str(status)})")
+
+
+class MqLayer(ctypes.Structure):
+    """mq_layer of include/mq.h."""
+    _fields_ = [
+        ("packed_W", ctypes.c_void_p), ("scales_t", ctypes.c_void_p), ("zeros_t", ctypes.c_void_p),
+        ("x", ctypes.c_void_p), ("y", ctypes.c_void_p),
+        ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("r", ctypes.c_int32), ("group", ctypes.c_int32),
+    ]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded C-ABI library.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2602_03537_amd.build` "
+            "(there is no CPU or PyTorch fallback)")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+    sig = {
+        "mq_status_str": (ctypes.c_char_p, [i32]),
+        "mq_version": (i32, []),
+        "mq_packed_bytes": (sz, [i64, i64, i32]),
+        "mq_meta_bytes": (sz, [i64, i64, i32]),
+        "mq_workspace_bytes": (sz, [i64, i64, i64, i32]),
+        "mq_workspace_init": (i32, [vp, sz, vp]),
+        "mq_slice_codes": (i32, [vp, i64, i32, i32, vp, vp]),
+        "mq_pack": (i32, [vp, i64, i64, i32, i32, vp, sz, vp]),
+        "mq_unpack": (i32, [vp, i64, i64, i32, i32, vp, vp]),
+        "mq_pack_meta": (i32, [vp, vp, i64, i64, i32, vp, vp, sz, vp]),
+        "mq_linear": (i32, [vp, i64, vp, vp, vp, i64, i64, i32, i32, vp, vp, sz, vp]),
+        "mq_stack_workspace_bytes": (sz, [vp, i32, i64]),
+        "mq_stack_plan": (i32, [vp, i32, i64, vp, sz, vp]),
+        "mq_linear_stack": (i32, [vp, vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = L
+    return L
+
+
+def _stream(stream=None):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise MqError(status, where)
+
+
+# ----------------------------------------------------------------- host-only
+def mq_status_str(status: int) -> str:
+    return lib().mq_status_str(int(status)).decode()
+
+
+def mq_version() -> int:
+    return lib().mq_version()
+
+
+def mq_packed_bytes(N: int, K: int, r: int) -> int:
+    return lib().mq_packed_bytes(N, K, r)
+
+
+def mq_meta_bytes(N: int, K: int, group: int = MQ_GROUP) -> int:
+    return lib().mq_meta_bytes(N, K, group)
+
+
+def mq_workspace_bytes(M: int, N: int, K: int, r: int) -> int:
+    return lib().mq_workspace_bytes(M, N, K, r)
+
+
+# ----------------------------------------------------------------- device calls
+def mq_workspace_init(ws, stream=None) -> None:
+    _check(lib().mq_workspace_init(_ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "mq_workspace_init")
+
+
+def new_workspace(M: int, N: int, K: int, r: int, device="cuda"):
+    """Allocate (torch) and initialise a workspace for mq_linear."""
+    import torch
+    nbytes = mq_workspace_bytes(M, N, K, r)
+    if nbytes == 0:
+        raise MqError(3, "mq_workspace_bytes")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    mq_workspace_init(ws)
+    return ws
+
+
+def mq_slice_codes(parent, c: int, r: int, out=None, stream=None):
+    import torch
+    if out is None:
+        out = torch.empty_like(parent)
+    _check(lib().mq_slice_codes(_ptr(parent), parent.numel(), c, r, _ptr(out), _stream(stream)), "mq_slice_codes")
+    return out
+
+
+def mq_pack(S, c: int, r: int, out=None, stream=None):
+    import torch
+    N, K = S.shape
+    if out is None:
+        nbytes = mq_packed_bytes(N, K, r)
+        out = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=S.device)
+    _check(lib().mq_pack(_ptr(S), N, K, c, r, _ptr(out), out.numel(), _stream(stream)), "mq_pack")
+    return out
+
+
+def mq_unpack(packed, N: int, K: int, c: int, r: int, out=None, stream=None):
+    import torch
+    if out is None:
+        out = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
+    _check(lib().mq_unpack(_ptr(packed), N, K, c, r, _ptr(out), _stream(stream)), "mq_unpack")
+    return out
+
+
+def mq_pack_meta(scales, zeros, K: int, group: int = MQ_GROUP, stream=None):
+    import torch
+    N = scales.shape[0]
+    nbytes = mq_meta_bytes(N, K, group)
+    st = torch.empty(max(nbytes // 2, 1), dtype=torch.float16, device=scales.device)
+    zt = torch.empty(max(nbytes // 2, 1), dtype=torch.float16, device=scales.device)
+    _check(lib().mq_pack_meta(_ptr(scales), _ptr(zeros), N, K, group, _ptr(st), _ptr(zt), nbytes, _stream(stream)),
+           "mq_pack_meta")
+    return st, zt
+
+
+def mq_linear(x, packed_W, scales_t, zeros_t, N: int, K: int, r: int, group: int, ws, y=None, stream=None):
+    import torch
+    M = x.shape[0]
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _check(lib().mq_linear(_ptr(x), M, _ptr(packed_W), _ptr(scales_t), _ptr(zeros_t), N, K, r, group, _ptr(y),
+                           _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "mq_linear")
+    return y
+
+
+def _layer_array(layers: Sequence[dict]):
+    arr = (MqLayer * len(layers))()
+    for i, L in enumerate(layers):
+        arr[i] = MqLayer(_ptr(L["packed_W"]), _ptr(L["scales_t"]), _ptr(L["zeros_t"]), _ptr(L["x"]), _ptr(L["y"]),
+                         L["N"], L["K"], L["r"], L.get("group", MQ_GROUP))
+    return arr
+
+
+def mq_stack_workspace_bytes(layers: Sequence[dict], M: int) -> int:
+    arr = _layer_array(layers)
+    return lib().mq_stack_workspace_bytes(ctypes.cast(arr, ctypes.c_void_p), len(layers), M)
+
+
+def mq_stack_plan(layers: Sequence[dict], M: int, device="cuda", stream=None):
+    """layers: dicts with packed_W, scales_t, zeros_t, x, y (tensors), N, K, r.  Returns the plan tensor."""
+    import torch
+    arr = _layer_array(layers)
+    nbytes = lib().mq_stack_workspace_bytes(ctypes.cast(arr, ctypes.c_void_p), len(layers), M)
+    if nbytes == 0:
+        raise MqError(3, "mq_stack_workspace_bytes")
+    plan = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    _check(lib().mq_stack_plan(ctypes.cast(arr, ctypes.c_void_p), len(layers), M, _ptr(plan), nbytes,
+                               _stream(stream)), "mq_stack_plan")
+    return plan
+
+
+def mq_linear_stack(plan, stream=None) -> None:
+    _check(lib().mq_linear_stack(_ptr(plan), _stream(stream)), "mq_linear_stack")
+
+
+# ----------------------------------------------------------------- convenience
+def prepare_layer(parent, scales, zeros, r: int, c: int = 8, group: int = MQ_GROUP) -> dict:
+    """parent/scales/zeros device tensors -> packed layer (slice, pack, meta), all on the GPU."""
+    N, K = parent.shape
+    S = mq_slice_codes(parent, c, r)
+    packed = mq_pack(S, c, r)
+    st, zt = mq_pack_meta(scales, zeros, K, group)
+    return {"packed_W": packed, "scales_t": st, "zeros_t": zt, "N": N, "K": K, "r": r, "group": group}

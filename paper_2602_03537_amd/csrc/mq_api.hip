@@ -1,0 +1,282 @@
+// C ABI of libmq: argument validation (host only, before anything is enqueued),
+// workspace arithmetic and dispatch to the kernel launchers.
+#include <mutex>
+#include <unordered_map>
+#include <vector>
+
+#include "mq_internal.h"
+
+using namespace mq;
+
+namespace {
+
+bool valid_pack_r(int r) { return r == 2 || r == 3 || r == 4 || r == 6 || r == 8; }
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+constexpr int64_t kMaxDim = (int64_t)1 << 24;  // rows / columns of one layer
+
+// shape checks shared by pack / meta / linear
+mq_status check_shape(int64_t N, int64_t K, int group) {
+    if (N < 1 || K < 1 || N > kMaxDim || K > kMaxDim) return MQ_ERR_BAD_SHAPE;
+    if (group != kGroup || K % group) return MQ_ERR_BAD_GROUP;
+    return MQ_OK;
+}
+
+size_t counter_bytes(int64_t row_blocks) { return align_up((size_t)row_blocks * 4, kCounterBytesAlign); }
+size_t partial_bytes(int64_t M) { return (size_t)kMaxWaves * 2 * (size_t)M * 64 * sizeof(float); }
+
+mq_status layer_status(const mq_layer &l, int64_t M) {
+    if (!l.packed_W || !l.scales_t || !l.zeros_t || !l.x || !l.y) return MQ_ERR_NULL;
+    if (!valid_pack_r(l.r)) return MQ_ERR_BAD_R;
+    if (M < 1 || M > MQ_MAX_M) return MQ_ERR_BAD_SHAPE;
+    if (mq_status st = check_shape(l.N, l.K, l.group)) return st;
+    if (!aligned(l.packed_W, 16) || !aligned(l.x, 4) || !aligned(l.scales_t, 2) || !aligned(l.zeros_t, 2) ||
+        !aligned(l.y, 2))
+        return MQ_ERR_ALIGN;
+    return MQ_OK;
+}
+
+LayerDesc make_desc(const mq_layer &l, uint64_t cost_start, int cnt_off) {
+    LayerDesc d{};
+    d.Wp = static_cast<const uint4 *>(l.packed_W);
+    d.st = reinterpret_cast<const _Float16 *>(l.scales_t);
+    d.zt = reinterpret_cast<const _Float16 *>(l.zeros_t);
+    d.x = reinterpret_cast<const _Float16 *>(l.x);
+    d.y = reinterpret_cast<_Float16 *>(l.y);
+    d.N = (int32_t)l.N;
+    d.K = (int32_t)l.K;
+    d.G = (int32_t)(l.K / kGroup);
+    d.RB = (int32_t)(pad_rows(l.N) / kRowBlock);
+    d.r = l.r;
+    d.cost = tile_cost(l.r);
+    d.cnt_off = cnt_off;
+    d.cost_start = cost_start;
+    return d;
+}
+
+// Plan workspace: [header 256 B][LayerDesc table][counters][partial sums]
+struct PlanHeader {
+    uint64_t magic;
+    uint64_t cost_total;
+    int32_t n_layers, M, max_cost, pad_;
+    uint64_t table_off, cnt_off, part_off, total_bytes;
+};
+constexpr uint64_t kPlanMagic = 0x4d51504c414e3031ull;  // "MQPLAN01"
+
+// Host-side copies of the plan headers, keyed by device address, so that running
+// a stack needs no read-back.  mq_stack_plan overwrites the entry of its address.
+std::mutex g_plan_mutex;
+std::unordered_map<void *, PlanHeader> g_plans;
+
+struct PlanLayout {
+    size_t table_off, cnt_off, cnt_bytes, part_off, total;
+};
+PlanLayout plan_layout(int n_layers, int64_t total_row_blocks, int64_t M) {
+    PlanLayout p;
+    p.table_off = 256;
+    p.cnt_off = align_up(p.table_off + (size_t)n_layers * sizeof(LayerDesc), 256);
+    p.cnt_bytes = counter_bytes(total_row_blocks);
+    p.part_off = p.cnt_off + p.cnt_bytes;
+    p.total = p.part_off + partial_bytes(M);
+    return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *mq_status_str(int status) {
+    switch (status) {
+        case MQ_OK: return "ok";
+        case MQ_ERR_NULL: return "null pointer";
+        case MQ_ERR_BAD_R: return "unsupported bit-width";
+        case MQ_ERR_BAD_SHAPE: return "bad shape";
+        case MQ_ERR_BAD_GROUP: return "bad group size";
+        case MQ_ERR_ALIGN: return "misaligned pointer";
+        case MQ_ERR_BUF_TOO_SMALL: return "buffer too small";
+        case MQ_ERR_HIP: return "HIP runtime error";
+        case MQ_ERR_UNSUPPORTED: return "unsupported configuration";
+    }
+    return "unknown status";
+}
+
+int mq_version(void) { return 1; }
+
+size_t mq_packed_bytes(int64_t N, int64_t K, int r) {
+    if (!valid_pack_r(r) || check_shape(N, K, kGroup) != MQ_OK) return 0;
+    return (size_t)pad_rows(N) * (size_t)K * (size_t)r / 8;
+}
+
+size_t mq_meta_bytes(int64_t N, int64_t K, int group) {
+    if (check_shape(N, K, group) != MQ_OK) return 0;
+    return (size_t)pad_rows(N) * (size_t)(K / group) * 2;
+}
+
+size_t mq_workspace_bytes(int64_t M, int64_t N, int64_t K, int r) {
+    if (!valid_pack_r(r) || check_shape(N, K, kGroup) != MQ_OK || M < 1 || M > MQ_MAX_M) return 0;
+    return counter_bytes(pad_rows(N) / kRowBlock) + partial_bytes(M);
+}
+
+mq_status mq_workspace_init(void *ws, size_t ws_bytes, mq_stream stream) {
+    if (!ws) return MQ_ERR_NULL;
+    if (!aligned(ws, 256)) return MQ_ERR_ALIGN;
+    if (ws_bytes < kCounterBytesAlign) return MQ_ERR_BUF_TOO_SMALL;
+    // counters sit at the start; the partial-sum slots need no initial value
+    size_t zero = ws_bytes;
+    const size_t cap = counter_bytes(kMaxDim / kRowBlock);
+    if (zero > cap) zero = cap;
+    return launch_fill_zero(ws, zero / 4 * 4, (hipStream_t)stream) == hipSuccess ? MQ_OK : MQ_ERR_HIP;
+}
+
+mq_status mq_slice_codes(const uint8_t *parent, int64_t n, int c, int r, uint8_t *S_out, mq_stream stream) {
+    if (!parent || !S_out) return MQ_ERR_NULL;
+    if (c < 1 || c > 8 || r < 1 || r > c) return MQ_ERR_BAD_R;
+    if (n < 0) return MQ_ERR_BAD_SHAPE;
+    return launch_slice(parent, n, c, r, S_out, (hipStream_t)stream) == hipSuccess ? MQ_OK : MQ_ERR_HIP;
+}
+
+mq_status mq_pack(const uint8_t *S, int64_t N, int64_t K, int c, int r, void *packed, size_t packed_bytes,
+                  mq_stream stream) {
+    if (!S || !packed) return MQ_ERR_NULL;
+    if (c != kC || !valid_pack_r(r)) return MQ_ERR_BAD_R;
+    if (mq_status st = check_shape(N, K, kGroup)) return st;
+    if (!aligned(packed, 16)) return MQ_ERR_ALIGN;
+    if (packed_bytes < mq_packed_bytes(N, K, r)) return MQ_ERR_BUF_TOO_SMALL;
+    return launch_pack(S, N, K, r, static_cast<uint4 *>(packed), (hipStream_t)stream) == hipSuccess ? MQ_OK
+                                                                                                     : MQ_ERR_HIP;
+}
+
+mq_status mq_unpack(const void *packed, int64_t N, int64_t K, int c, int r, uint8_t *S_out, mq_stream stream) {
+    if (!packed || !S_out) return MQ_ERR_NULL;
+    if (c != kC || !valid_pack_r(r)) return MQ_ERR_BAD_R;
+    if (mq_status st = check_shape(N, K, kGroup)) return st;
+    if (!aligned(packed, 16)) return MQ_ERR_ALIGN;
+    return launch_unpack(static_cast<const uint4 *>(packed), N, K, r, S_out, (hipStream_t)stream) == hipSuccess
+               ? MQ_OK
+               : MQ_ERR_HIP;
+}
+
+mq_status mq_pack_meta(const mq_half *scales, const mq_half *zeros, int64_t N, int64_t K, int group,
+                       mq_half *scales_t, mq_half *zeros_t, size_t meta_bytes, mq_stream stream) {
+    if (!scales || !zeros || !scales_t || !zeros_t) return MQ_ERR_NULL;
+    if (mq_status st = check_shape(N, K, group)) return st;
+    if (!aligned(scales, 2) || !aligned(zeros, 2) || !aligned(scales_t, 2) || !aligned(zeros_t, 2))
+        return MQ_ERR_ALIGN;
+    if (meta_bytes < mq_meta_bytes(N, K, group)) return MQ_ERR_BUF_TOO_SMALL;
+    return launch_pack_meta(reinterpret_cast<const _Float16 *>(scales), reinterpret_cast<const _Float16 *>(zeros), N,
+                            K / group, reinterpret_cast<_Float16 *>(scales_t), reinterpret_cast<_Float16 *>(zeros_t),
+                            (hipStream_t)stream) == hipSuccess
+               ? MQ_OK
+               : MQ_ERR_HIP;
+}
+
+mq_status mq_linear(const mq_half *x, int64_t M, const void *packed_W, const mq_half *scales_t,
+                    const mq_half *zeros_t, int64_t N, int64_t K, int r, int group, mq_half *y, void *ws,
+                    size_t ws_bytes, mq_stream stream) {
+    if (!ws) return MQ_ERR_NULL;
+    mq_layer l{packed_W, scales_t, zeros_t, x, y, N, K, r, group};
+    if (mq_status st = layer_status(l, M)) return st;
+    if (!aligned(ws, 256)) return MQ_ERR_ALIGN;
+    if (ws_bytes < mq_workspace_bytes(M, N, K, r)) return MQ_ERR_BUF_TOO_SMALL;
+    if (!linear_supports_m(M)) return MQ_ERR_UNSUPPORTED;
+
+    StackParams p{};
+    p.table = nullptr;
+    p.n_layers = 1;
+    p.single = make_desc(l, 0, 0);
+    p.cost_total = (uint64_t)p.single.RB * p.single.G * p.single.cost;
+    p.cnt = static_cast<int32_t *>(ws);
+    p.part = reinterpret_cast<float *>(static_cast<char *>(ws) + counter_bytes(p.single.RB));
+    p.M = (int32_t)M;
+    return launch_stack(p, p.single.cost, (hipStream_t)stream) == hipSuccess ? MQ_OK : MQ_ERR_HIP;
+}
+
+size_t mq_stack_workspace_bytes(const mq_layer *layers, int n_layers, int64_t M) {
+    if (!layers || n_layers < 1 || n_layers > (1 << 20) || M < 1 || M > MQ_MAX_M) return 0;
+    int64_t rbs = 0;
+    for (int i = 0; i < n_layers; ++i) {
+        if (check_shape(layers[i].N, layers[i].K, layers[i].group) != MQ_OK) return 0;
+        rbs += pad_rows(layers[i].N) / kRowBlock;
+    }
+    return plan_layout(n_layers, rbs, M).total;
+}
+
+mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *plan, size_t plan_bytes,
+                        mq_stream stream) {
+    if (!layers || !plan) return MQ_ERR_NULL;
+    if (n_layers < 1 || n_layers > (1 << 20)) return MQ_ERR_BAD_SHAPE;
+    for (int i = 0; i < n_layers; ++i)
+        if (mq_status st = layer_status(layers[i], M)) return st;
+    if (!aligned(plan, 256)) return MQ_ERR_ALIGN;
+    const size_t need = mq_stack_workspace_bytes(layers, n_layers, M);
+    if (need == 0) return MQ_ERR_BAD_SHAPE;
+    if (plan_bytes < need) return MQ_ERR_BUF_TOO_SMALL;
+    if (!linear_supports_m(M)) return MQ_ERR_UNSUPPORTED;
+
+    int64_t rbs = 0;
+    uint64_t cost = 0;
+    int max_cost = 0;
+    std::vector<LayerDesc> table((size_t)n_layers);
+    for (int i = 0; i < n_layers; ++i) {
+        table[i] = make_desc(layers[i], cost, (int)rbs);
+        cost += (uint64_t)table[i].RB * table[i].G * table[i].cost;
+        rbs += table[i].RB;
+        if (table[i].cost > max_cost) max_cost = table[i].cost;
+    }
+    const PlanLayout pl = plan_layout(n_layers, rbs, M);
+    PlanHeader h{};
+    h.magic = kPlanMagic;
+    h.cost_total = cost;
+    h.n_layers = n_layers;
+    h.M = (int32_t)M;
+    h.max_cost = max_cost;
+    h.table_off = pl.table_off;
+    h.cnt_off = pl.cnt_off;
+    h.part_off = pl.part_off;
+    h.total_bytes = pl.total;
+
+    hipStream_t s = (hipStream_t)stream;
+    char *base = static_cast<char *>(plan);
+    // set-up call: the copies are waited for, so the host arrays may go away
+    if (hipMemcpyAsync(base, &h, sizeof(h), hipMemcpyHostToDevice, s) != hipSuccess) return MQ_ERR_HIP;
+    if (hipMemcpyAsync(base + pl.table_off, table.data(), table.size() * sizeof(LayerDesc), hipMemcpyHostToDevice,
+                       s) != hipSuccess)
+        return MQ_ERR_HIP;
+    if (launch_fill_zero(base + pl.cnt_off, pl.cnt_bytes, s) != hipSuccess) return MQ_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return MQ_ERR_HIP;
+    {
+        std::lock_guard<std::mutex> lock(g_plan_mutex);
+        g_plans[plan] = h;
+    }
+    return MQ_OK;
+}
+
+mq_status mq_linear_stack(void *plan, mq_stream stream) {
+    if (!plan) return MQ_ERR_NULL;
+    if (!aligned(plan, 256)) return MQ_ERR_ALIGN;
+    PlanHeader h{};
+    bool known = false;
+    {
+        std::lock_guard<std::mutex> lock(g_plan_mutex);
+        auto it = g_plans.find(plan);
+        if (it != g_plans.end()) { h = it->second; known = true; }
+    }
+    if (!known) {  // planned by another process image: read the header back once
+        if (hipMemcpy(&h, plan, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return MQ_ERR_HIP;
+        if (h.magic != kPlanMagic) return MQ_ERR_BAD_SHAPE;
+        std::lock_guard<std::mutex> lock(g_plan_mutex);
+        g_plans[plan] = h;
+    }
+    char *base = static_cast<char *>(plan);
+    StackParams p{};
+    p.table = reinterpret_cast<const LayerDesc *>(base + h.table_off);
+    p.n_layers = h.n_layers;
+    p.cost_total = h.cost_total;
+    p.cnt = reinterpret_cast<int32_t *>(base + h.cnt_off);
+    p.part = reinterpret_cast<float *>(base + h.part_off);
+    p.M = h.M;
+    return launch_stack(p, h.max_cost, (hipStream_t)stream) == hipSuccess ? MQ_OK : MQ_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,210 @@
+// Slice, pack, unpack and meta re-tiling kernels (load-time steps of the path).
+//   slice : Eq. 1 (Section 2), elementwise on bytes
+//   pack  : Section 4's offline reorder, into the tile layout of mq_layout.h
+#include "mq_internal.h"
+#include "mq_static_for.h"
+
+namespace mq {
+
+// ------------------------------------------------------------------ slice
+// Eq. 1 with round-half-up: t = min((q + 2^(c-r-1)) >> (c-r), 2^r - 1); S = t << (c-r).
+__device__ __forceinline__ uint32_t slice_byte(uint32_t q, int cmask, int sh, int half, int tmax) {
+    q &= cmask;
+    uint32_t t = (q + half) >> sh;
+    t = t < (uint32_t)tmax ? t : (uint32_t)tmax;
+    return t << sh;
+}
+
+__global__ __launch_bounds__(256) void slice_kernel(const uint8_t *__restrict__ in, uint8_t *__restrict__ out,
+                                                    int64_t n, int cmask, int sh, int half, int tmax, int vec) {
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int64_t nvec = vec ? n / 16 : 0;
+    for (int64_t i = tid; i < nvec; i += stride) {
+        uint4 v = reinterpret_cast<const uint4 *>(in)[i];
+        uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t o = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) o |= slice_byte((w[j] >> (8 * b)) & 0xFF, cmask, sh, half, tmax) << (8 * b);
+            w[j] = o;
+        }
+        reinterpret_cast<uint4 *>(out)[i] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    for (int64_t i = nvec * 16 + tid; i < n; i += stride) out[i] = (uint8_t)slice_byte(in[i], cmask, sh, half, tmax);
+}
+
+hipError_t launch_slice(const uint8_t *parent, int64_t n, int c, int r, uint8_t *out, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    const int sh = c - r;
+    const int half = sh ? (1 << (sh - 1)) : 0;
+    const int vec = ((reinterpret_cast<uintptr_t>(parent) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
+    int64_t work = vec ? (n + 15) / 16 : n;
+    int64_t blocks = (work + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    hipLaunchKernelGGL(slice_kernel, dim3((unsigned)blocks), dim3(256), 0, s, parent, out, n, (1 << c) - 1, sh, half,
+                       (1 << r) - 1, vec);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ pack
+// One thread per (row block, group, lane): reads its row's 128 codes, emits 4R dwords.
+template <int R>
+__global__ __launch_bounds__(256) void pack_kernel(const uint8_t *__restrict__ S, uint4 *__restrict__ packed, int N,
+                                                   int64_t K, int G, int64_t ntiles) {
+    using T = Layout<R>;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int64_t tile = tid >> 6;
+    if (tile >= ntiles) return;
+    const int64_t rb = tile / G;
+    const int g = (int)(tile - rb * G);
+    const int64_t n = rb * kRowBlock + lane;
+
+    uint8_t code[kGroup];
+    if (n < N) {
+        const uint8_t *src = S + n * K + (int64_t)g * kGroup;
+#pragma unroll
+        for (int i = 0; i < kGroup; ++i) code[i] = src[i] >> (kC - R);
+    } else {
+#pragma unroll
+        for (int i = 0; i < kGroup; ++i) code[i] = 0;
+    }
+
+    uint32_t dw[4 * R];
+#pragma unroll
+    for (int i = 0; i < 4 * R; ++i) dw[i] = 0;
+    constexpr int NU = 4 * R / T::UD;
+    static_for<NU>([&](auto un) {
+        static_for<T::NOPS>([&](auto oi) {
+            constexpr Op o = T::op(oi);
+            constexpr int p = ctz16(o.mask);
+            constexpr uint32_t fm = (uint32_t)(o.mask >> p);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t t = code[2 * (un * T::PPU + o.pair) + h];
+                dw[un * T::UD + o.dw] |= ((t >> o.d) & fm) << (p + o.sh + 16 * h);
+            }
+        });
+    });
+    uint4 *dst = packed + tile * (R * 64) + lane;
+#pragma unroll
+    for (int i = 0; i < R; ++i) dst[i * 64] = make_uint4(dw[4 * i], dw[4 * i + 1], dw[4 * i + 2], dw[4 * i + 3]);
+}
+
+template <int R>
+__global__ __launch_bounds__(256) void unpack_kernel(const uint4 *__restrict__ packed, uint8_t *__restrict__ S, int N,
+                                                     int64_t K, int G, int64_t ntiles) {
+    using T = Layout<R>;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int64_t tile = tid >> 6;
+    if (tile >= ntiles) return;
+    const int64_t rb = tile / G;
+    const int g = (int)(tile - rb * G);
+    const int64_t n = rb * kRowBlock + lane;
+    if (n >= N) return;
+
+    uint32_t dw[4 * R];
+    const uint4 *src = packed + tile * (R * 64) + lane;
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+        const uint4 v = src[i * 64];
+        dw[4 * i] = v.x; dw[4 * i + 1] = v.y; dw[4 * i + 2] = v.z; dw[4 * i + 3] = v.w;
+    }
+    uint8_t code[kGroup];
+#pragma unroll
+    for (int i = 0; i < kGroup; ++i) code[i] = 0;
+    constexpr int NU = 4 * R / T::UD;
+    static_for<NU>([&](auto un) {
+        static_for<T::NOPS>([&](auto oi) {
+            constexpr Op o = T::op(oi);
+            constexpr int p = ctz16(o.mask);
+            constexpr uint32_t fm = (uint32_t)(o.mask >> p);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t f = (dw[un * T::UD + o.dw] >> (p + o.sh + 16 * h)) & fm;
+                code[2 * (un * T::PPU + o.pair) + h] |= (uint8_t)(f << o.d);
+            }
+        });
+    });
+    uint8_t *dst = S + n * K + (int64_t)g * kGroup;
+#pragma unroll
+    for (int i = 0; i < kGroup; ++i) dst[i] = (uint8_t)(code[i] << (kC - R));
+}
+
+template <int R>
+static hipError_t launch_pack_r(const uint8_t *S, int64_t N, int64_t K, uint4 *packed, hipStream_t s) {
+    const int G = (int)(K / kGroup);
+    const int64_t ntiles = pad_rows(N) / kRowBlock * G;
+    const int64_t blocks = (ntiles * 64 + 255) / 256;
+    hipLaunchKernelGGL(pack_kernel<R>, dim3((unsigned)blocks), dim3(256), 0, s, S, packed, (int)N, K, G, ntiles);
+    return hipGetLastError();
+}
+template <int R>
+static hipError_t launch_unpack_r(const uint4 *packed, int64_t N, int64_t K, uint8_t *S, hipStream_t s) {
+    const int G = (int)(K / kGroup);
+    const int64_t ntiles = pad_rows(N) / kRowBlock * G;
+    const int64_t blocks = (ntiles * 64 + 255) / 256;
+    hipLaunchKernelGGL(unpack_kernel<R>, dim3((unsigned)blocks), dim3(256), 0, s, packed, S, (int)N, K, G, ntiles);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack(const uint8_t *S, int64_t N, int64_t K, int r, uint4 *packed, hipStream_t s) {
+    switch (r) {
+        case 2: return launch_pack_r<2>(S, N, K, packed, s);
+        case 3: return launch_pack_r<3>(S, N, K, packed, s);
+        case 4: return launch_pack_r<4>(S, N, K, packed, s);
+        case 6: return launch_pack_r<6>(S, N, K, packed, s);
+        case 8: return launch_pack_r<8>(S, N, K, packed, s);
+    }
+    return hipErrorInvalidValue;
+}
+hipError_t launch_unpack(const uint4 *packed, int64_t N, int64_t K, int r, uint8_t *S, hipStream_t s) {
+    switch (r) {
+        case 2: return launch_unpack_r<2>(packed, N, K, S, s);
+        case 3: return launch_unpack_r<3>(packed, N, K, S, s);
+        case 4: return launch_unpack_r<4>(packed, N, K, S, s);
+        case 6: return launch_unpack_r<6>(packed, N, K, S, s);
+        case 8: return launch_unpack_r<8>(packed, N, K, S, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------------------------ meta
+// [N, G] -> [RB][G][64]; pad rows get scale 0 / zero 0.
+__global__ __launch_bounds__(256) void pack_meta_kernel(const _Float16 *__restrict__ sc, const _Float16 *__restrict__ zr,
+                                                        _Float16 *__restrict__ st, _Float16 *__restrict__ zt, int64_t N,
+                                                        int64_t G, int64_t total) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int lane = (int)(i & 63);
+    const int64_t tile = i >> 6;
+    const int64_t rb = tile / G;
+    const int64_t g = tile - rb * G;
+    const int64_t n = rb * kRowBlock + lane;
+    st[i] = n < N ? sc[n * G + g] : (_Float16)0.f;
+    zt[i] = n < N ? zr[n * G + g] : (_Float16)0.f;
+}
+
+hipError_t launch_pack_meta(const _Float16 *sc, const _Float16 *zr, int64_t N, int64_t G, _Float16 *st, _Float16 *zt,
+                            hipStream_t s) {
+    const int64_t total = pad_rows(N) * G;
+    hipLaunchKernelGGL(pack_meta_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, sc, zr, st, zt, N, G,
+                       total);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t *p, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s) {
+    const size_t n = bytes / 4;
+    if (!n) return hipSuccess;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (uint32_t *)p, n);
+    return hipGetLastError();
+}
+
+}  // namespace mq
