@@ -80,7 +80,8 @@ mq_status mq_workspace_init(void *ws, size_t ws_bytes, mq_stream stream);
  * r == c is the identity.  Elementwise over n codes.
  *   parent : device, n bytes, c-bit codes (values >= 2^c are masked to c bits)
  *   S_out  : device, n bytes, c-bit codes on the 2^(c-r) grid; may alias parent
- * Errors: NULL, BAD_R (r or c out of 1 <= r <= c <= 8), BAD_SHAPE (n < 0).  n == 0 is a no-op. */
+ * Errors: BAD_R (r or c out of 1 <= r <= c <= 8), BAD_SHAPE (n < 0), NULL.
+ * n == 0 is a no-op that returns MQ_OK even for NULL pointers. */
 mq_status mq_slice_codes(const uint8_t *parent, int64_t n, int c, int r, uint8_t *S_out,
                          mq_stream stream);
 

@@ -130,9 +130,10 @@ mq_status mq_workspace_init(void *ws, size_t ws_bytes, mq_stream stream) {
 }
 
 mq_status mq_slice_codes(const uint8_t *parent, int64_t n, int c, int r, uint8_t *S_out, mq_stream stream) {
-    if (!parent || !S_out) return MQ_ERR_NULL;
     if (c < 1 || c > 8 || r < 1 || r > c) return MQ_ERR_BAD_R;
     if (n < 0) return MQ_ERR_BAD_SHAPE;
+    if (n == 0) return MQ_OK;  // nothing to do; pointers of an empty array may be NULL
+    if (!parent || !S_out) return MQ_ERR_NULL;
     return launch_slice(parent, n, c, r, S_out, (hipStream_t)stream) == hipSuccess ? MQ_OK : MQ_ERR_HIP;
 }
 

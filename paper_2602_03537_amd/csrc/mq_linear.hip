@@ -90,23 +90,42 @@ __device__ __forceinline__ void flush_rows(const LayerDesc &L, const StackParams
         return;
     }
     const int slot = ga == 0 ? 1 : 0;  // the wave holding a row block's first tile uses slot 1
+    // Partial sums travel through agent-scope atomic stores/loads (write-through, cache
+    // bypassing), so no whole-L2 write-back or invalidate is needed to publish them.
     float *mine = p.part + ((size_t)(wave * 2 + slot) * M) * 64 + lane;
 #pragma unroll
-    for (int m = 0; m < M; ++m) mine[m * 64] = yacc[m];
-    __threadfence();  // release the partial sums to the device
+    for (int m = 0; m < M; ++m) __hip_atomic_store(mine + m * 64, yacc[m], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // the write-through stores must have been acknowledged before the counter moves
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     int old = 0;
     int32_t *cnt = p.cnt + L.cnt_off + rb;
     if (lane == 0) old = __hip_atomic_fetch_add(cnt, gb - ga, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     old = __builtin_amdgcn_readfirstlane(old);
     if (old + (gb - ga) != L.G) return;
-    __threadfence();  // acquire everybody else's partial sums
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     const uint64_t a = L.cost_start + (uint64_t)rb * L.G * L.cost;
     const int w_lo = wave_of(a, p.nwaves, p.cost_total);
     const int w_hi = wave_of(a + (uint64_t)(L.G - 1) * L.cost, p.nwaves, p.cost_total);
+    // Fixed summation order (w_lo's slot 1, then slot 0 of w_lo+1 .. w_hi); loads are issued
+    // in batches so that their round trips overlap.
+    constexpr int kBatch = 16;
 #pragma unroll
     for (int m = 0; m < M; ++m) {
-        float tot = p.part[((size_t)(w_lo * 2 + 1) * M + m) * 64 + lane];
-        for (int w = w_lo + 1; w <= w_hi; ++w) tot += p.part[((size_t)(w * 2) * M + m) * 64 + lane];
+        float tot = __hip_atomic_load(p.part + ((size_t)(w_lo * 2 + 1) * M + m) * 64 + lane, __ATOMIC_RELAXED,
+                                      __HIP_MEMORY_SCOPE_AGENT);
+        for (int w0 = w_lo + 1; w0 <= w_hi; w0 += kBatch) {
+            float v[kBatch];
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const int w = w0 + j <= w_hi ? w0 + j : w_hi;
+                v[j] = __hip_atomic_load(p.part + ((size_t)(w * 2) * M + m) * 64 + lane, __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+            }
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j)
+                if (w0 + j <= w_hi) tot += v[j];
+        }
         if (row < L.N) L.y[(size_t)m * L.N + row] = (_Float16)tot;
     }
     if (lane == 0) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -1,0 +1,342 @@
+"""GPU parity tests: every call goes through the C-ABI library (ctypes binding)
+and is compared with the CPU oracle on the same seeded inputs.
+
+Bars: integer work (slice, pack, unpack) bit-exact; y within max-abs 2e-2 and
+relative-L2 1e-3 of the float64 oracle (fp16 activations, fp32 accumulation,
+fp16 output)."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2602_03537_amd as mq
+from paper_2602_03537_amd import synth
+from layout_ref import pack_ref, meta_ref
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+WIDTHS = (2, 3, 4, 6, 8)
+C = 8
+MAX_ABS = 2e-2
+REL_L2 = 1e-3
+DEV = "cuda"
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def check_y(y_gpu, y_ref, what=""):
+    yg = y_gpu.detach().cpu().numpy().astype(np.float64)
+    assert yg.shape == y_ref.shape, what
+    assert np.all(np.isfinite(yg)), what
+    err = np.abs(yg - y_ref).max()
+    rel = np.linalg.norm(yg - y_ref) / max(np.linalg.norm(y_ref), 1e-30)
+    assert err <= MAX_ABS, f"{what}: max-abs {err}"
+    assert rel <= REL_L2, f"{what}: rel-L2 {rel}"
+
+
+def run_linear(L, r, M=None):
+    """host layer dict -> y (device tensor) through slice, pack, meta, linear."""
+    N, K = L["parent"].shape
+    lay = mq.prepare_layer(dev(L["parent"]), dev(L["scales"]), dev(L["zeros"]), r)
+    x = dev(L["x"] if M is None else L["x"][:M])
+    ws = mq.new_workspace(x.shape[0], N, K, r)
+    y = mq.mq_linear(x, lay["packed_W"], lay["scales_t"], lay["zeros_t"], N, K, r, 128, ws)
+    torch.cuda.synchronize()
+    return y
+
+
+# ------------------------------------------------------------------ slice
+def test_slice_every_code_every_width_bit_exact():
+    q = np.arange(256, dtype=np.uint8)
+    for c in (8, 6, 4, 1):
+        qc = (q & ((1 << c) - 1)).astype(np.uint8)
+        for r in range(1, c + 1):
+            got = mq.mq_slice_codes(dev(qc), c, r).cpu().numpy()
+            assert np.array_equal(got, oracle.slice_codes(qc, c, r)), (c, r)
+
+
+@pytest.mark.parametrize("n", [0, 1, 15, 16, 17, 4097, 1_000_003])
+def test_slice_ragged_lengths_and_unaligned_views(n):
+    rng = np.random.default_rng(n)
+    q = rng.integers(0, 256, n + 3, dtype=np.uint8)
+    buf = dev(q)
+    for off in (0, 1):                      # off=1: pointer not 16-byte aligned
+        src = buf[off:off + n]
+        out = torch.full((n + 2,), 0xAB, dtype=torch.uint8, device=DEV)
+        mq.mq_slice_codes(src, C, 3, out=out[1:1 + n])
+        torch.cuda.synchronize()
+        o = out.cpu().numpy()
+        assert o[0] == 0xAB and o[-1] == 0xAB                      # guard bytes untouched
+        assert np.array_equal(o[1:1 + n], oracle.slice_codes(q[off:off + n], C, 3))
+
+
+def test_slice_in_place():
+    q = np.random.default_rng(1).integers(0, 256, 5000, dtype=np.uint8)
+    t = dev(q)
+    mq.mq_slice_codes(t, C, 4, out=t)
+    assert np.array_equal(t.cpu().numpy(), oracle.slice_codes(q, C, 4))
+
+
+# ------------------------------------------------------------------ pack
+def _patterns(N, K, r, rng):
+    step = 1 << (8 - r)
+    top = ((1 << r) - 1) * step
+    yield "random", (rng.integers(0, 1 << r, (N, K)) * step).astype(np.uint8)
+    yield "zeros", np.zeros((N, K), np.uint8)
+    yield "max", np.full((N, K), top, np.uint8)
+    alt = np.zeros((N, K), np.uint8)
+    alt[:, ::2] = top
+    yield "alternating", alt
+    ramp = ((np.arange(N)[:, None] * 7 + np.arange(K)[None, :]) % (1 << r) * step).astype(np.uint8)
+    yield "ramp", ramp
+
+
+@pytest.mark.parametrize("r", WIDTHS)
+@pytest.mark.parametrize("shape", [(64, 128), (130, 384), (1, 128), (200, 1280)])
+def test_pack_matches_documented_layout_and_round_trips(r, shape):
+    N, K = shape
+    rng = np.random.default_rng([r, N, K])
+    for name, S in _patterns(N, K, r, rng):
+        packed = mq.mq_pack(dev(S), C, r)
+        ref = pack_ref(S, r)
+        assert packed.numel() == mq.mq_packed_bytes(N, K, r) == ref.size
+        assert np.array_equal(packed.cpu().numpy(), ref), (name, r, shape)
+        back = mq.mq_unpack(packed, N, K, C, r)
+        assert np.array_equal(back.cpu().numpy(), S), (name, r, shape)
+
+
+@pytest.mark.parametrize("r", (2, 3, 6))
+def test_pack_one_hot_positions(r):
+    # a single non-zero code moves to exactly one place; every position of a group is visited
+    N, K = 64, 256
+    top = ((1 << r) - 1) << (8 - r)
+    for k in list(range(0, 128, 7)) + [127, 128, 255]:
+        S = np.zeros((N, K), np.uint8)
+        S[k % N, k] = top
+        packed = mq.mq_pack(dev(S), C, r)
+        assert np.array_equal(packed.cpu().numpy(), pack_ref(S, r)), k
+        assert np.array_equal(mq.mq_unpack(packed, N, K, C, r).cpu().numpy(), S), k
+
+
+def test_pack_ignores_low_bits_of_off_grid_codes():
+    rng = np.random.default_rng(5)
+    q = rng.integers(0, 256, (64, 128), dtype=np.uint8)
+    for r in WIDTHS:
+        a = mq.mq_pack(dev(q), C, r).cpu().numpy()
+        b = mq.mq_pack(dev((q >> (8 - r) << (8 - r)).astype(np.uint8)), C, r).cpu().numpy()
+        assert np.array_equal(a, b)
+
+
+def test_pack_meta_tiling():
+    rng = np.random.default_rng(2)
+    for N, K in [(64, 128), (200, 1280), (1, 256)]:
+        s = rng.uniform(1e-4, 1e-2, (N, K // 128)).astype(np.float16)
+        z = rng.integers(0, 256, (N, K // 128)).astype(np.float16)
+        st, zt = mq.mq_pack_meta(dev(s), dev(z), K)
+        assert np.array_equal(st.cpu().numpy(), meta_ref(s))
+        assert np.array_equal(zt.cpu().numpy(), meta_ref(z))
+
+
+def test_slice_then_pack_of_parent_equals_pack_of_oracle_slice():
+    L = synth.make_layer(192, 512, seed=[0, 9])
+    for r in WIDTHS:
+        S = mq.mq_slice_codes(dev(L["parent"]), C, r)
+        assert np.array_equal(mq.mq_pack(S, C, r).cpu().numpy(), pack_ref(oracle.slice_codes(L["parent"], C, r), r))
+
+
+# ------------------------------------------------------------------ linear
+def test_linear_config_512x512_r4_seed0():
+    # smallest configuration: K=512, N=512, M=1, group 128, r=4, seed 0
+    L = synth.make_layer(512, 512, M=1, seed=0)
+    y = run_linear(L, 4)
+    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, 4, 128), "config 512x512")
+
+
+@pytest.mark.parametrize("r", WIDTHS)
+@pytest.mark.parametrize("shape", [(64, 128), (1, 128), (63, 256), (130, 384), (200, 1280), (448, 2048)])
+def test_linear_matches_oracle_multi_tile_and_ragged(r, shape):
+    N, K = shape
+    L = synth.make_layer(N, K, M=1, seed=[1, N, K])
+    y = run_linear(L, r)
+    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"{shape} r={r}")
+
+
+@pytest.mark.parametrize("r", WIDTHS)
+@pytest.mark.parametrize("M", [2, 3, 4])
+def test_linear_small_batches(r, M):
+    L = synth.make_layer(200, 768, M=M, seed=[2, M])
+    y = run_linear(L, r)
+    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"M={M} r={r}")
+
+
+@pytest.mark.parametrize("r", WIDTHS)
+def test_linear_uniform_random_codes_and_fractional_zeros(r):
+    # not a quantiser's output: every code value, non-integer zero-offsets
+    L = synth.make_random_codes_layer(192, 640, M=2, seed=[3, r])
+    y = run_linear(L, r)
+    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"random codes r={r}")
+
+
+def test_linear_symmetric_zero_offsets():
+    # Section 5's setup is symmetric quantisation: zero = 2^(c-1) everywhere
+    L = synth.make_layer(128, 512, M=1, seed=[4])
+    L["zeros"] = np.full_like(L["zeros"], 128.0)
+    for r in WIDTHS:
+        check_y(run_linear(L, r), oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"sym r={r}")
+
+
+def test_linear_degenerate_inputs():
+    L = synth.make_layer(128, 256, M=1, seed=[5])
+    zero_x = dict(L, x=np.zeros_like(L["x"]))
+    assert torch.count_nonzero(run_linear(zero_x, 3)) == 0
+    # extreme codes only (0 and 255): clamp region of Eq. 1 at every width
+    ext = dict(L, parent=np.where(L["parent"] > 127, 255, 0).astype(np.uint8))
+    for r in WIDTHS:
+        check_y(run_linear(ext, r), oracle.linear(ext["x"], ext["parent"], ext["scales"], ext["zeros"], C, r, 128),
+                f"extreme r={r}")
+    # large activations (outliers) keep the fp16-subnormal arithmetic exact
+    big = dict(L, x=(L["x"].astype(np.float32) * 64).astype(np.float16), scales=(L["scales"] / 64).astype(np.float16))
+    check_y(run_linear(big, 2), oracle.linear(big["x"], big["parent"], big["scales"], big["zeros"], C, 2, 128), "big x")
+
+
+def test_linear_r8_equals_plain_8bit_layer_and_low_widths_differ():
+    L = synth.make_layer(128, 512, M=1, seed=[6])
+    y8 = run_linear(L, 8).cpu().numpy().astype(np.float64)
+    w = np.repeat(L["scales"].astype(np.float64), 128, 1) * (L["parent"].astype(np.float64)
+                                                              - np.repeat(L["zeros"].astype(np.float64), 128, 1))
+    ref8 = L["x"].astype(np.float64) @ w.T
+    assert np.abs(y8 - ref8).max() <= MAX_ABS
+    y2 = run_linear(L, 2).cpu().numpy().astype(np.float64)
+    assert np.abs(y2 - ref8).max() > 10 * MAX_ABS          # the 2-bit slice is a different model
+
+
+def test_linear_is_deterministic_and_leaves_guard_bands_alone():
+    N, K, r = 200, 1280, 3
+    L = synth.make_layer(N, K, M=2, seed=[7])
+    lay = mq.prepare_layer(dev(L["parent"]), dev(L["scales"]), dev(L["zeros"]), r)
+    x = dev(L["x"])
+    ws = mq.new_workspace(2, N, K, r)
+    buf = torch.full((2 * N + 128,), float("nan"), dtype=torch.float16, device=DEV)
+    y = buf[64:64 + 2 * N].view(2, N)
+    outs = []
+    for _ in range(3):
+        y.fill_(float("nan"))
+        mq.mq_linear(x, lay["packed_W"], lay["scales_t"], lay["zeros_t"], N, K, r, 128, ws, y=y)
+        torch.cuda.synchronize()
+        outs.append(y.clone())
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    assert torch.isnan(buf[:64]).all() and torch.isnan(buf[64 + 2 * N:]).all()
+    check_y(outs[0], oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), "guard")
+
+
+def test_linear_workspace_is_reusable_across_shapes():
+    # counters are left at zero by every call, so one workspace serves many layers
+    ws = mq.new_workspace(1, 4096, 4096, 8)
+    for (N, K, r) in [(4096, 512, 4), (200, 1280, 2), (512, 512, 6), (4096, 512, 3)]:
+        L = synth.make_layer(N, K, M=1, seed=[8, N, K, r])
+        lay = mq.prepare_layer(dev(L["parent"]), dev(L["scales"]), dev(L["zeros"]), r)
+        y = mq.mq_linear(dev(L["x"]), lay["packed_W"], lay["scales_t"], lay["zeros_t"], N, K, r, 128, ws)
+        check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"reuse {N}x{K} r={r}")
+
+
+def test_linear_rejects_unsupported_batch_loudly():
+    L = synth.make_layer(64, 128, M=1, seed=[9])
+    lay = mq.prepare_layer(dev(L["parent"]), dev(L["scales"]), dev(L["zeros"]), 4)
+    x = torch.zeros((300, 128), dtype=torch.float16, device=DEV)
+    ws = mq.new_workspace(1, 64, 128, 4)
+    with pytest.raises(mq.MqError):
+        mq.mq_linear(x, lay["packed_W"], lay["scales_t"], lay["zeros_t"], 64, 128, 4, 128, ws)
+
+
+# ------------------------------------------------ full-size layers, sampled rows
+LLAMA7B = [(4096, 4096), (11008, 4096), (4096, 11008)]
+
+
+@pytest.mark.parametrize("shape", LLAMA7B)
+def test_linear_llama2_7b_shapes_sampled_rows(shape):
+    N, K = shape
+    L = synth.make_layer(N, K, M=1, seed=[0, N, K])
+    rng = np.random.default_rng([11, N])
+    rows = np.unique(np.concatenate([[0, 63, 64, N - 1], rng.integers(0, N, 252)]))
+    p, s, z, x = dev(L["parent"]), dev(L["scales"]), dev(L["zeros"]), dev(L["x"])
+    for r in WIDTHS:
+        lay = mq.prepare_layer(p, s, z, r)
+        ws = mq.new_workspace(1, N, K, r)
+        y = mq.mq_linear(x, lay["packed_W"], lay["scales_t"], lay["zeros_t"], N, K, r, 128, ws)
+        ref = oracle.linear_rows(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128, rows)
+        check_y(y[:, torch.from_numpy(rows).to(DEV)], ref, f"{shape} r={r}")
+        # the sliced codes of the whole matrix, bit-exact
+        S = mq.mq_unpack(lay["packed_W"], N, K, C, r).cpu().numpy()
+        assert np.array_equal(S, oracle.slice_codes(L["parent"], C, r))
+        assert torch.isfinite(y).all()
+
+
+# ------------------------------------------------------------------ stack
+def _stack(shapes_r, M=1, seed=0):
+    host, layers = [], []
+    for i, (N, K, r) in enumerate(shapes_r):
+        L = synth.make_layer(N, K, M=M, seed=[seed, i, N, K])
+        lay = mq.prepare_layer(dev(L["parent"]), dev(L["scales"]), dev(L["zeros"]), r)
+        lay.update(x=dev(L["x"]), y=torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV))
+        host.append(dict(L, r=r))
+        layers.append(lay)
+    return host, layers
+
+
+@pytest.mark.parametrize("M", [1, 2])
+def test_stack_mixed_widths_matches_oracle(M):
+    shapes_r = [(256, 512, 2), (64, 128, 8), (200, 1280, 3), (512, 256, 6), (130, 384, 4), (1024, 1024, 3),
+                (63, 128, 2), (320, 640, 8)]
+    host, layers = _stack(shapes_r, M=M, seed=21)
+    plan = mq.mq_stack_plan(layers, M)
+    for rep in range(2):                               # the plan is reusable (counters self-reset)
+        for lay in layers:
+            lay["y"].fill_(float("nan"))
+        mq.mq_linear_stack(plan)
+        torch.cuda.synchronize()
+        refs = oracle.linear_stack(host, C, 128)
+        for i, (lay, ref) in enumerate(zip(layers, refs)):
+            check_y(lay["y"], ref, f"stack layer {i} rep {rep}")
+
+
+def test_stack_equals_layer_by_layer_calls_bit_for_bit_when_unsplit():
+    # one tile per layer: no split-K anywhere, so stack and single calls do identical arithmetic
+    shapes_r = [(64, 128, r) for r in WIDTHS]
+    host, layers = _stack(shapes_r, seed=22)
+    plan = mq.mq_stack_plan(layers, 1)
+    mq.mq_linear_stack(plan)
+    torch.cuda.synchronize()
+    for lay in layers:
+        ws = mq.new_workspace(1, lay["N"], lay["K"], lay["r"])
+        y = mq.mq_linear(lay["x"], lay["packed_W"], lay["scales_t"], lay["zeros_t"], lay["N"], lay["K"], lay["r"],
+                         128, ws)
+        assert torch.equal(y, lay["y"])
+
+
+def test_stack_llama2_7b_block_mixed_widths_sampled_rows():
+    # two decoder blocks (14 linears) at the real shapes, widths drawn by seed
+    shapes = [(N, K) for _ in range(2) for (_, N, K) in synth.LLAMA2_7B_BLOCK]
+    widths, _ = synth.draw_bitwidths([N * K for N, K in shapes], 3.5, seed=3, tol=0.5)
+    base = {}
+    host, layers = [], []
+    for i, ((N, K), r) in enumerate(zip(shapes, widths)):
+        if (N, K) not in base:
+            base[(N, K)] = synth.make_layer(N, K, M=1, seed=[31, N, K])
+        L = dict(base[(N, K)])
+        L["x"] = synth.make_x(1, K, [32, i])
+        lay = mq.prepare_layer(dev(L["parent"]), dev(L["scales"]), dev(L["zeros"]), int(r))
+        lay.update(x=dev(L["x"]), y=torch.full((1, N), float("nan"), dtype=torch.float16, device=DEV))
+        host.append(dict(L, r=int(r)))
+        layers.append(lay)
+    plan = mq.mq_stack_plan(layers, 1)
+    mq.mq_linear_stack(plan)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(33)
+    for i, (L, lay) in enumerate(zip(host, layers)):
+        N = lay["N"]
+        rows = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, 62)]))
+        ref = oracle.linear_rows(L["x"], L["parent"], L["scales"], L["zeros"], C, L["r"], 128, rows)
+        check_y(lay["y"][:, torch.from_numpy(rows).to(DEV)], ref, f"block linear {i} r={L['r']}")
+        assert torch.isfinite(lay["y"]).all()

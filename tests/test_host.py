@@ -1,0 +1,226 @@
+"""CPU-only checks: the C-ABI library loads and exports everything include/mq.h
+declares, host-side size arithmetic, every argument-validation path (which
+returns before anything is enqueued, so no GPU is touched), the synthetic input
+recipe, and the reference layout used by the GPU pack test."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2602_03537_amd as mq
+from paper_2602_03537_amd import synth
+from layout_ref import FIELDS, pack_ref, meta_ref
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mq.h")
+FAKE = 0x10000  # a non-null, 256-byte aligned "device pointer" that is never dereferenced
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mq_[a-z_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    L = mq.lib()
+    names = declared_symbols()
+    assert {"mq_pack", "mq_slice_codes", "mq_linear", "mq_linear_stack", "mq_unpack", "mq_pack_meta",
+            "mq_stack_plan", "mq_workspace_init"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+    assert mq.mq_version() >= 1
+
+
+def test_binding_exposes_the_same_names():
+    for n in declared_symbols():
+        assert hasattr(mq, n), n
+
+
+def test_status_strings():
+    for code, name in mq.STATUS.items():
+        assert mq.mq_status_str(code) not in ("", "unknown status"), name
+    assert mq.mq_status_str(99) == "unknown status"
+
+
+@pytest.mark.parametrize("r", [2, 3, 4, 6, 8])
+def test_packed_bytes_is_exactly_r_bits_per_weight(r):
+    assert mq.mq_packed_bytes(4096, 4096, r) == 4096 * 4096 * r // 8
+    assert mq.mq_packed_bytes(11008, 4096, r) == 11008 * 4096 * r // 8
+    assert mq.mq_packed_bytes(100, 256, r) == 128 * 256 * r // 8       # rows pad to 64
+    assert mq.mq_packed_bytes(1, 128, r) == 64 * 128 * r // 8
+
+
+def test_size_queries_reject_bad_arguments():
+    assert mq.mq_packed_bytes(64, 128, 5) == 0
+    assert mq.mq_packed_bytes(64, 100, 4) == 0
+    assert mq.mq_packed_bytes(0, 128, 4) == 0
+    assert mq.mq_meta_bytes(64, 256, 64) == 0
+    assert mq.mq_meta_bytes(100, 256, 128) == 128 * 2 * 2
+    assert mq.mq_workspace_bytes(0, 64, 128, 4) == 0
+    assert mq.mq_workspace_bytes(257, 64, 128, 4) == 0
+    assert mq.mq_workspace_bytes(1, 4096, 4096, 4) > 0
+    assert mq.mq_workspace_bytes(2, 4096, 4096, 4) > mq.mq_workspace_bytes(1, 4096, 4096, 4)
+
+
+def _st(name):
+    return {v: k for k, v in mq.STATUS.items()}[name]
+
+
+def test_slice_validation():
+    L = mq.lib()
+    assert L.mq_slice_codes(None, 16, 8, 4, FAKE, None) == _st("MQ_ERR_NULL")
+    assert L.mq_slice_codes(FAKE, 16, 8, 4, None, None) == _st("MQ_ERR_NULL")
+    assert L.mq_slice_codes(None, 0, 8, 4, None, None) == _st("MQ_OK")        # empty input: no-op
+    for c, r in [(8, 0), (8, 9), (9, 4), (4, 5), (0, 0)]:
+        assert L.mq_slice_codes(FAKE, 16, c, r, FAKE, None) == _st("MQ_ERR_BAD_R")
+    assert L.mq_slice_codes(FAKE, -1, 8, 4, FAKE, None) == _st("MQ_ERR_BAD_SHAPE")
+
+
+def test_pack_validation():
+    L = mq.lib()
+    big = 1 << 30
+    assert L.mq_pack(None, 64, 128, 8, 4, FAKE, big, None) == _st("MQ_ERR_NULL")
+    assert L.mq_pack(FAKE, 64, 128, 8, 4, None, big, None) == _st("MQ_ERR_NULL")
+    assert L.mq_pack(FAKE, 64, 128, 8, 5, FAKE, big, None) == _st("MQ_ERR_BAD_R")
+    assert L.mq_pack(FAKE, 64, 128, 8, 1, FAKE, big, None) == _st("MQ_ERR_BAD_R")
+    assert L.mq_pack(FAKE, 64, 128, 7, 4, FAKE, big, None) == _st("MQ_ERR_BAD_R")
+    assert L.mq_pack(FAKE, 0, 128, 8, 4, FAKE, big, None) == _st("MQ_ERR_BAD_SHAPE")
+    assert L.mq_pack(FAKE, 64, 100, 8, 4, FAKE, big, None) == _st("MQ_ERR_BAD_GROUP")
+    assert L.mq_pack(FAKE, 64, 128, 8, 4, FAKE + 4, big, None) == _st("MQ_ERR_ALIGN")
+    assert L.mq_pack(FAKE, 64, 128, 8, 4, FAKE, 64 * 128 // 2 - 1, None) == _st("MQ_ERR_BUF_TOO_SMALL")
+    assert L.mq_unpack(None, 64, 128, 8, 4, FAKE, None) == _st("MQ_ERR_NULL")
+    assert L.mq_unpack(FAKE, 64, 128, 8, 7, FAKE, None) == _st("MQ_ERR_BAD_R")
+    assert L.mq_unpack(FAKE + 8, 64, 128, 8, 4, FAKE, None) == _st("MQ_ERR_ALIGN")
+    assert L.mq_pack_meta(FAKE, FAKE, 64, 256, 64, FAKE, FAKE, big, None) == _st("MQ_ERR_BAD_GROUP")
+    assert L.mq_pack_meta(FAKE, None, 64, 256, 128, FAKE, FAKE, big, None) == _st("MQ_ERR_NULL")
+    assert L.mq_pack_meta(FAKE, FAKE, 64, 256, 128, FAKE, FAKE, 10, None) == _st("MQ_ERR_BUF_TOO_SMALL")
+    assert L.mq_pack_meta(FAKE, FAKE + 1, 64, 256, 128, FAKE, FAKE, big, None) == _st("MQ_ERR_ALIGN")
+
+
+def _linear(L, **kw):
+    a = dict(x=FAKE, M=1, W=FAKE, st=FAKE, zt=FAKE, N=64, K=128, r=4, group=128, y=FAKE, ws=FAKE, wsb=1 << 30)
+    a.update(kw)
+    return L.mq_linear(a["x"], a["M"], a["W"], a["st"], a["zt"], a["N"], a["K"], a["r"], a["group"], a["y"],
+                       a["ws"], a["wsb"], None)
+
+
+def test_linear_validation():
+    L = mq.lib()
+    for k in ("x", "W", "st", "zt", "y", "ws"):
+        assert _linear(L, **{k: None}) == _st("MQ_ERR_NULL"), k
+    assert _linear(L, r=5) == _st("MQ_ERR_BAD_R")
+    assert _linear(L, r=1) == _st("MQ_ERR_BAD_R")
+    assert _linear(L, M=0) == _st("MQ_ERR_BAD_SHAPE")
+    assert _linear(L, M=257) == _st("MQ_ERR_BAD_SHAPE")
+    assert _linear(L, N=0) == _st("MQ_ERR_BAD_SHAPE")
+    assert _linear(L, K=0) == _st("MQ_ERR_BAD_SHAPE")
+    assert _linear(L, K=192) == _st("MQ_ERR_BAD_GROUP")
+    assert _linear(L, group=64) == _st("MQ_ERR_BAD_GROUP")
+    assert _linear(L, W=FAKE + 8) == _st("MQ_ERR_ALIGN")
+    assert _linear(L, x=FAKE + 2) == _st("MQ_ERR_ALIGN")
+    assert _linear(L, ws=FAKE + 64) == _st("MQ_ERR_ALIGN")
+    assert _linear(L, wsb=128) == _st("MQ_ERR_BUF_TOO_SMALL")
+
+
+def test_workspace_and_stack_validation():
+    L = mq.lib()
+    assert L.mq_workspace_init(None, 1024, None) == _st("MQ_ERR_NULL")
+    assert L.mq_workspace_init(FAKE + 16, 1024, None) == _st("MQ_ERR_ALIGN")
+    assert L.mq_workspace_init(FAKE, 8, None) == _st("MQ_ERR_BUF_TOO_SMALL")
+    lay = (mq.MqLayer * 2)()
+    lay[0] = mq.MqLayer(FAKE, FAKE, FAKE, FAKE, FAKE, 64, 128, 4, 128)
+    lay[1] = mq.MqLayer(FAKE, FAKE, FAKE, FAKE, FAKE, 64, 128, 3, 128)
+    p = ctypes.cast(lay, ctypes.c_void_p)
+    need = L.mq_stack_workspace_bytes(p, 2, 1)
+    assert need > 0
+    assert L.mq_stack_workspace_bytes(p, 0, 1) == 0
+    assert L.mq_stack_workspace_bytes(None, 2, 1) == 0
+    assert L.mq_stack_plan(None, 2, 1, FAKE, need, None) == _st("MQ_ERR_NULL")
+    assert L.mq_stack_plan(p, 2, 1, None, need, None) == _st("MQ_ERR_NULL")
+    assert L.mq_stack_plan(p, 0, 1, FAKE, need, None) == _st("MQ_ERR_BAD_SHAPE")
+    assert L.mq_stack_plan(p, 2, 1, FAKE + 32, need, None) == _st("MQ_ERR_ALIGN")
+    assert L.mq_stack_plan(p, 2, 1, FAKE, need - 1, None) == _st("MQ_ERR_BUF_TOO_SMALL")
+    lay[1].r = 5
+    assert L.mq_stack_plan(p, 2, 1, FAKE, need, None) == _st("MQ_ERR_BAD_R")
+    lay[1].r = 3
+    lay[1].x = None
+    assert L.mq_stack_plan(p, 2, 1, FAKE, need, None) == _st("MQ_ERR_NULL")
+    assert L.mq_linear_stack(None, None) == _st("MQ_ERR_NULL")
+
+
+# ------------------------------------------------------------ input recipe
+def test_parent_quantiser_recipe():
+    L = synth.make_layer(96, 512, M=2, seed=0)
+    assert L["parent"].dtype == np.uint8 and L["scales"].dtype == np.float16 and L["zeros"].dtype == np.float16
+    assert L["parent"].shape == (96, 512) and L["scales"].shape == (96, 4) and L["x"].shape == (2, 512)
+    # min-max RTN: every group reaches (within one step) both ends of the code range
+    g = L["parent"].reshape(96, 4, 128)
+    assert g.min(axis=2).max() <= 1 and g.min(axis=2).min() == 0
+    assert g.max(axis=2).min() >= 254
+    z = L["zeros"].astype(np.float64)
+    assert np.all(z == np.rint(z)) and z.min() >= 0 and z.max() <= 255
+    L2 = synth.make_layer(96, 512, M=2, seed=0)
+    assert np.array_equal(L["parent"], L2["parent"]) and np.array_equal(L["x"], L2["x"])
+    L3 = synth.make_layer(96, 512, M=2, seed=1)
+    assert not np.array_equal(L["parent"], L3["parent"])
+
+
+def test_constant_group_gets_unit_scale():
+    W = np.zeros((2, 128), dtype=np.float32)
+    q, s, z = synth.quantize_parent(W)
+    assert np.all(s == 1.0) and np.all(q == z.astype(np.uint8)[:, :, None].repeat(128, 2).reshape(2, 128))
+
+
+@pytest.mark.parametrize("target", [3.5, 4.0])
+def test_bitwidth_vector_hits_parameter_weighted_mean(target):
+    block = synth.LLAMA2_7B_BLOCK if target == 3.5 else synth.LLAMA3_70B_BLOCK
+    nl = 32 if target == 3.5 else 80
+    sizes = [N * K for (_, _, N, K) in synth.stack_shapes(block, nl)]
+    w, mean = synth.draw_bitwidths(sizes, target, seed=0)
+    assert len(w) == 7 * nl and set(np.unique(w)) <= {2, 3, 4, 6, 8}
+    assert abs(mean - target) <= 0.02
+    assert abs(float((w * np.array(sizes)).sum() / np.sum(sizes)) - mean) < 1e-12
+    w2, _ = synth.draw_bitwidths(sizes, target, seed=0)
+    assert np.array_equal(w, w2)
+    assert len(set(w.tolist())) >= 4
+
+
+# ------------------------------------------------------------ reference layout
+@pytest.mark.parametrize("r", [2, 3, 4, 6, 8])
+def test_reference_layout_uses_every_bit_exactly_once(r):
+    ud, ppu, fields = FIELDS[r]
+    assert ppu * 2 * r == ud * 32 and (4 * r) % ud == 0
+    used = [0] * ud
+    for p, fl in fields.items():
+        bits = 0
+        for (dw, pos, nb, b0) in fl:
+            m = ((1 << nb) - 1) << pos
+            assert used[dw] & m == 0
+            used[dw] |= m
+            cb = ((1 << nb) - 1) << b0
+            assert bits & cb == 0
+            bits |= cb
+        assert bits == (1 << r) - 1
+    assert all(u == 0xFFFF for u in used)
+
+
+@pytest.mark.parametrize("r", [2, 3, 4, 6, 8])
+def test_reference_pack_is_injective_and_sized(r):
+    rng = np.random.default_rng(r)
+    S = (rng.integers(0, 1 << r, (70, 256)).astype(np.uint8) << (8 - r)).astype(np.uint8)
+    a = pack_ref(S, r)
+    assert a.size == mq.mq_packed_bytes(70, 256, r)
+    assert int(np.unpackbits(a).sum()) == int(np.unpackbits((S >> (8 - r)).astype(np.uint8)).sum())
+    S2 = S.copy()
+    S2[37, 200] ^= 1 << (8 - r)
+    b = pack_ref(S2, r)
+    assert np.count_nonzero(np.unpackbits(a ^ b)) == 1          # one code bit -> one packed bit
+
+
+def test_reference_meta_tiling():
+    a = np.arange(70 * 3, dtype=np.float16).reshape(70, 3)
+    t = meta_ref(a).reshape(2, 3, 64)
+    assert t[0, 1, 5] == a[5, 1] and t[1, 2, 5] == a[69, 2] and t[1, 0, 6] == 0
