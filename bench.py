@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of the sliced, group-dequantised linear hot path on one MI355X.
+
+Workload (default): the Llama-2-7B-shaped decoder linears at batch M=1
+(q/k/v/o 4096x4096, gate/up 11008x4096, down 4096x11008; 32 blocks = 224
+linears), 8-bit parent with group 128, benchmarked at EVERY r in {2,3,4,6,8}.
+One step = five persistent launches (mq_linear_stack), one per r, each running
+all 224 linears at that width from weights already packed and resident in HBM
+(slice + pack are load-time steps and are reported separately).  The stacks are
+1.6-6.5 GB each, far beyond the 256 MB last-level cache, so every launch
+streams from HBM.
+
+Prints ONE JSON line: effective HBM GB/s over the step (algorithmic bytes:
+r/8 per weight + fp16 scale and zero per group + activations in and out), the
+per-r microseconds and GB/s, the roofline object of the dominant kernel
+(mq::stack_kernel<1>, HBM-bound) measured with events on the launch stream, and
+the CPU oracle timed on the host cores on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+# HBM bytes per launch of mq::stack_kernel<1> on the default workload (mean over the five widths),
+# from the two rocprofv3 --pmc runs summarised in profiles/stack_kernel_llama2_7b_m1_hbm_traffic.txt
+# (FETCH_SIZE scaled by 1.9987, WRITE_SIZE by 1.0, both calibrated on a 45 MB copy in the same run).
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 3936200739
+WIDTHS = (2, 3, 4, 6, 8)
+
+
+def algo_bytes(N, K, r, M=1, group=128):
+    """Bytes the method must move for one linear: r/8 per weight, fp16 scale + zero per group, x in, y out."""
+    return N * K * r / 8.0 + 4.0 * N * (K // group) + 2.0 * M * K + 2.0 * M * N
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--layers", type=int, default=32, help="decoder blocks in the stack")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-single", action="store_true", help="skip the per-call mq_linear table")
+    ap.add_argument("--no-loadtime", action="store_true", help="skip the slice/pack throughput leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2602_03537_amd as mq
+    from paper_2602_03537_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    block = synth.LLAMA2_7B_BLOCK
+    M = 1
+
+    # ---- inputs: one seeded parent per distinct shape (host recipe), uploaded once
+    host = {}
+    for (name, N, K) in block:
+        if (N, K) not in host:
+            host[(N, K)] = synth.make_layer(N, K, M=M, seed=[0, N, K])
+    devp = {nk: tuple(torch.from_numpy(L[k]).to(dev) for k in ("parent", "scales", "zeros")) for nk, L in host.items()}
+    xdev = {K: torch.from_numpy(synth.make_x(M, K, [0, 77, K])).to(dev) for K in {K for (_, _, K) in block}}
+
+    # ---- load-time steps: slice + pack + meta (timed separately, not part of `value`)
+    loadtime = {}
+    stacks = {}
+    for r in WIDTHS:
+        prepared = {}
+        for nk, (p, s, z) in devp.items():
+            prepared[nk] = mq.prepare_layer(p, s, z, r)
+        layers, nbytes, nweights = [], 0.0, 0
+        for _ in range(args.layers):
+            for (name, N, K) in block:
+                pl = prepared[(N, K)]
+                layers.append(dict(packed_W=pl["packed_W"].clone(), scales_t=pl["scales_t"].clone(),
+                                   zeros_t=pl["zeros_t"].clone(), x=xdev[K],
+                                   y=torch.empty((M, N), dtype=torch.float16, device=dev), N=N, K=K, r=r))
+                nbytes += algo_bytes(N, K, r, M)
+                nweights += N * K
+        plan = mq.mq_stack_plan(layers, M, device=dev)
+        stacks[r] = dict(layers=layers, plan=plan, bytes=nbytes, weights=nweights)
+    torch.cuda.synchronize()
+
+    if not args.no_loadtime:
+        N, K = 11008, 4096
+        p, s, z = devp[(N, K)]
+        S = torch.empty_like(p)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        for r in WIDTHS:
+            out = torch.empty(mq.mq_packed_bytes(N, K, r), dtype=torch.uint8, device=dev)
+            mq.mq_slice_codes(p, 8, r, out=S); mq.mq_pack(S, 8, r, out=out)
+            torch.cuda.synchronize()
+            ev[0].record()
+            for _ in range(5):
+                mq.mq_slice_codes(p, 8, r, out=S)
+            ev[1].record()
+            for _ in range(5):
+                mq.mq_pack(S, 8, r, out=out)
+            ev[2].record()
+            torch.cuda.synchronize()
+            ts, tp = ev[0].elapsed_time(ev[1]) / 5e3, ev[1].elapsed_time(ev[2]) / 5e3
+            loadtime[str(r)] = {"slice_GBps": round(2.0 * N * K / ts / 1e9, 1),
+                                "pack_GBps": round((1.0 + r / 8.0) * N * K / tp / 1e9, 1)}
+
+    # ---- the timed region
+    def step(events=None):
+        for i, r in enumerate(WIDTHS):
+            if events is not None:
+                events[i].record()
+            mq.mq_linear_stack(stacks[r]["plan"])
+        if events is not None:
+            events[len(WIDTHS)].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(WIDTHS) + 1)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(evs[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    per_r_us = {r: [] for r in WIDTHS}
+    for k in range(args.steps):
+        for i, r in enumerate(WIDTHS):
+            per_r_us[r].append(evs[k][i].elapsed_time(evs[k][i + 1]) * 1e3)
+    step_bytes = sum(stacks[r]["bytes"] for r in WIDTHS)
+    n_lin = len(stacks[WIDTHS[0]]["layers"])
+    per_r = {}
+    for r in WIDTHS:
+        us = float(np.median(per_r_us[r]))
+        gbps = stacks[r]["bytes"] / us / 1e3
+        per_r[str(r)] = {"us_per_stack": round(us, 1), "us_min": round(float(np.min(per_r_us[r])), 1),
+                         "us_per_linear": round(us / n_lin, 3), "GBps": round(gbps, 1),
+                         "frac_of_8TBps": round(gbps / HBM_PEAK_GBPS, 4), "algorithmic_MB": round(stacks[r]["bytes"] / 1e6, 1)}
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # roofline of the dominant kernel (mq::stack_kernel<1>): algorithmic bytes per launch / mean launch duration
+    launches = [u for r in WIDTHS for u in per_r_us[r]]
+    avg_launch_us = float(np.mean(launches))
+    bytes_per_launch = step_bytes / len(WIDTHS)
+    achieved = bytes_per_launch / avg_launch_us / 1e3
+    roofline = {"bound": "hbm", "kernel": "mq::stack_kernel<1>", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "avg_launch_us": round(avg_launch_us, 1), "algorithmic_bytes_per_launch": int(bytes_per_launch),
+                "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH if args.layers == 32 else None}
+
+    # ---- per-call table: one mq_linear launch per layer, cold (cycling distinct copies), replayed from a HIP graph
+    single = None
+    if not args.no_single:
+        single = {}
+        for (N, K) in host:
+            for r in WIDTHS:
+                lay = stacks[r]["layers"]
+                same = [L for L in lay if L["N"] == N and L["K"] == K]
+                ws = mq.new_workspace(M, N, K, r)
+                y = torch.empty((M, N), dtype=torch.float16, device=dev)
+
+                def run_all():
+                    for L in same:
+                        mq.mq_linear(L["x"], L["packed_W"], L["scales_t"], L["zeros_t"], N, K, r, 128, ws, y=y)
+
+                run_all()
+                torch.cuda.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    run_all()
+                g.replay()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(3):
+                    g.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / (3 * len(same))
+                b = algo_bytes(N, K, r, M)
+                single[f"{N}x{K}:r{r}"] = {"us": round(us, 2), "GBps": round(b / us / 1e3, 1), "copies": len(same)}
+                del g
+
+    # ---- CPU oracle on the host cores: one decoder block (7 linears) at every r
+    cpu = None
+    if not args.no_cpu:
+        from oracle import c_oracle
+        cb, ct, cores = 0.0, 0.0, 1
+        t_cpu0 = time.perf_counter()
+        for r in WIDTHS:
+            for (name, N, K) in block:
+                L = host[(N, K)]
+                ta = time.perf_counter()
+                _, cores = c_oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], 8, r, 128)
+                ct += time.perf_counter() - ta
+                cb += algo_bytes(N, K, r, M)
+            if time.perf_counter() - t_cpu0 > 60:
+                break
+        cpu = {"value": round(cb / ct / 1e9, 3), "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+               "sample": "plain-C oracle (oracle/mq_oracle.c, slice+dequant+fp64 dot per weight, OpenMP over rows) on "
+                         "one Llama-2-7B decoder block (7 linears, M=1) at each r in {2,3,4,6,8}; same algorithmic-byte "
+                         "accounting as the GPU value", "seconds": round(ct, 2)}
+
+    out = {
+        "metric": "batch-1 sliced GEMV effective HBM GB/s (algorithmic bytes / time) over r in {2,3,4,6,8}",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"Llama-2-7B-shaped decoder linears x{args.layers} blocks ({n_lin} linears), M=1, "
+                               "8-bit parent, group 128, every r in {2,3,4,6,8} (one persistent launch per r)",
+                   "M": M, "group": 128, "c": 8, "widths": list(WIDTHS), "launches_per_step": len(WIDTHS),
+                   "algorithmic_GB_per_step": round(step_bytes / 1e9, 3)},
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
+        "per_r": per_r,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "single_call": single,
+        "load_time": loadtime or None,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -57,6 +57,10 @@ def lib():
         raise RuntimeError(
             f"{_LIB_PATH} is missing: build it with `python -m paper_2602_03537_amd.build` "
             "(there is no CPU or PyTorch fallback)")
+    # PyTorch ships its own copy of the HIP runtime (same soname).  It must be in the
+    # process before libmq.so is loaded, so that both use ONE runtime: streams and
+    # device pointers made by torch are then valid for the library's launches.
+    import torch  # noqa: F401
     L = ctypes.CDLL(_LIB_PATH)
     vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
     sig = {

@@ -268,6 +268,7 @@ template <int M> static hipError_t launch_stack_m(StackParams p, int max_cost, h
     if (cap < 1) cap = 1;
     p.nwaves = (int)(cap < (uint64_t)hw ? cap : (uint64_t)hw);
     const unsigned blocks = (unsigned)((p.nwaves + 3) / 4);
+    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
     hipLaunchKernelGGL(stack_kernel<M>, dim3(blocks), dim3(256), 0, s, p);
     return hipGetLastError();
 }

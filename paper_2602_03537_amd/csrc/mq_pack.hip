@@ -43,6 +43,7 @@ hipError_t launch_slice(const uint8_t *parent, int64_t n, int c, int r, uint8_t 
     int64_t work = vec ? (n + 15) / 16 : n;
     int64_t blocks = (work + 255) / 256;
     if (blocks > 256 * 64) blocks = 256 * 64;
+    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
     hipLaunchKernelGGL(slice_kernel, dim3((unsigned)blocks), dim3(256), 0, s, parent, out, n, (1 << c) - 1, sh, half,
                        (1 << r) - 1, vec);
     return hipGetLastError();
@@ -139,6 +140,7 @@ static hipError_t launch_pack_r(const uint8_t *S, int64_t N, int64_t K, uint4 *p
     const int G = (int)(K / kGroup);
     const int64_t ntiles = pad_rows(N) / kRowBlock * G;
     const int64_t blocks = (ntiles * 64 + 255) / 256;
+    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
     hipLaunchKernelGGL(pack_kernel<R>, dim3((unsigned)blocks), dim3(256), 0, s, S, packed, (int)N, K, G, ntiles);
     return hipGetLastError();
 }
@@ -147,6 +149,7 @@ static hipError_t launch_unpack_r(const uint4 *packed, int64_t N, int64_t K, uin
     const int G = (int)(K / kGroup);
     const int64_t ntiles = pad_rows(N) / kRowBlock * G;
     const int64_t blocks = (ntiles * 64 + 255) / 256;
+    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
     hipLaunchKernelGGL(unpack_kernel<R>, dim3((unsigned)blocks), dim3(256), 0, s, packed, S, (int)N, K, G, ntiles);
     return hipGetLastError();
 }
@@ -191,6 +194,7 @@ __global__ __launch_bounds__(256) void pack_meta_kernel(const _Float16 *__restri
 hipError_t launch_pack_meta(const _Float16 *sc, const _Float16 *zr, int64_t N, int64_t G, _Float16 *st, _Float16 *zt,
                             hipStream_t s) {
     const int64_t total = pad_rows(N) * G;
+    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
     hipLaunchKernelGGL(pack_meta_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, sc, zr, st, zt, N, G,
                        total);
     return hipGetLastError();
@@ -203,6 +207,7 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t *p, size_t n) {
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s) {
     const size_t n = bytes / 4;
     if (!n) return hipSuccess;
+    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
     hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (uint32_t *)p, n);
     return hipGetLastError();
 }
