@@ -1,5 +1,6 @@
 // C ABI of libmq: argument validation (host only, before anything is enqueued),
 // workspace arithmetic and dispatch to the kernel launchers.
+#include <climits>
 #include <mutex>
 #include <unordered_map>
 #include <vector>
@@ -24,26 +25,44 @@ mq_status check_shape(int64_t N, int64_t K, int group) {
 }
 
 size_t counter_bytes(int64_t row_blocks) { return align_up((size_t)row_blocks * 4, kCounterBytesAlign); }
-size_t partial_bytes(int64_t M) { return (size_t)kMaxWaves * 2 * (size_t)M * 64 * sizeof(float); }
+bool use_mfma(int64_t M) { return M > kValuMaxM; }
+int64_t chunks(int64_t M) { return use_mfma(M) ? (M + kChunkCols - 1) / kChunkCols : 1; }
+int slot_floats(int64_t M) { return use_mfma(M) ? 64 * kChunkCols : 64 * (int)M; }
+size_t partial_bytes(int64_t M) {
+    return (size_t)(use_mfma(M) ? kMaxWavesMfma : kMaxWaves) * 2 * (size_t)slot_floats(M) * sizeof(float);
+}
+// MFMA path: re-ordered activations and their group sums for one layer
+size_t xt_bytes(int64_t M, int64_t K, int r) {
+    return use_mfma(M) ? (size_t)chunks(M) * (size_t)(K / kGroup) * (size_t)mfma_per_tile(r) * 256 : 0;
+}
+size_t xsum_bytes(int64_t M, int64_t K) {
+    return use_mfma(M) ? align_up((size_t)chunks(M) * (size_t)(K / kGroup) * kChunkCols * sizeof(float), 256) : 0;
+}
 
 mq_status layer_status(const mq_layer &l, int64_t M) {
     if (!l.packed_W || !l.scales_t || !l.zeros_t || !l.x || !l.y) return MQ_ERR_NULL;
     if (!valid_pack_r(l.r)) return MQ_ERR_BAD_R;
     if (M < 1 || M > MQ_MAX_M) return MQ_ERR_BAD_SHAPE;
     if (mq_status st = check_shape(l.N, l.K, l.group)) return st;
-    if (!aligned(l.packed_W, 16) || !aligned(l.x, 4) || !aligned(l.scales_t, 2) || !aligned(l.zeros_t, 2) ||
-        !aligned(l.y, 2))
+    // the MFMA path reads four scales / zeros with one 8-byte load
+    const size_t meta_align = use_mfma(M) ? 8 : 2;
+    if (!aligned(l.packed_W, 16) || !aligned(l.x, 4) || !aligned(l.scales_t, meta_align) ||
+        !aligned(l.zeros_t, meta_align) || !aligned(l.y, 2))
         return MQ_ERR_ALIGN;
     return MQ_OK;
 }
 
-LayerDesc make_desc(const mq_layer &l, uint64_t cost_start, int cnt_off) {
+// xt / xsum: where the MFMA path keeps this layer's prepared activations (nullptr on the ALU path)
+LayerDesc make_desc(const mq_layer &l, int64_t M, uint64_t cost_start, int cnt_off, int job_start, void *xt,
+                    void *xsum) {
     LayerDesc d{};
     d.Wp = static_cast<const uint4 *>(l.packed_W);
     d.st = reinterpret_cast<const _Float16 *>(l.scales_t);
     d.zt = reinterpret_cast<const _Float16 *>(l.zeros_t);
     d.x = reinterpret_cast<const _Float16 *>(l.x);
     d.y = reinterpret_cast<_Float16 *>(l.y);
+    d.xt = static_cast<const uint4 *>(xt);
+    d.xsum = static_cast<const float *>(xsum);
     d.N = (int32_t)l.N;
     d.K = (int32_t)l.K;
     d.G = (int32_t)(l.K / kGroup);
@@ -51,18 +70,21 @@ LayerDesc make_desc(const mq_layer &l, uint64_t cost_start, int cnt_off) {
     d.r = l.r;
     d.cost = tile_cost(l.r);
     d.cnt_off = cnt_off;
+    d.M = (int32_t)M;
+    d.CB = (int32_t)chunks(M);
+    d.job_start = job_start;
     d.cost_start = cost_start;
     return d;
 }
 
-// Plan workspace: [header 256 B][LayerDesc table][counters][partial sums]
+// Plan workspace: [header 256 B][LayerDesc table][counters][partial sums][prepared activations per layer]
 struct PlanHeader {
     uint64_t magic;
     uint64_t cost_total;
-    int32_t n_layers, M, max_cost, pad_;
+    int32_t n_layers, M, max_cost, n_jobs;
     uint64_t table_off, cnt_off, part_off, total_bytes;
 };
-constexpr uint64_t kPlanMagic = 0x4d51504c414e3031ull;  // "MQPLAN01"
+constexpr uint64_t kPlanMagic = 0x4d51504c414e3032ull;  // "MQPLAN02"
 
 // Host-side copies of the plan headers, keyed by device address, so that running
 // a stack needs no read-back.  mq_stack_plan overwrites the entry of its address.
@@ -70,15 +92,22 @@ std::mutex g_plan_mutex;
 std::unordered_map<void *, PlanHeader> g_plans;
 
 struct PlanLayout {
-    size_t table_off, cnt_off, cnt_bytes, part_off, total;
+    size_t table_off, cnt_off, cnt_bytes, part_off, act_off, total;
 };
-PlanLayout plan_layout(int n_layers, int64_t total_row_blocks, int64_t M) {
+PlanLayout plan_layout(const mq_layer *layers, int n_layers, int64_t M) {
+    int64_t counters = 0;
+    size_t act = 0;
+    for (int i = 0; i < n_layers; ++i) {
+        counters += chunks(M) * (pad_rows(layers[i].N) / kRowBlock);
+        act += xt_bytes(M, layers[i].K, layers[i].r) + xsum_bytes(M, layers[i].K);
+    }
     PlanLayout p;
     p.table_off = 256;
     p.cnt_off = align_up(p.table_off + (size_t)n_layers * sizeof(LayerDesc), 256);
-    p.cnt_bytes = counter_bytes(total_row_blocks);
+    p.cnt_bytes = counter_bytes(counters);
     p.part_off = p.cnt_off + p.cnt_bytes;
-    p.total = p.part_off + partial_bytes(M);
+    p.act_off = p.part_off + partial_bytes(M);
+    p.total = p.act_off + act;
     return p;
 }
 
@@ -115,7 +144,8 @@ size_t mq_meta_bytes(int64_t N, int64_t K, int group) {
 
 size_t mq_workspace_bytes(int64_t M, int64_t N, int64_t K, int r) {
     if (!valid_pack_r(r) || check_shape(N, K, kGroup) != MQ_OK || M < 1 || M > MQ_MAX_M) return 0;
-    return counter_bytes(pad_rows(N) / kRowBlock) + partial_bytes(M);
+    return counter_bytes(chunks(M) * (pad_rows(N) / kRowBlock)) + partial_bytes(M) + xt_bytes(M, K, r) +
+           xsum_bytes(M, K);
 }
 
 mq_status mq_workspace_init(void *ws, size_t ws_bytes, mq_stream stream) {
@@ -180,27 +210,30 @@ mq_status mq_linear(const mq_half *x, int64_t M, const void *packed_W, const mq_
     if (mq_status st = layer_status(l, M)) return st;
     if (!aligned(ws, 256)) return MQ_ERR_ALIGN;
     if (ws_bytes < mq_workspace_bytes(M, N, K, r)) return MQ_ERR_BUF_TOO_SMALL;
-    if (!linear_supports_m(M)) return MQ_ERR_UNSUPPORTED;
 
+    char *base = static_cast<char *>(ws);
+    const size_t cnt_b = counter_bytes(chunks(M) * (pad_rows(N) / kRowBlock));
+    char *act = base + cnt_b + partial_bytes(M);
     StackParams p{};
     p.table = nullptr;
     p.n_layers = 1;
-    p.single = make_desc(l, 0, 0);
-    p.cost_total = (uint64_t)p.single.RB * p.single.G * p.single.cost;
-    p.cnt = static_cast<int32_t *>(ws);
-    p.part = reinterpret_cast<float *>(static_cast<char *>(ws) + counter_bytes(p.single.RB));
+    p.single = make_desc(l, M, 0, 0, 0, use_mfma(M) ? act : nullptr, use_mfma(M) ? act + xt_bytes(M, K, r) : nullptr);
+    p.cost_total = (uint64_t)p.single.CB * p.single.RB * p.single.G * p.single.cost;
+    p.cnt = reinterpret_cast<int32_t *>(base);
+    p.part = reinterpret_cast<float *>(base + cnt_b);
     p.M = (int32_t)M;
-    return launch_stack(p, p.single.cost, (hipStream_t)stream) == hipSuccess ? MQ_OK : MQ_ERR_HIP;
+    p.slot_floats = slot_floats(M);
+    p.n_jobs = p.single.CB * p.single.G;
+    const hipError_t e = use_mfma(M) ? launch_stack_mfma(p, p.single.cost, (hipStream_t)stream)
+                                     : launch_stack(p, p.single.cost, (hipStream_t)stream);
+    return e == hipSuccess ? MQ_OK : MQ_ERR_HIP;
 }
 
 size_t mq_stack_workspace_bytes(const mq_layer *layers, int n_layers, int64_t M) {
     if (!layers || n_layers < 1 || n_layers > (1 << 20) || M < 1 || M > MQ_MAX_M) return 0;
-    int64_t rbs = 0;
-    for (int i = 0; i < n_layers; ++i) {
-        if (check_shape(layers[i].N, layers[i].K, layers[i].group) != MQ_OK) return 0;
-        rbs += pad_rows(layers[i].N) / kRowBlock;
-    }
-    return plan_layout(n_layers, rbs, M).total;
+    for (int i = 0; i < n_layers; ++i)
+        if (!valid_pack_r(layers[i].r) || check_shape(layers[i].N, layers[i].K, layers[i].group) != MQ_OK) return 0;
+    return plan_layout(layers, n_layers, M).total;
 }
 
 mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *plan, size_t plan_bytes,
@@ -213,25 +246,32 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
     const size_t need = mq_stack_workspace_bytes(layers, n_layers, M);
     if (need == 0) return MQ_ERR_BAD_SHAPE;
     if (plan_bytes < need) return MQ_ERR_BUF_TOO_SMALL;
-    if (!linear_supports_m(M)) return MQ_ERR_UNSUPPORTED;
 
-    int64_t rbs = 0;
+    const PlanLayout pl = plan_layout(layers, n_layers, M);
+    char *base_dev = static_cast<char *>(plan);
+    int64_t counters = 0, jobs = 0;
     uint64_t cost = 0;
     int max_cost = 0;
+    size_t act = pl.act_off;
     std::vector<LayerDesc> table((size_t)n_layers);
     for (int i = 0; i < n_layers; ++i) {
-        table[i] = make_desc(layers[i], cost, (int)rbs);
-        cost += (uint64_t)table[i].RB * table[i].G * table[i].cost;
-        rbs += table[i].RB;
+        const size_t xb = xt_bytes(M, layers[i].K, layers[i].r), sb = xsum_bytes(M, layers[i].K);
+        table[i] = make_desc(layers[i], M, cost, (int)counters, (int)jobs, xb ? base_dev + act : nullptr,
+                             xb ? base_dev + act + xb : nullptr);
+        act += xb + sb;
+        cost += (uint64_t)table[i].CB * table[i].RB * table[i].G * table[i].cost;
+        counters += (int64_t)table[i].CB * table[i].RB;
+        jobs += (int64_t)table[i].CB * table[i].G;
         if (table[i].cost > max_cost) max_cost = table[i].cost;
     }
-    const PlanLayout pl = plan_layout(n_layers, rbs, M);
+    if (counters > INT32_MAX || jobs > INT32_MAX) return MQ_ERR_BAD_SHAPE;
     PlanHeader h{};
     h.magic = kPlanMagic;
     h.cost_total = cost;
     h.n_layers = n_layers;
     h.M = (int32_t)M;
     h.max_cost = max_cost;
+    h.n_jobs = (int32_t)jobs;
     h.table_off = pl.table_off;
     h.cnt_off = pl.cnt_off;
     h.part_off = pl.part_off;
@@ -277,7 +317,11 @@ mq_status mq_linear_stack(void *plan, mq_stream stream) {
     p.cnt = reinterpret_cast<int32_t *>(base + h.cnt_off);
     p.part = reinterpret_cast<float *>(base + h.part_off);
     p.M = h.M;
-    return launch_stack(p, h.max_cost, (hipStream_t)stream) == hipSuccess ? MQ_OK : MQ_ERR_HIP;
+    p.slot_floats = slot_floats(h.M);
+    p.n_jobs = h.n_jobs;
+    const hipError_t e = use_mfma(h.M) ? launch_stack_mfma(p, h.max_cost, (hipStream_t)stream)
+                                       : launch_stack(p, h.max_cost, (hipStream_t)stream);
+    return e == hipSuccess ? MQ_OK : MQ_ERR_HIP;
 }
 
 }  // extern "C"

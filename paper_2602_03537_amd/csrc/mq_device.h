@@ -1,0 +1,152 @@
+// Device-side pieces shared by the vector-ALU kernel (mq_linear.hip) and the
+// MFMA kernel (mq_gemm.hip): the persistent schedule over all tiles of a stack
+// and the deterministic split-K hand-off.
+//
+// Schedule.  A layer is CB x RB x G tiles (column chunk, row block of 64 rows,
+// group of 128 columns; CB = 1 unless the batch is served 16 columns at a time).
+// Tiles of all layers form one line in "cost" space (cost ~ bytes of a tile);
+// wavefront w owns the tiles whose start lies in [w*C/W, (w+1)*C/W): a
+// contiguous run, group index fastest, i.e. a contiguous piece of packed
+// memory, while the wave keeps fp32 running sums for its current row block.
+//
+// Split-K.  When a run ends inside a row block the wave leaves its partial sums
+// in a slot of its own and adds the number of groups it covered to the row
+// block's counter; whoever brings the counter to G adds the slots up in wave
+// order (so the result does not depend on timing), writes y and resets the
+// counter.  Nobody waits for anybody.
+#pragma once
+#include "mq_internal.h"
+#include "mq_static_for.h"
+
+namespace mq {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef const uint32_t __attribute__((address_space(4))) *cptr32;  // scalar (SGPR) loads
+
+__device__ __forceinline__ cptr32 as_const(const void *p) { return (cptr32)(uintptr_t)p; }
+
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, a), __builtin_bit_cast(half2_t, b), c, false);
+}
+
+template <int CTRL> __device__ __forceinline__ float dpp_add(float v) {
+    const int t = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false);
+    return v + __builtin_bit_cast(float, t);
+}
+// Sum over the 64 lanes, result in every lane.
+__device__ __forceinline__ float wave_sum(float v) {
+    v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);  // row_half_mirror
+    v = dpp_add<0x140>(v);  // row_mirror: every lane of a 16-lane row holds the row total
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    return v;
+}
+
+__device__ __forceinline__ LayerDesc load_desc(const LayerDesc *p) {
+    constexpr int ND = sizeof(LayerDesc) / 4;
+    static_assert(sizeof(LayerDesc) % 4 == 0, "descriptor is read as dwords");
+    uint32_t w[ND];
+    cptr32 c = as_const(p);
+#pragma unroll
+    for (int i = 0; i < ND; ++i) w[i] = c[i];
+    LayerDesc d;
+    __builtin_memcpy(&d, w, sizeof(d));
+    return d;
+}
+
+// wave that owns the tile starting at cost position pos
+__device__ __forceinline__ int wave_of(uint64_t pos, uint64_t nw, uint64_t ctot) {
+    return (int)(((pos + 1) * nw - 1) / ctot);
+}
+
+// Walk the tiles owned by `wave`: f(L, u_begin, u_end) is called once per layer
+// the wave touches, with tile indices in [0, CB*RB*G) of that layer.
+template <class F> __device__ __forceinline__ void walk_tiles(const StackParams &p, int wave, F &&f) {
+    const uint64_t b_lo = (uint64_t)wave * p.cost_total / (uint64_t)p.nwaves;
+    const uint64_t b_hi = (uint64_t)(wave + 1) * p.cost_total / (uint64_t)p.nwaves;
+    int li = 0;
+    if (p.table) {  // last layer whose cost_start <= b_lo
+        int lo = 0, hi = p.n_layers - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            const uint64_t cs = load_desc(p.table + mid).cost_start;
+            if (cs <= b_lo) lo = mid; else hi = mid - 1;
+        }
+        li = lo;
+    }
+    uint64_t pos = b_lo;
+    while (li < p.n_layers) {
+        const LayerDesc L = p.table ? load_desc(p.table + li) : p.single;
+        const uint64_t layer_end = L.cost_start + (uint64_t)L.CB * L.RB * L.G * L.cost;
+        if (pos < layer_end) {
+            const uint64_t hi = b_hi < layer_end ? b_hi : layer_end;
+            const int u_begin = (int)((pos - L.cost_start + L.cost - 1) / L.cost);
+            const int u_end = (int)((hi - L.cost_start + L.cost - 1) / L.cost);
+            if (u_begin < u_end) f(L, u_begin, u_end);
+        }
+        if (b_hi <= layer_end) break;
+        pos = layer_end;
+        ++li;
+    }
+}
+
+// End of a wave's run inside row block (chunk c, rb): groups [ga, gb) are in acc[NV] (per lane).
+// Complete row block -> final(acc).  Otherwise publish the partial sums; the last
+// contributor sums all slots in wave order and calls final(total).
+//   cnt     : the row block's counter
+//   a       : cost position of the row block's first tile
+// Partial sums travel through agent-scope atomic stores/loads (write-through, cache
+// bypassing), so no whole-L2 write-back or invalidate is needed to publish them.
+template <int NV, class Final>
+__device__ __forceinline__ void finish_row_block(const LayerDesc &L, const StackParams &p, int32_t *cnt, uint64_t a,
+                                                 int ga, int gb, float (&acc)[NV], int wave, int lane, Final &&final) {
+    if (ga == 0 && gb == L.G) {
+        final(acc);
+        return;
+    }
+    const int slot = ga == 0 ? 1 : 0;  // the wave holding a row block's first tile uses slot 1
+    const size_t slot_floats = (size_t)p.slot_floats;
+    float *mine = p.part + (size_t)(wave * 2 + slot) * slot_floats + lane;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) __hip_atomic_store(mine + v * 64, acc[v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // the write-through stores must have been acknowledged before the counter moves
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    int old = 0;
+    if (lane == 0) old = __hip_atomic_fetch_add(cnt, gb - ga, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    old = __builtin_amdgcn_readfirstlane(old);
+    if (old + (gb - ga) != L.G) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    const int w_lo = wave_of(a, p.nwaves, p.cost_total);
+    const int w_hi = wave_of(a + (uint64_t)(L.G - 1) * L.cost, p.nwaves, p.cost_total);
+    // Fixed summation order (w_lo's slot 1, then slot 0 of w_lo+1 .. w_hi); loads are issued
+    // in batches so that their round trips overlap.
+    constexpr int kBatch = NV >= 8 ? 4 : 16;
+    float tot[NV];
+    const float *first = p.part + (size_t)(w_lo * 2 + 1) * slot_floats + lane;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) tot[v] = __hip_atomic_load(first + v * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int w0 = w_lo + 1; w0 <= w_hi; w0 += kBatch) {
+        float t[kBatch][NV];
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const int w = w0 + j <= w_hi ? w0 + j : w_hi;
+            const float *src = p.part + (size_t)(w * 2) * slot_floats + lane;
+#pragma unroll
+            for (int v = 0; v < NV; ++v)
+                t[j][v] = __hip_atomic_load(src + v * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j)
+            if (w0 + j <= w_hi) {
+#pragma unroll
+                for (int v = 0; v < NV; ++v) tot[v] += t[j][v];
+            }
+    }
+    final(tot);
+    if (lane == 0) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+}  // namespace mq

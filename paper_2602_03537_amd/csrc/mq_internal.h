@@ -11,21 +11,30 @@ namespace mq {
 // Upper bound on resident wavefronts of a persistent launch (256 CUs x 32);
 // sizes the partial-sum slots of a workspace independently of the device.
 constexpr int kMaxWaves = 8192;
+constexpr int kMaxWavesMfma = 4096;  // the MFMA kernel runs at most 2 waves per SIMD
 constexpr int kCounterBytesAlign = 256;
 
-// One layer as the persistent kernel sees it.
+// Batches up to kValuMaxM run on the vector ALUs; larger ones on MFMA, 16 columns per chunk.
+constexpr int kValuMaxM = 4;
+constexpr int kChunkCols = 16;
+
+// One layer as the persistent kernels see it.
 struct LayerDesc {
     const uint4 *Wp;
     const _Float16 *st;
     const _Float16 *zt;
     const _Float16 *x;
     _Float16 *y;
+    const uint4 *xt;        // MFMA path: activations re-ordered per (chunk, group, MFMA) by the prep kernel
+    const float *xsum;      // MFMA path: per (chunk, group, column) sums of x
     int32_t N, K, G, RB;    // RB = row blocks = ceil(N/64)
     int32_t r;
     int32_t cost;           // schedule cost of one (row block, group) tile
-    int32_t cnt_off;        // index of this layer's first row-block counter
-    int32_t pad_;
-    uint64_t cost_start;    // sum of RB*G*cost over the preceding layers
+    int32_t cnt_off;        // index of this layer's first row-block counter (CB*RB counters)
+    int32_t M;              // batch rows of x
+    int32_t CB;             // column chunks: 1 on the vector-ALU path, ceil(M/16) on the MFMA path
+    int32_t job_start;      // prep kernel: sum of CB*G over the preceding layers
+    uint64_t cost_start;    // sum of CB*RB*G*cost over the preceding layers
 };
 
 struct StackParams {
@@ -33,12 +42,25 @@ struct StackParams {
     int32_t n_layers;
     int32_t nwaves;          // wavefronts taking part in the schedule
     uint64_t cost_total;
-    float *part;             // [nwaves][2][M][64] partial sums
+    float *part;             // [nwaves][2][slot_floats] partial sums
     int32_t *cnt;            // row-block counters, zero between launches
     int32_t M;
+    int32_t slot_floats;     // floats per partial-sum slot (64*M, or 64*16 on the MFMA path)
+    int32_t n_jobs;          // prep kernel jobs (MFMA path)
     int32_t pad_;
     LayerDesc single;
 };
+
+// MFMA instructions per tile on the MFMA path: (units / 4) * fields per unit
+inline int mfma_per_tile(int r) {
+    switch (r) {
+        case 2: return 16;
+        case 3: return 18;
+        case 4: return 16;
+        case 6: return 20;
+        default: return 16;
+    }
+}
 
 inline int tile_cost(int r) { return 4 * r + 2; }  // ~256-byte lines per tile: weights + meta/x
 
@@ -51,9 +73,9 @@ hipError_t launch_unpack(const uint4 *packed, int64_t N, int64_t K, int r, uint8
 hipError_t launch_pack_meta(const _Float16 *sc, const _Float16 *zr, int64_t N, int64_t G, _Float16 *st,
                             _Float16 *zt, hipStream_t s);
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
-// Fills p.nwaves and launches.  max_cost = largest tile cost in the stack.
+// Fills p.nwaves and launches (vector-ALU path, M <= kValuMaxM).  max_cost = largest tile cost in the stack.
 hipError_t launch_stack(StackParams p, int max_cost, hipStream_t s);
-// True if this build has a kernel for batch M.
-bool linear_supports_m(int64_t M);
+// MFMA path (M > kValuMaxM): activation prep kernel + persistent MFMA kernel.
+hipError_t launch_stack_mfma(StackParams p, int max_cost, hipStream_t s);
 
 }  // namespace mq

@@ -241,13 +241,98 @@ def test_linear_workspace_is_reusable_across_shapes():
         check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"reuse {N}x{K} r={r}")
 
 
-def test_linear_rejects_unsupported_batch_loudly():
+def test_linear_rejects_oversized_batch_loudly():
     L = synth.make_layer(64, 128, M=1, seed=[9])
     lay = mq.prepare_layer(dev(L["parent"]), dev(L["scales"]), dev(L["zeros"]), 4)
     x = torch.zeros((300, 128), dtype=torch.float16, device=DEV)
     ws = mq.new_workspace(1, 64, 128, 4)
     with pytest.raises(mq.MqError):
         mq.mq_linear(x, lay["packed_W"], lay["scales_t"], lay["zeros_t"], 64, 128, 4, 128, ws)
+    small_ws = mq.new_workspace(1, 64, 128, 4)          # sized for M=1, used with M=8
+    with pytest.raises(mq.MqError):
+        mq.mq_linear(x[:8], lay["packed_W"], lay["scales_t"], lay["zeros_t"], 64, 128, 4, 128, small_ws)
+
+
+# ------------------------------------------------------------------ matrix-core path (M > 4)
+@pytest.mark.parametrize("r", WIDTHS)
+@pytest.mark.parametrize("M", [5, 8, 16])
+def test_linear_mfma_one_chunk(r, M):
+    L = synth.make_layer(200, 768, M=M, seed=[40, M])
+    y = run_linear(L, r)
+    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"mfma M={M} r={r}")
+
+
+@pytest.mark.parametrize("r", WIDTHS)
+@pytest.mark.parametrize("shape_m", [(64, 128, 17), (130, 384, 33), (63, 256, 64), (257, 1280, 20), (448, 2048, 256),
+                                     (1, 128, 7), (1027, 512, 12)])
+def test_linear_mfma_chunks_ragged_rows_and_columns(r, shape_m):
+    # several 16-column chunks, a ragged last chunk, N not a multiple of 64 or of 4
+    N, K, M = shape_m
+    L = synth.make_layer(N, K, M=M, seed=[41, N, K, M])
+    y = run_linear(L, r)
+    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"mfma {shape_m} r={r}")
+
+
+@pytest.mark.parametrize("r", WIDTHS)
+def test_linear_mfma_uniform_random_codes_and_fractional_zeros(r):
+    L = synth.make_random_codes_layer(192, 640, M=24, seed=[42, r])
+    y = run_linear(L, r)
+    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"mfma random codes r={r}")
+
+
+def test_linear_mfma_deterministic_guard_bands_and_matches_alu_path():
+    N, K, r, M = 200, 1280, 3, 8
+    L = synth.make_layer(N, K, M=M, seed=[43])
+    lay = mq.prepare_layer(dev(L["parent"]), dev(L["scales"]), dev(L["zeros"]), r)
+    x = dev(L["x"])
+    ws = mq.new_workspace(M, N, K, r)
+    buf = torch.full((M * N + 128,), float("nan"), dtype=torch.float16, device=DEV)
+    y = buf[64:64 + M * N].view(M, N)
+    outs = []
+    for _ in range(3):
+        y.fill_(float("nan"))
+        mq.mq_linear(x, lay["packed_W"], lay["scales_t"], lay["zeros_t"], N, K, r, 128, ws, y=y)
+        torch.cuda.synchronize()
+        outs.append(y.clone())
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    assert torch.isnan(buf[:64]).all() and torch.isnan(buf[64 + M * N:]).all()
+    check_y(outs[0], oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), "mfma guard")
+    # the same rows through the vector-ALU path (M=4 at a time) agree to fp16 rounding of the same fp32 sums
+    ws4 = mq.new_workspace(4, N, K, r)
+    y4 = torch.cat([mq.mq_linear(x[i:i + 4], lay["packed_W"], lay["scales_t"], lay["zeros_t"], N, K, r, 128, ws4)
+                    for i in (0, 4)])
+    assert (outs[0].float() - y4.float()).abs().max() <= 2e-2
+
+
+@pytest.mark.parametrize("M", [8, 20])
+def test_stack_mfma_mixed_widths(M):
+    shapes_r = [(256, 512, 2), (64, 128, 8), (200, 1280, 3), (512, 256, 6), (130, 384, 4), (1024, 1024, 3)]
+    host, layers = _stack(shapes_r, M=M, seed=44)
+    plan = mq.mq_stack_plan(layers, M)
+    for rep in range(2):
+        for lay in layers:
+            lay["y"].fill_(float("nan"))
+        mq.mq_linear_stack(plan)
+        torch.cuda.synchronize()
+        for i, (lay, ref) in enumerate(zip(layers, oracle.linear_stack(host, C, 128))):
+            check_y(lay["y"], ref, f"mfma stack layer {i} rep {rep}")
+
+
+def test_linear_llama3_70b_mlp_shape_batched_sampled_rows():
+    # batched regime on the 8192 -> 28672 up-projection shape; rows sampled for the oracle
+    N, K = 28672, 8192
+    L = synth.make_layer(N, K, M=16, seed=[45])
+    rng = np.random.default_rng(46)
+    rows = np.unique(np.concatenate([[0, 63, 64, N - 1], rng.integers(0, N, 124)]))
+    p, s, z = dev(L["parent"]), dev(L["scales"]), dev(L["zeros"])
+    for r in (3, 4, 8):
+        lay = mq.prepare_layer(p, s, z, r)
+        for M in (1, 4, 16):
+            ws = mq.new_workspace(M, N, K, r)
+            y = mq.mq_linear(dev(L["x"][:M]), lay["packed_W"], lay["scales_t"], lay["zeros_t"], N, K, r, 128, ws)
+            ref = oracle.linear_rows(L["x"][:M], L["parent"], L["scales"], L["zeros"], C, r, 128, rows)
+            check_y(y[:, torch.from_numpy(rows).to(DEV)], ref, f"70B up r={r} M={M}")
+            assert torch.isfinite(y).all()
 
 
 # ------------------------------------------------ full-size layers, sampled rows
@@ -274,7 +359,7 @@ def test_linear_llama2_7b_shapes_sampled_rows(shape):
 
 
 # ------------------------------------------------------------------ stack
-def _stack(shapes_r, M=1, seed=0):
+def _stack(shapes_r, M=1, seed=0):  # noqa: E302
     host, layers = [], []
     for i, (N, K, r) in enumerate(shapes_r):
         L = synth.make_layer(N, K, M=M, seed=[seed, i, N, K])
