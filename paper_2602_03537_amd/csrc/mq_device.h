@@ -21,6 +21,15 @@
 namespace mq {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Pointers inside LayerDesc arrive as plain 64-bit values, so the compiler would treat
+// them as generic ("flat") addresses, whose loads cannot be counted separately from LDS
+// traffic and force full waits.  Everything here lives in global memory: say so.
+#define MQ_GLOBAL __attribute__((address_space(1)))
+template <class T> __device__ __forceinline__ const T MQ_GLOBAL *gl(const T *p) { return (const T MQ_GLOBAL *)p; }
+template <class T> __device__ __forceinline__ T MQ_GLOBAL *gl(T *p) { return (T MQ_GLOBAL *)p; }
 typedef const uint32_t __attribute__((address_space(4))) *cptr32;  // scalar (SGPR) loads
 
 __device__ __forceinline__ cptr32 as_const(const void *p) { return (cptr32)(uintptr_t)p; }
@@ -108,14 +117,14 @@ __device__ __forceinline__ void finish_row_block(const LayerDesc &L, const Stack
     }
     const int slot = ga == 0 ? 1 : 0;  // the wave holding a row block's first tile uses slot 1
     const size_t slot_floats = (size_t)p.slot_floats;
-    float *mine = p.part + (size_t)(wave * 2 + slot) * slot_floats + lane;
+    float MQ_GLOBAL *mine = gl(p.part + (size_t)(wave * 2 + slot) * slot_floats + lane);
 #pragma unroll
     for (int v = 0; v < NV; ++v) __hip_atomic_store(mine + v * 64, acc[v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     // the write-through stores must have been acknowledged before the counter moves
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     int old = 0;
-    if (lane == 0) old = __hip_atomic_fetch_add(cnt, gb - ga, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (lane == 0) old = __hip_atomic_fetch_add(gl(cnt), gb - ga, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     old = __builtin_amdgcn_readfirstlane(old);
     if (old + (gb - ga) != L.G) return;
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
@@ -125,7 +134,7 @@ __device__ __forceinline__ void finish_row_block(const LayerDesc &L, const Stack
     // in batches so that their round trips overlap.
     constexpr int kBatch = NV >= 8 ? 4 : 16;
     float tot[NV];
-    const float *first = p.part + (size_t)(w_lo * 2 + 1) * slot_floats + lane;
+    const float MQ_GLOBAL *first = gl(p.part + (size_t)(w_lo * 2 + 1) * slot_floats + lane);
 #pragma unroll
     for (int v = 0; v < NV; ++v) tot[v] = __hip_atomic_load(first + v * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     for (int w0 = w_lo + 1; w0 <= w_hi; w0 += kBatch) {
@@ -133,7 +142,7 @@ __device__ __forceinline__ void finish_row_block(const LayerDesc &L, const Stack
 #pragma unroll
         for (int j = 0; j < kBatch; ++j) {
             const int w = w0 + j <= w_hi ? w0 + j : w_hi;
-            const float *src = p.part + (size_t)(w * 2) * slot_floats + lane;
+            const float MQ_GLOBAL *src = gl(p.part + (size_t)(w * 2) * slot_floats + lane);
 #pragma unroll
             for (int v = 0; v < NV; ++v)
                 t[j][v] = __hip_atomic_load(src + v * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -146,7 +155,7 @@ __device__ __forceinline__ void finish_row_block(const LayerDesc &L, const Stack
             }
     }
     final(tot);
-    if (lane == 0) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (lane == 0) __hip_atomic_store(gl(cnt), 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 }  // namespace mq

@@ -31,7 +31,7 @@ namespace mq {
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
-typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
+typedef u32x4 uint4_t;
 
 template <int R> struct Mfma {
     using T = Layout<R>;
@@ -50,8 +50,10 @@ template <int R> __device__ __forceinline__ void xprep_job(const LayerDesc &L, i
     const int m = lane >> 2, j = lane & 3;
     const int col = c * kChunkCols + m;
     const bool live = col < L.M;
-    const uint32_t *xrow = reinterpret_cast<const uint32_t *>(L.x + (size_t)(live ? col : 0) * L.K) + (size_t)g * 64;
-    uint32_t *out = reinterpret_cast<uint32_t *>(const_cast<uint4 *>(L.xt)) + ((size_t)(c * L.G + g) * NMF) * 64 + lane;
+    const uint32_t MQ_GLOBAL *xrow =
+        gl(reinterpret_cast<const uint32_t *>(L.x + (size_t)(live ? col : 0) * L.K) + (size_t)g * 64);
+    uint32_t MQ_GLOBAL *out =
+        gl(reinterpret_cast<uint32_t *>(const_cast<uint4 *>(L.xt)) + ((size_t)(c * L.G + g) * NMF) * 64 + lane);
     static_for<NMF>([&](auto mf) {
         constexpr int Q = mf / T::NOPS;
         constexpr Op o = T::op(mf % T::NOPS);
@@ -65,7 +67,7 @@ template <int R> __device__ __forceinline__ void xprep_job(const LayerDesc &L, i
     for (int i = 0; i < 16; ++i) s = dot2(live ? xrow[j * 16 + i] : 0u, 0x3C003C00u, s);
     s = dpp_add<0xB1>(s);
     s = dpp_add<0x4E>(s);
-    if (j == 0) const_cast<float *>(L.xsum)[(size_t)(c * L.G + g) * kChunkCols + m] = s;
+    if (j == 0) gl(const_cast<float *>(L.xsum))[(size_t)(c * L.G + g) * kChunkCols + m] = s;
 }
 
 __global__ __launch_bounds__(256) void xprep_kernel(const StackParams p) {
@@ -96,7 +98,7 @@ __global__ __launch_bounds__(256) void xprep_kernel(const StackParams p) {
 // ------------------------------------------------------------------ main kernel
 template <int R> struct GemmTile {
     uint32_t w[4 * R];
-    uint2 s4[4], z4[4];  // scale / zero of the 16 tile rows this lane holds in the D layout
+    u32x2 s4[4], z4[4];  // scale / zero of the 16 tile rows this lane holds in the D layout
     float xg;            // X_g of this lane's output column
 };
 
@@ -120,28 +122,39 @@ __device__ __forceinline__ LaneMap lane_map(int lane) {
 template <int R>
 __device__ __forceinline__ void load_gemm_tile(GemmTile<R> &t, const LayerDesc &L, int c, int u, int g,
                                                const LaneMap &lm, int lane) {
-    const uint4 *src = L.Wp + (size_t)u * (R * 64) + lane;
+    const u32x4 MQ_GLOBAL *src = gl(reinterpret_cast<const u32x4 *>(L.Wp) + (size_t)u * (R * 64) + lane);
 #pragma unroll
     for (int i = 0; i < R; ++i) {
-        const uint4 v = src[i * 64];
+        const u32x4 v = src[i * 64];
         t.w[4 * i] = v.x; t.w[4 * i + 1] = v.y; t.w[4 * i + 2] = v.z; t.w[4 * i + 3] = v.w;
     }
-    const uint2 *s = reinterpret_cast<const uint2 *>(L.st + (size_t)u * 64 + lm.rowbase);
-    const uint2 *z = reinterpret_cast<const uint2 *>(L.zt + (size_t)u * 64 + lm.rowbase);
+    const u32x2 MQ_GLOBAL *s = gl(reinterpret_cast<const u32x2 *>(L.st + (size_t)u * 64 + lm.rowbase));
+    const u32x2 MQ_GLOBAL *z = gl(reinterpret_cast<const u32x2 *>(L.zt + (size_t)u * 64 + lm.rowbase));
 #pragma unroll
     for (int q = 0; q < 4; ++q) { t.s4[q] = s[2 * q]; t.z4[q] = z[2 * q]; }
-    t.xg = L.xsum[(size_t)(c * L.G + g) * kChunkCols + lm.col];
+    t.xg = gl(L.xsum)[(size_t)(c * L.G + g) * kChunkCols + lm.col];
 }
 
-__device__ __forceinline__ float half_of(uint2 v, int e) {
+__device__ __forceinline__ float half_of(u32x2 v, int e) {
     const uint32_t w = e < 2 ? v.x : v.y;
     const uint16_t h = (uint16_t)(e & 1 ? w >> 16 : w & 0xFFFF);
     return (float)__builtin_bit_cast(_Float16, h);
 }
 
+// B operands of one tile: NMF x 16 bytes per lane.  They are loaded one tile ahead, each
+// register quad being refilled right after the MFMA that consumed it.
+template <int R> struct BRegs {
+    uint4_t b[Mfma<R>::NMF];
+};
 template <int R>
-__device__ __forceinline__ void gemm_tile_math(const GemmTile<R> &t, __amdgpu_buffer_rsrc_t xt, uint32_t tile_off,
-                                               const LaneMap &lm, float (&yacc)[16]) {
+__device__ __forceinline__ void load_b_all(BRegs<R> &B, __amdgpu_buffer_rsrc_t xt, uint32_t voff) {
+    static_for<Mfma<R>::NMF>([&](auto mf) { B.b[mf] = __builtin_amdgcn_raw_buffer_load_b128(xt, voff + mf * 256, 0, 0); });
+}
+
+// voff_next: this lane's B offset for the NEXT tile of the run (any valid tile if there is none).
+template <int R>
+__device__ __forceinline__ void gemm_tile_math(const GemmTile<R> &t, BRegs<R> &B, __amdgpu_buffer_rsrc_t xt,
+                                               uint32_t voff_next, float (&yacc)[16]) {
     using T = Layout<R>;
     using MF = Mfma<R>;
     float16_t D[T::NKEYS];
@@ -149,7 +162,6 @@ __device__ __forceinline__ void gemm_tile_math(const GemmTile<R> &t, __amdgpu_bu
     for (int k = 0; k < T::NKEYS; ++k)
 #pragma unroll
         for (int v = 0; v < 16; ++v) D[k][v] = 0.f;
-    const uint32_t voff = lm.boff + tile_off;  // stays out of range for the zero lanes
     static_for<MF::NMF>([&](auto mf) {
         constexpr int Q = mf / T::NOPS;
         constexpr int oi = mf % T::NOPS;
@@ -163,9 +175,9 @@ __device__ __forceinline__ void gemm_tile_math(const GemmTile<R> &t, __amdgpu_bu
             a[j] = v & ((uint32_t)o.mask * 0x10001u);
         }
         const uint4_t av = {a[0], a[1], a[2], a[3]};
-        const uint4_t bv = __builtin_amdgcn_raw_buffer_load_b128(xt, voff + mf * 256, 0, 0);
-        D[key] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, av), __builtin_bit_cast(half8_t, bv),
-                                                        D[key], 0, 0, 0);
+        D[key] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, av),
+                                                        __builtin_bit_cast(half8_t, B.b[mf]), D[key], 0, 0, 0);
+        B.b[mf] = __builtin_amdgcn_raw_buffer_load_b128(xt, voff_next + mf * 256, 0, 0);
     });
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
@@ -195,10 +207,13 @@ __device__ __forceinline__ void run_gemm_units(const LayerDesc &L, const StackPa
     const bool fast_store = (L.N & 3) == 0 && (reinterpret_cast<uintptr_t>(L.y) & 7) == 0;
 
     GemmTile<R> cur, nxt;
+    BRegs<R> B;
     load_gemm_tile<R>(cur, L, c, u_begin, g, lm, lane);
+    load_b_all<R>(B, xt, lm.boff + (uint32_t)(c * L.G + g) * (MF::NMF * 256u));
     for (int u = u_begin; u < u_end; ++u) {
-        if (u + 1 < u_end) load_gemm_tile<R>(nxt, L, c, u + 1, g + 1 == L.G ? 0 : g + 1, lm, lane);
-        gemm_tile_math<R>(cur, xt, (uint32_t)(c * L.G + g) * (MF::NMF * 256u), lm, yacc);
+        const int g_next = (u + 1 < u_end) ? (g + 1 == L.G ? 0 : g + 1) : g;
+        if (u + 1 < u_end) load_gemm_tile<R>(nxt, L, c, u + 1, g_next, lm, lane);
+        gemm_tile_math<R>(cur, B, xt, lm.boff + (uint32_t)(c * L.G + g_next) * (MF::NMF * 256u), yacc);
         ++g;
         if (g == L.G || u + 1 == u_end) {
             const uint64_t a = L.cost_start + ((uint64_t)c * L.RB * L.G + (uint64_t)rb * L.G) * L.cost;
@@ -206,17 +221,16 @@ __device__ __forceinline__ void run_gemm_units(const LayerDesc &L, const StackPa
             finish_row_block<16>(L, p, p.cnt + L.cnt_off + c * L.RB + rb, a, ga, g, yacc, wave, lane,
                                  [&](const float(&tot)[16]) {
                                      if (col >= L.M) return;
-                                     _Float16 *yrow = L.y + (size_t)col * L.N;
+                                     _Float16 MQ_GLOBAL *yrow = gl(L.y + (size_t)col * L.N);
 #pragma unroll
                                      for (int q = 0; q < 4; ++q) {
                                          const int row = row0 + 8 * q;
                                          if (fast_store && row + 3 < L.N) {
                                              const half2_t lo = {(_Float16)tot[4 * q], (_Float16)tot[4 * q + 1]};
                                              const half2_t hi = {(_Float16)tot[4 * q + 2], (_Float16)tot[4 * q + 3]};
-                                             uint2 pk;
-                                             pk.x = __builtin_bit_cast(uint32_t, lo);
-                                             pk.y = __builtin_bit_cast(uint32_t, hi);
-                                             *reinterpret_cast<uint2 *>(yrow + row) = pk;
+                                             const u32x2 pk = {__builtin_bit_cast(uint32_t, lo),
+                                                               __builtin_bit_cast(uint32_t, hi)};
+                                             *(u32x2 MQ_GLOBAL *)(yrow + row) = pk;
                                          } else {
 #pragma unroll
                                              for (int e = 0; e < 4; ++e)

@@ -18,14 +18,14 @@ template <int R> struct TileRegs {
 };
 
 template <int R> __device__ __forceinline__ void load_tile(TileRegs<R> &t, const LayerDesc &L, int u, int lane) {
-    const uint4 *src = L.Wp + (size_t)u * (R * 64) + lane;
+    const u32x4 MQ_GLOBAL *src = gl(reinterpret_cast<const u32x4 *>(L.Wp) + (size_t)u * (R * 64) + lane);
 #pragma unroll
     for (int i = 0; i < R; ++i) {
-        const uint4 v = src[i * 64];
+        const u32x4 v = src[i * 64];
         t.w[4 * i] = v.x; t.w[4 * i + 1] = v.y; t.w[4 * i + 2] = v.z; t.w[4 * i + 3] = v.w;
     }
-    t.s = L.st[(size_t)u * 64 + lane];
-    t.z = L.zt[(size_t)u * 64 + lane];
+    t.s = gl(L.st)[(size_t)u * 64 + lane];
+    t.z = gl(L.zt)[(size_t)u * 64 + lane];
 }
 
 template <int R, int M>
@@ -37,7 +37,7 @@ __device__ __forceinline__ void tile_math(const TileRegs<R> &t, const LayerDesc 
 #pragma unroll
     for (int m = 0; m < M; ++m) {
         const _Float16 *xrow = L.x + (size_t)m * L.K + (size_t)g * kGroup;
-        const uint32_t xl = reinterpret_cast<const uint32_t *>(xrow)[lane];
+        const uint32_t xl = gl(reinterpret_cast<const uint32_t *>(xrow))[lane];
         xg[m] = wave_sum(dot2(xl, 0x3C003C00u, 0.f));  // (1.0, 1.0)
         xs[m] = as_const(xrow);
     }
@@ -93,7 +93,7 @@ __device__ __forceinline__ void run_units(const LayerDesc &L, const StackParams 
                                 wave, lane, [&](const float(&tot)[M]) {
 #pragma unroll
                                     for (int m = 0; m < M; ++m)
-                                        if (row < L.N) L.y[(size_t)m * L.N + row] = (_Float16)tot[m];
+                                        if (row < L.N) gl(L.y)[(size_t)m * L.N + row] = (_Float16)tot[m];
                                 });
             ++rb;
             g = 0;
