@@ -96,44 +96,28 @@ __global__ __launch_bounds__(256) void xprep_kernel(const StackParams p) {
 }
 
 // ------------------------------------------------------------------ main kernel
-template <int R> struct GemmTile {
-    uint32_t w[4 * R];
-    u32x2 s4[4], z4[4];  // scale / zero of the 16 tile rows this lane holds in the D layout
-    float xg;            // X_g of this lane's output column
-};
-
 // D layout of a 32x32 accumulator: register v of lane l is D[8*(v/4) + 4*(l/32) + v%4][l%32];
 // output column j = l%32 maps to batch column j%16 and tile-row half j/16.
 struct LaneMap {
-    int col;      // batch column inside the chunk
-    int rowbase;  // tile row of v = 0: 32*(j/16) + 4*(l/32); row(v) = rowbase + 8*(v/4) + v%4
-    uint32_t boff;  // byte offset of this lane's B operand inside a 256-byte MFMA block, or out of range
+    int col;        // batch column inside the chunk
+    int rowbase;    // tile row of v = 0: 32*(j/16) + 4*(l/32); row(v) = rowbase + 8*(v/4) + v%4
+    bool b_live;    // as a B supplier the lane is k-half l/32 of output column j: non-zero only if l/32 == j/16
 };
 __device__ __forceinline__ LaneMap lane_map(int lane) {
     LaneMap m;
     const int j = lane & 31, hh = j >> 4, dh = lane >> 5;
     m.col = j & 15;
     m.rowbase = 32 * hh + 4 * dh;
-    // as a B supplier the lane is k-half dh of output column j: non-zero only if dh == hh
-    m.boff = dh == hh ? (uint32_t)(m.col * 16) : 0xF0000000u;
+    m.b_live = dh == hh;
     return m;
 }
 
-template <int R>
-__device__ __forceinline__ void load_gemm_tile(GemmTile<R> &t, const LayerDesc &L, int c, int u, int g,
-                                               const LaneMap &lm, int lane) {
-    const u32x4 MQ_GLOBAL *src = gl(reinterpret_cast<const u32x4 *>(L.Wp) + (size_t)u * (R * 64) + lane);
-#pragma unroll
-    for (int i = 0; i < R; ++i) {
-        const u32x4 v = src[i * 64];
-        t.w[4 * i] = v.x; t.w[4 * i + 1] = v.y; t.w[4 * i + 2] = v.z; t.w[4 * i + 3] = v.w;
-    }
-    const u32x2 MQ_GLOBAL *s = gl(reinterpret_cast<const u32x2 *>(L.st + (size_t)u * 64 + lm.rowbase));
-    const u32x2 MQ_GLOBAL *z = gl(reinterpret_cast<const u32x2 *>(L.zt + (size_t)u * 64 + lm.rowbase));
-#pragma unroll
-    for (int q = 0; q < 4; ++q) { t.s4[q] = s[2 * q]; t.z4[q] = z[2 * q]; }
-    t.xg = gl(L.xsum)[(size_t)(c * L.G + g) * kChunkCols + lm.col];
-}
+// Per-wave LDS: two stages of prepared activations (the B operands of one tile each) so
+// that B is read just in time with ds_read instead of being held in 64..80 registers.
+constexpr int kStageBytes = 5 * 1024;                 // >= NMF * 256 for every width (NMF <= 20)
+constexpr int kWaveLds = 2 * kStageBytes;
+constexpr int kZeroOff = 4 * kWaveLds;                // 16 zero bytes after the four waves' stages
+constexpr int kLdsBytes = kZeroOff + 16;
 
 __device__ __forceinline__ float half_of(u32x2 v, int e) {
     const uint32_t w = e < 2 ? v.x : v.y;
@@ -141,62 +125,94 @@ __device__ __forceinline__ float half_of(u32x2 v, int e) {
     return (float)__builtin_bit_cast(_Float16, h);
 }
 
-// B operands of one tile: NMF x 16 bytes per lane.  They are loaded one tile ahead, each
-// register quad being refilled right after the MFMA that consumed it.
-template <int R> struct BRegs {
-    uint4_t b[Mfma<R>::NMF];
-};
-template <int R>
-__device__ __forceinline__ void load_b_all(BRegs<R> &B, __amdgpu_buffer_rsrc_t xt, uint32_t voff) {
-    static_for<Mfma<R>::NMF>([&](auto mf) { B.b[mf] = __builtin_amdgcn_raw_buffer_load_b128(xt, voff + mf * 256, 0, 0); });
-}
+template <int R> struct GemmCtx {
+    using MF = Mfma<R>;
+    static constexpr int NXL = (MF::NMF * 256 + 1023) / 1024;  // 1 KiB wave-loads per tile of activations
+    const LayerDesc &L;
+    const LaneMap lm;
+    const int lane, c;
+    __amdgpu_buffer_rsrc_t xt;
+    uint8_t *lds;   // this wave's two stages
+    uint8_t *zero;  // 16 zero bytes
 
-// voff_next: this lane's B offset for the NEXT tile of the run (any valid tile if there is none).
+    __device__ __forceinline__ void load_w(uint32_t (&w)[4 * R], int u) const {
+        const u32x4 MQ_GLOBAL *src = gl(reinterpret_cast<const u32x4 *>(L.Wp) + (size_t)u * (R * 64) + lane);
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            const u32x4 v = src[i * 64];
+            w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
+        }
+    }
+    // activations of group g of this chunk: NXL coalesced 16-byte loads (past the end of the buffer -> 0)
+    __device__ __forceinline__ void load_x(u32x4 (&xb)[NXL], int g) const {
+        const uint32_t off = (uint32_t)(c * L.G + g) * (MF::NMF * 256u) + (uint32_t)lane * 16u;
+#pragma unroll
+        for (int i = 0; i < NXL; ++i) xb[i] = __builtin_amdgcn_raw_buffer_load_b128(xt, off + i * 1024, 0, 0);
+    }
+    __device__ __forceinline__ void store_x(const u32x4 (&xb)[NXL], int stage) const {
+        u32x4 *dst = reinterpret_cast<u32x4 *>(lds + stage * kStageBytes) + lane;
+#pragma unroll
+        for (int i = 0; i < NXL; ++i) dst[i * 64] = xb[i];
+    }
+};
+
+// One tile: MFMAs key by key (one 32x32 accumulator live at a time), then the per-group
+// scale / zero step.  B comes from LDS stage `stage`.
 template <int R>
-__device__ __forceinline__ void gemm_tile_math(const GemmTile<R> &t, BRegs<R> &B, __amdgpu_buffer_rsrc_t xt,
-                                               uint32_t voff_next, float (&yacc)[16]) {
+__device__ __forceinline__ void gemm_tile_math(const GemmCtx<R> &cx, const uint32_t (&w)[4 * R], int stage,
+                                               const u32x2 (&s4)[4], const u32x2 (&z4)[4], float xg,
+                                               float (&yacc)[16]) {
     using T = Layout<R>;
     using MF = Mfma<R>;
-    float16_t D[T::NKEYS];
+    const u32x4 *bsrc = cx.lm.b_live ? reinterpret_cast<const u32x4 *>(cx.lds + stage * kStageBytes) + cx.lm.col
+                                     : reinterpret_cast<const u32x4 *>(cx.zero);
+    const int bstep = cx.lm.b_live ? 16 : 0;  // u32x4 elements per MFMA block (256 bytes)
+    // field value = digit * 2^(key-24): back to code units, then Eq. 1's rescale 2^(8-r)
+    float dsum[16];
+    static_for<T::NKEYS>([&](auto key) {
+        float16_t D;
 #pragma unroll
-    for (int k = 0; k < T::NKEYS; ++k)
+        for (int v = 0; v < 16; ++v) D[v] = 0.f;
+        static_for<MF::NMF>([&](auto mf) {
+            constexpr int Q = mf / T::NOPS;
+            constexpr int oi = mf % T::NOPS;
+            constexpr Op o = T::op(oi);
+            if constexpr (key_index<R>(oi) == key) {
+                uint32_t a[4];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) D[k][v] = 0.f;
-    static_for<MF::NMF>([&](auto mf) {
-        constexpr int Q = mf / T::NOPS;
-        constexpr int oi = mf % T::NOPS;
-        constexpr Op o = T::op(oi);
-        constexpr int key = key_index<R>(oi);
-        uint32_t a[4];
+                for (int j = 0; j < 4; ++j) {
+                    uint32_t v = w[(4 * Q + j) * T::UD + o.dw];
+                    if constexpr (o.sh != 0) v >>= o.sh;
+                    a[j] = v & ((uint32_t)o.mask * 0x10001u);
+                }
+                const u32x4 av = {a[0], a[1], a[2], a[3]};
+                const u32x4 bv = bsrc[mf * bstep];
+                D = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, av),
+                                                           __builtin_bit_cast(half8_t, bv), D, 0, 0, 0);
+            }
+        });
+        const float ck = __builtin_ldexpf(1.f, 24 - T::key(key) + kC - R);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            uint32_t v = t.w[(4 * Q + j) * T::UD + o.dw];
-            if constexpr (o.sh != 0) v >>= o.sh;
-            a[j] = v & ((uint32_t)o.mask * 0x10001u);
-        }
-        const uint4_t av = {a[0], a[1], a[2], a[3]};
-        D[key] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, av),
-                                                        __builtin_bit_cast(half8_t, B.b[mf]), D[key], 0, 0, 0);
-        B.b[mf] = __builtin_amdgcn_raw_buffer_load_b128(xt, voff_next + mf * 256, 0, 0);
+        for (int v = 0; v < 16; ++v) dsum[v] = key == 0 ? D[v] * ck : fmaf(D[v], ck, dsum[v]);
     });
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-        const float s = half_of(t.s4[v >> 2], v & 3), z = half_of(t.z4[v >> 2], v & 3);
-        float d = 0.f;
-        static_for<T::NKEYS>([&](auto k) { d = fmaf(D[k][v], __builtin_ldexpf(1.f, 24 - T::key(k) + kC - R), d); });
-        yacc[v] = fmaf(s, fmaf(-z, t.xg, d), yacc[v]);
+        const float s = half_of(s4[v >> 2], v & 3), z = half_of(z4[v >> 2], v & 3);
+        yacc[v] = fmaf(s, fmaf(-z, xg, dsum[v]), yacc[v]);
     }
 }
 
 // Tiles [u_begin, u_end) of chunk c of one layer (tile index u = rb*G + g).
 template <int R>
 __device__ __forceinline__ void run_gemm_units(const LayerDesc &L, const StackParams &p, int c, int u_begin, int u_end,
-                                               int wave, int lane) {
+                                               int wave, int lane, uint8_t *lds_wave, uint8_t *lds_zero) {
     using MF = Mfma<R>;
-    const LaneMap lm = lane_map(lane);
+    using Ctx = GemmCtx<R>;
     const uint32_t xt_bytes = (uint32_t)L.CB * L.G * MF::NMF * 256u;
-    const __amdgpu_buffer_rsrc_t xt =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(L.xt), 0, (int)xt_bytes, 0x00020000);
+    const Ctx cx{L, lane_map(lane), lane, c,
+                 __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(L.xt), 0, (int)xt_bytes, 0x00020000), lds_wave,
+                 lds_zero};
+    const LaneMap &lm = cx.lm;
     int rb = u_begin / L.G;
     int g = u_begin - rb * L.G;
     int ga = g;
@@ -206,14 +222,31 @@ __device__ __forceinline__ void run_gemm_units(const LayerDesc &L, const StackPa
     const int col = c * kChunkCols + lm.col;
     const bool fast_store = (L.N & 3) == 0 && (reinterpret_cast<uintptr_t>(L.y) & 7) == 0;
 
-    GemmTile<R> cur, nxt;
-    BRegs<R> B;
-    load_gemm_tile<R>(cur, L, c, u_begin, g, lm, lane);
-    load_b_all<R>(B, xt, lm.boff + (uint32_t)(c * L.G + g) * (MF::NMF * 256u));
-    for (int u = u_begin; u < u_end; ++u) {
-        const int g_next = (u + 1 < u_end) ? (g + 1 == L.G ? 0 : g + 1) : g;
-        if (u + 1 < u_end) load_gemm_tile<R>(nxt, L, c, u + 1, g_next, lm, lane);
-        gemm_tile_math<R>(cur, B, xt, lm.boff + (uint32_t)(c * L.G + g_next) * (MF::NMF * 256u), yacc);
+    uint32_t w[2][4 * R];
+    {
+        u32x4 xb[Ctx::NXL];
+        cx.load_x(xb, g);
+        cx.load_w(w[0], u_begin);
+        cx.store_x(xb, 0);
+    }
+    int u = u_begin;
+    // one tile: compute on wc from LDS stage `st`, prefetch the next tile into wn / stage st^1
+    auto body = [&](const uint32_t (&wc)[4 * R], uint32_t (&wn)[4 * R], int st) {
+        // the last tile of the run prefetches itself again: no branch, so no full wait at a join
+        const bool more = u + 1 < u_end;
+        const int g_next = more ? (g + 1 == L.G ? 0 : g + 1) : g;
+        u32x4 xb[Ctx::NXL];
+        cx.load_x(xb, g_next);                 // first: it is awaited first (loads return in order)
+        cx.load_w(wn, more ? u + 1 : u);
+        u32x2 s4[4], z4[4];
+        const u32x2 MQ_GLOBAL *sp = gl(reinterpret_cast<const u32x2 *>(L.st + (size_t)u * 64 + lm.rowbase));
+        const u32x2 MQ_GLOBAL *zp = gl(reinterpret_cast<const u32x2 *>(L.zt + (size_t)u * 64 + lm.rowbase));
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { s4[q] = sp[2 * q]; z4[q] = zp[2 * q]; }
+        const float xg = gl(L.xsum)[(size_t)(c * L.G + g) * kChunkCols + lm.col];
+        __builtin_amdgcn_sched_barrier(0);     // keep the loads up here, ahead of the math
+        gemm_tile_math<R>(cx, wc, st, s4, z4, xg, yacc);
+        cx.store_x(xb, st ^ 1);
         ++g;
         if (g == L.G || u + 1 == u_end) {
             const uint64_t a = L.cost_start + ((uint64_t)c * L.RB * L.G + (uint64_t)rb * L.G) * L.cost;
@@ -244,14 +277,23 @@ __device__ __forceinline__ void run_gemm_units(const LayerDesc &L, const StackPa
 #pragma unroll
             for (int v = 0; v < 16; ++v) yacc[v] = 0.f;
         }
-        cur = nxt;
+        ++u;
+    };
+    while (u < u_end) {
+        body(w[0], w[1], 0);
+        if (u >= u_end) break;
+        body(w[1], w[0], 1);
     }
 }
 
 __global__ __launch_bounds__(256, 2) void gemm_stack_kernel(const StackParams p) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kLdsBytes];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6));
     if (wave >= p.nwaves) return;
+    uint8_t *lds_wave = lds + (threadIdx.x >> 6) * kWaveLds;
+    uint8_t *lds_zero = lds + kZeroOff;
+    if (lane < 4) reinterpret_cast<uint32_t *>(lds_zero)[lane] = 0u;  // every wave writes the same zeros before it reads them
     walk_tiles(p, wave, [&](const LayerDesc &L, int u_begin, int u_end) {
         const int per_chunk = L.RB * L.G;
         for (int c = u_begin / per_chunk; c < L.CB && c * per_chunk < u_end; ++c) {
@@ -259,11 +301,11 @@ __global__ __launch_bounds__(256, 2) void gemm_stack_kernel(const StackParams p)
             const int hi = (u_end < (c + 1) * per_chunk ? u_end : (c + 1) * per_chunk) - c * per_chunk;
             if (lo >= hi) continue;
             switch (L.r) {
-                case 2: run_gemm_units<2>(L, p, c, lo, hi, wave, lane); break;
-                case 3: run_gemm_units<3>(L, p, c, lo, hi, wave, lane); break;
-                case 4: run_gemm_units<4>(L, p, c, lo, hi, wave, lane); break;
-                case 6: run_gemm_units<6>(L, p, c, lo, hi, wave, lane); break;
-                default: run_gemm_units<8>(L, p, c, lo, hi, wave, lane); break;
+                case 2: run_gemm_units<2>(L, p, c, lo, hi, wave, lane, lds_wave, lds_zero); break;
+                case 3: run_gemm_units<3>(L, p, c, lo, hi, wave, lane, lds_wave, lds_zero); break;
+                case 4: run_gemm_units<4>(L, p, c, lo, hi, wave, lane, lds_wave, lds_zero); break;
+                case 6: run_gemm_units<6>(L, p, c, lo, hi, wave, lane, lds_wave, lds_zero); break;
+                default: run_gemm_units<8>(L, p, c, lo, hi, wave, lane, lds_wave, lds_zero); break;
             }
         }
     });
