@@ -224,8 +224,13 @@ mq_status mq_linear(const mq_half *x, int64_t M, const void *packed_W, const mq_
     p.M = (int32_t)M;
     p.slot_floats = slot_floats(M);
     p.n_jobs = p.single.CB * p.single.G;
-    const hipError_t e = use_mfma(M) ? launch_stack_mfma(p, p.single.cost, (hipStream_t)stream)
-                                     : launch_stack(p, p.single.cost, (hipStream_t)stream);
+    hipError_t e;
+    if (use_mfma(M))
+        e = launch_stack_mfma(p, p.single.cost, (hipStream_t)stream);
+    else if (linear_rb_fits(p.single, partial_bytes(M)))
+        e = launch_linear_rb(p.single, p.part, p.cnt, (hipStream_t)stream);
+    else
+        e = launch_stack(p, p.single.cost, (hipStream_t)stream);
     return e == hipSuccess ? MQ_OK : MQ_ERR_HIP;
 }
 

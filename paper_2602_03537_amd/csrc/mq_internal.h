@@ -75,6 +75,9 @@ hipError_t launch_pack_meta(const _Float16 *sc, const _Float16 *zr, int64_t N, i
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
 // Fills p.nwaves and launches (vector-ALU path, M <= kValuMaxM).  max_cost = largest tile cost in the stack.
 hipError_t launch_stack(StackParams p, int max_cost, hipStream_t s);
+// Single layer, M <= kValuMaxM: one workgroup per (row block, K slice); see mq_linear.hip.
+bool linear_rb_fits(const LayerDesc &L, size_t part_bytes);
+hipError_t launch_linear_rb(const LayerDesc &L, float *part, int32_t *cnt, hipStream_t s);
 // MFMA path (M > kValuMaxM): activation prep kernel + persistent MFMA kernel.
 hipError_t launch_stack_mfma(StackParams p, int max_cost, hipStream_t s);
 

@@ -120,6 +120,130 @@ template <int M> __global__ __launch_bounds__(256) void stack_kernel(const Stack
     });
 }
 
+// ------------------------------------------------------------------ one layer, low latency
+// mq_linear on a single layer is latency- rather than bandwidth-bound for Llama-sized
+// matrices (a 4096 x 4096 layer at r = 4 is 8 MB: one microsecond of HBM time), so the
+// single-layer entry point uses a launch shaped for the shortest dependency chain instead of
+// the streaming schedule above: one workgroup per (row block, K slice); its W waves take the
+// slice's groups round-robin (all their loads are in flight at once), add their lane sums up
+// through LDS in wave order, and -- only if K is cut into KS > 1 slices -- hand over to the
+// last-arriving slice through KS slots (same deterministic protocol as the stack kernel, with
+// KS <= 8 contributors instead of up to G).
+template <int R, int M>
+__global__ __launch_bounds__(1024) void linear_rb_kernel(const LayerDesc L, const int KS, float *part, int32_t *cnt) {
+    __shared__ float red[16][M][64];
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6, W = blockDim.x >> 6;
+    const int rb = blockIdx.x / KS, ks = blockIdx.x - rb * KS;
+    const int g_lo = (int)((int64_t)ks * L.G / KS), g_hi = (int)((int64_t)(ks + 1) * L.G / KS);
+    float yacc[M];
+#pragma unroll
+    for (int m = 0; m < M; ++m) yacc[m] = 0.f;
+    int g = g_lo + w;
+    if (g < g_hi) {
+        TileRegs<R> cur, nxt;
+        load_tile<R>(cur, L, rb * L.G + g, lane);
+        while (true) {
+            const int g2 = g + W;
+            if (g2 < g_hi) load_tile<R>(nxt, L, rb * L.G + g2, lane);
+            tile_math<R, M>(cur, L, g, lane, yacc);
+            if (g2 >= g_hi) break;
+            cur = nxt;
+            g = g2;
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < M; ++m) red[w][m][lane] = yacc[m];
+    __syncthreads();
+    if (w != 0) return;
+    float tot[M];
+#pragma unroll
+    for (int m = 0; m < M; ++m) {
+        tot[m] = red[0][m][lane];
+        for (int i = 1; i < W; ++i) tot[m] += red[i][m][lane];
+    }
+    const int row = rb * kRowBlock + lane;
+    if (KS > 1) {
+        float MQ_GLOBAL *mine = gl(part + ((size_t)blockIdx.x * M) * 64 + lane);
+#pragma unroll
+        for (int m = 0; m < M; ++m) __hip_atomic_store(mine + m * 64, tot[m], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // the write-through stores must have been acknowledged before the counter moves
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        int old = 0;
+        if (lane == 0) old = __hip_atomic_fetch_add(gl(cnt + rb), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        old = __builtin_amdgcn_readfirstlane(old);
+        if (old != KS - 1) return;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        const float MQ_GLOBAL *src = gl(part + ((size_t)rb * KS * M) * 64 + lane);
+        float v[8][M];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int m = 0; m < M; ++m)
+                v[i][m] = __hip_atomic_load(src + ((size_t)(i < KS ? i : KS - 1) * M + m) * 64, __ATOMIC_RELAXED,
+                                            __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            tot[m] = v[0][m];
+#pragma unroll
+            for (int i = 1; i < 8; ++i)
+                if (i < KS) tot[m] += v[i][m];
+        }
+        if (lane == 0) __hip_atomic_store(gl(cnt + rb), 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+#pragma unroll
+    for (int m = 0; m < M; ++m)
+        if (row < L.N) gl(L.y)[(size_t)m * L.N + row] = (_Float16)tot[m];
+}
+
+// Launch shape, from sweeps on Llama-2-7B / Llama-3-70B shapes (cold weights): enough K slices
+// that (a) there are >= 256 workgroups when there are few row blocks and (b) no wave owns more
+// than about two tiles; at most 8 slices, each at least 4 groups long.
+static int pick_k_slices(const LayerDesc &L) {
+    const int cover = L.RB >= 128 ? 1 : (256 + L.RB - 1) / L.RB;
+    const int depth = (L.G + 31) / 32;
+    int ks = cover > depth ? cover : depth;
+    if (ks > 8) ks = 8;
+    while (ks > 1 && L.G / ks < 4) --ks;
+    return ks < 1 ? 1 : ks;
+}
+
+template <int R, int M>
+static hipError_t launch_linear_rb_rm(const LayerDesc &L, float *part, int32_t *cnt, hipStream_t s) {
+    const int KS = pick_k_slices(L);
+    const int per_block = (L.G + KS - 1) / KS;
+    const int W = (per_block >= 24 || (KS == 1 && per_block >= 12)) ? 16 : per_block >= 6 ? 8 : 4;
+    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
+    hipLaunchKernelGGL((linear_rb_kernel<R, M>), dim3((unsigned)(L.RB * KS)), dim3(64 * W), 0, s, L, KS, part, cnt);
+    return hipGetLastError();
+}
+template <int M> static hipError_t launch_linear_rb_m(const LayerDesc &L, float *part, int32_t *cnt, hipStream_t s) {
+    switch (L.r) {
+        case 2: return launch_linear_rb_rm<2, M>(L, part, cnt, s);
+        case 3: return launch_linear_rb_rm<3, M>(L, part, cnt, s);
+        case 4: return launch_linear_rb_rm<4, M>(L, part, cnt, s);
+        case 6: return launch_linear_rb_rm<6, M>(L, part, cnt, s);
+        case 8: return launch_linear_rb_rm<8, M>(L, part, cnt, s);
+    }
+    return hipErrorInvalidValue;
+}
+// The low-latency shape pays off while a wave owns few tiles; big layers stream better under
+// the persistent schedule.  Slots needed: RB * KS * M * 64 floats (KS <= 8).
+bool linear_rb_fits(const LayerDesc &L, size_t part_bytes) {
+    if ((int64_t)L.RB * L.G > 12288) return false;
+    return (size_t)L.RB * 8 * (size_t)L.M * 64 * sizeof(float) <= part_bytes;
+}
+hipError_t launch_linear_rb(const LayerDesc &L, float *part, int32_t *cnt, hipStream_t s) {
+    switch (L.M) {
+        case 1: return launch_linear_rb_m<1>(L, part, cnt, s);
+        case 2: return launch_linear_rb_m<2>(L, part, cnt, s);
+        case 3: return launch_linear_rb_m<3>(L, part, cnt, s);
+        case 4: return launch_linear_rb_m<4>(L, part, cnt, s);
+    }
+    return hipErrorInvalidValue;
+}
+
 template <int M> static int resident_waves() {
     static int cached = 0;
     if (cached) return cached;
