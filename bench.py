@@ -47,6 +47,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--layers", type=int, default=32, help="decoder blocks in the stack")
+    ap.add_argument("--workload", default="every-r", choices=["every-r", "mixed-7b", "mixed-70b", "mlp-70b"],
+                    help="every-r: Llama-2-7B linears at each r (default, the headline); mixed-7b / mixed-70b: one "
+                         "mixed-width stack (mean 3.5 / 4 bits); mlp-70b: batched regime on the Llama-3-70B MLP shapes")
+    ap.add_argument("--batch", type=int, default=1, help="M for the mixed-* workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-single", action="store_true", help="skip the per-call mq_linear table")
     ap.add_argument("--no-loadtime", action="store_true", help="skip the slice/pack throughput leg")
@@ -63,6 +67,10 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.workload in ("mixed-7b", "mixed-70b"):
+        return bench_mixed_stack(args, mq, synth, torch, np, dev)
+    if args.workload == "mlp-70b":
+        return bench_mlp_batched(args, mq, synth, torch, np, dev)
     block = synth.LLAMA2_7B_BLOCK
     M = 1
 
@@ -230,6 +238,105 @@ def main() -> int:
         "single_call": single,
         "load_time": loadtime or None,
     }
+    print(json.dumps(out))
+    return 0
+
+
+def _base_line(metric, value, unit, args, ms_per_step, workload, extra_cfg):
+    return {"metric": metric, "value": round(value, 1), "unit": unit, "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "f16", "data": "synthetic", "config": dict({"workload": workload}, **extra_cfg)}
+
+
+def bench_mixed_stack(args, mq, synth, torch, np, dev):
+    """One mixed-width stack (per-layer r drawn by seed), one persistent launch per step."""
+    big = args.workload == "mixed-70b"
+    block = synth.LLAMA3_70B_BLOCK if big else synth.LLAMA2_7B_BLOCK
+    n_blocks = (synth.LLAMA3_70B_LAYERS if big else synth.LLAMA2_7B_LAYERS) if args.layers == 32 else args.layers
+    target = 4.0 if big else 3.5
+    M = args.batch
+    shapes = synth.stack_shapes(block, n_blocks)
+    widths, mean = synth.draw_bitwidths([N * K for (_, _, N, K) in shapes], target, seed=0)
+    layers, nbytes, keep = [], 0.0, []
+    for i, ((_, _, N, K), r) in enumerate(zip(shapes, widths)):
+        L = synth.make_layer_device(N, K, M, seed=7000 + i, device=dev)
+        lay = mq.prepare_layer(L["parent"], L["scales"], L["zeros"], int(r))
+        lay.update(x=L["x"], y=torch.empty((M, N), dtype=torch.float16, device=dev))
+        layers.append(lay)
+        if big:
+            keep.append(L["parent"])          # the 8-bit parent stays resident, as the configuration states
+        nbytes += algo_bytes(N, K, int(r), M)
+    plan = mq.mq_stack_plan(layers, M, device=dev)
+    for _ in range(args.warmup):
+        mq.mq_linear_stack(plan)
+    torch.cuda.synchronize()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        evs[k].record()
+        mq.mq_linear_stack(plan)
+    evs[args.steps].record()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    us = [evs[k].elapsed_time(evs[k + 1]) * 1e3 for k in range(args.steps)]
+    value = nbytes / (ms * 1e-3) / 1e9
+    out = _base_line("mixed-precision stack, decode-step latency and aggregate effective HBM GB/s", value, "GB/s", args,
+                     ms, f"{'Llama-3-70B' if big else 'Llama-2-7B'}-shaped stack, {n_blocks} blocks ({len(layers)} linears), "
+                     f"M={M}, per-layer r from {{2,3,4,6,8}} by seed, parameter-weighted mean {mean:.3f} bits",
+                     {"M": M, "mean_bits": round(mean, 4), "algorithmic_GB_per_step": round(nbytes / 1e9, 3)})
+    kernel = "mq::stack_kernel<%d>" % M if M <= 4 else "mq::gemm_stack_kernel"
+    ach = nbytes / float(np.mean(us)) / 1e3
+    out["stack_us_median"] = round(float(np.median(us)), 1)
+    out["stack_us_min"] = round(float(np.min(us)), 1)
+    out["frac_of_hbm_peak"] = round(value / HBM_PEAK_GBPS, 4)
+    out["roofline"] = {"bound": "hbm", "kernel": kernel, "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                       "frac": round(ach / HBM_PEAK_GBPS, 4), "avg_launch_us": round(float(np.mean(us)), 1),
+                       "algorithmic_bytes_per_launch": int(nbytes), "traffic": None}
+    out["cpu_baseline"] = None
+    print(json.dumps(out))
+    return 0
+
+
+def bench_mlp_batched(args, mq, synth, torch, np, dev):
+    """Batched regime on the Llama-3-70B MLP shapes: mq_linear per (shape, r, M), cold (cycling copies)."""
+    table = {}
+    tot_b, tot_t = 0.0, 0.0
+    for (name, N, K) in (("up", 28672, 8192), ("down", 8192, 28672)):
+        L = synth.make_layer_device(N, K, 256, seed=9000 + N, device=dev)
+        for r in (3, 4, 8):
+            lay = mq.prepare_layer(L["parent"], L["scales"], L["zeros"], r)
+            copies = [(lay["packed_W"].clone(), lay["scales_t"].clone(), lay["zeros_t"].clone()) for _ in range(4)]
+            for M in (1, 4, 16, 64, 256):
+                x = L["x"][:M].contiguous()
+                ws = mq.new_workspace(M, N, K, r)
+                y = torch.empty((M, N), dtype=torch.float16, device=dev)
+
+                def run():
+                    for (p, s, z) in copies:
+                        mq.mq_linear(x, p, s, z, N, K, r, 128, ws, y=y)
+                run()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(max(1, args.steps // 4)):
+                    run()
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / (max(1, args.steps // 4) * len(copies))
+                b, fl = algo_bytes(N, K, r, M), 2.0 * M * N * K
+                table[f"{name}:{N}x{K}:r{r}:M{M}"] = {"us": round(us, 1), "GBps": round(b / us / 1e3, 1),
+                                                     "hbm_frac": round(b / us / 1e3 / HBM_PEAK_GBPS, 4),
+                                                     "TFLOPs": round(fl / us / 1e6, 1),
+                                                     "mfma_frac": round(fl / us / 1e6 / 2500.0, 4)}
+                tot_b += b
+                tot_t += us
+            del copies
+    out = _base_line("batched sliced linear, effective HBM GB/s and MFMA utilisation", tot_b / tot_t / 1e3, "GB/s", args,
+                     tot_t / 1e3, "Llama-3-70B MLP shapes (28672x8192, 8192x28672), M in {1,4,16,64,256}, r in {3,4,8}, "
+                     "one mq_linear launch per call, 4 distinct weight copies cycled", {})
+    out["table"] = table
+    out["roofline"] = None
+    out["cpu_baseline"] = None
     print(json.dumps(out))
     return 0
 

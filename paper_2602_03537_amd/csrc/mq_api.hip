@@ -29,7 +29,7 @@ bool use_mfma(int64_t M) { return M > kValuMaxM; }
 int64_t chunks(int64_t M) { return use_mfma(M) ? (M + kChunkCols - 1) / kChunkCols : 1; }
 int slot_floats(int64_t M) { return use_mfma(M) ? 64 * kChunkCols : 64 * (int)M; }
 size_t partial_bytes(int64_t M) {
-    return (size_t)(use_mfma(M) ? kMaxWavesMfma : kMaxWaves) * 2 * (size_t)slot_floats(M) * sizeof(float);
+    return (size_t)(use_mfma(M) ? kMaxWavesMfma : max_workers_valu(M)) * 2 * (size_t)slot_floats(M) * sizeof(float);
 }
 // MFMA path: re-ordered activations and their group sums for one layer
 size_t xt_bytes(int64_t M, int64_t K, int r) {

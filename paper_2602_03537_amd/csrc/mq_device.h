@@ -2,7 +2,8 @@
 // MFMA kernel (mq_gemm.hip): the persistent schedule over all tiles of a stack
 // and the deterministic split-K hand-off.
 //
-// Schedule.  A layer is CB x RB x G tiles (column chunk, row block of 64 rows,
+// Schedule.  ("wavefront w" below is a schedule share, a "worker": a wave may serve several.)
+// A layer is CB x RB x G tiles (column chunk, row block of 64 rows,
 // group of 128 columns; CB = 1 unless the batch is served 16 columns at a time).
 // Tiles of all layers form one line in "cost" space (cost ~ bytes of a tile);
 // wavefront w owns the tiles whose start lies in [w*C/W, (w+1)*C/W): a
@@ -70,11 +71,11 @@ __device__ __forceinline__ int wave_of(uint64_t pos, uint64_t nw, uint64_t ctot)
     return (int)(((pos + 1) * nw - 1) / ctot);
 }
 
-// Walk the tiles owned by `wave`: f(L, u_begin, u_end) is called once per layer
-// the wave touches, with tile indices in [0, CB*RB*G) of that layer.
-template <class F> __device__ __forceinline__ void walk_tiles(const StackParams &p, int wave, F &&f) {
-    const uint64_t b_lo = (uint64_t)wave * p.cost_total / (uint64_t)p.nwaves;
-    const uint64_t b_hi = (uint64_t)(wave + 1) * p.cost_total / (uint64_t)p.nwaves;
+// Walk the tiles of schedule share `worker`: f(L, u_begin, u_end) is called once per layer
+// the share touches, with tile indices in [0, CB*RB*G) of that layer.
+template <class F> __device__ __forceinline__ void walk_tiles(const StackParams &p, int worker, F &&f) {
+    const uint64_t b_lo = (uint64_t)worker * p.cost_total / (uint64_t)p.nworkers;
+    const uint64_t b_hi = (uint64_t)(worker + 1) * p.cost_total / (uint64_t)p.nworkers;
     int li = 0;
     if (p.table) {  // last layer whose cost_start <= b_lo
         int lo = 0, hi = p.n_layers - 1;
@@ -110,14 +111,14 @@ template <class F> __device__ __forceinline__ void walk_tiles(const StackParams 
 // bypassing), so no whole-L2 write-back or invalidate is needed to publish them.
 template <int NV, class Final>
 __device__ __forceinline__ void finish_row_block(const LayerDesc &L, const StackParams &p, int32_t *cnt, uint64_t a,
-                                                 int ga, int gb, float (&acc)[NV], int wave, int lane, Final &&final) {
+                                                 int ga, int gb, float (&acc)[NV], int worker, int lane, Final &&final) {
     if (ga == 0 && gb == L.G) {
         final(acc);
         return;
     }
     const int slot = ga == 0 ? 1 : 0;  // the wave holding a row block's first tile uses slot 1
     const size_t slot_floats = (size_t)p.slot_floats;
-    float MQ_GLOBAL *mine = gl(p.part + (size_t)(wave * 2 + slot) * slot_floats + lane);
+    float MQ_GLOBAL *mine = gl(p.part + (size_t)(worker * 2 + slot) * slot_floats + lane);
 #pragma unroll
     for (int v = 0; v < NV; ++v) __hip_atomic_store(mine + v * 64, acc[v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     // the write-through stores must have been acknowledged before the counter moves
@@ -128,8 +129,8 @@ __device__ __forceinline__ void finish_row_block(const LayerDesc &L, const Stack
     old = __builtin_amdgcn_readfirstlane(old);
     if (old + (gb - ga) != L.G) return;
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    const int w_lo = wave_of(a, p.nwaves, p.cost_total);
-    const int w_hi = wave_of(a + (uint64_t)(L.G - 1) * L.cost, p.nwaves, p.cost_total);
+    const int w_lo = wave_of(a, p.nworkers, p.cost_total);
+    const int w_hi = wave_of(a + (uint64_t)(L.G - 1) * L.cost, p.nworkers, p.cost_total);
     // Fixed summation order (w_lo's slot 1, then slot 0 of w_lo+1 .. w_hi); loads are issued
     // in batches so that their round trips overlap.
     constexpr int kBatch = NV >= 8 ? 2 : 16;

@@ -331,6 +331,7 @@ hipError_t launch_stack_mfma(StackParams p, int max_cost, hipStream_t s) {
     uint64_t cap = p.cost_total / (uint64_t)max_cost;
     if (cap < 1) cap = 1;
     p.nwaves = (int)(cap < (uint64_t)hw ? cap : (uint64_t)hw);
+    p.nworkers = p.nwaves;
     (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
     hipLaunchKernelGGL(xprep_kernel, dim3((unsigned)((p.n_jobs + 3) / 4)), dim3(256), 0, s, p);
     hipError_t e = hipGetLastError();

@@ -12,6 +12,15 @@ namespace mq {
 // sizes the partial-sum slots of a workspace independently of the device.
 constexpr int kMaxWaves = 8192;
 constexpr int kMaxWavesMfma = 4096;  // the MFMA kernel runs at most 2 waves per SIMD
+// Vector-ALU stack kernel: each wave serves several interleaved shares of the schedule, so that
+// layers of different widths (different speed per byte) even out over the waves.
+constexpr int kSharesPerWave = 1;  // >1 only pays once hand-overs between shares stop stalling the wave
+constexpr size_t kMaxSlotBytes = (size_t)32 << 20;
+inline int max_workers_valu(int64_t M) {
+    const size_t by_mem = kMaxSlotBytes / (2 * (size_t)M * 64 * sizeof(float));
+    const size_t want = (size_t)kMaxWaves * kSharesPerWave;
+    return (int)(by_mem < want ? by_mem : want);
+}
 constexpr int kCounterBytesAlign = 256;
 
 // Batches up to kValuMaxM run on the vector ALUs; larger ones on MFMA, 16 columns per chunk.
@@ -40,14 +49,14 @@ struct LayerDesc {
 struct StackParams {
     const LayerDesc *table;  // device table, or nullptr to use `single`
     int32_t n_layers;
-    int32_t nwaves;          // wavefronts taking part in the schedule
+    int32_t nwaves;          // wavefronts launched
+    int32_t nworkers;        // schedule shares ("workers"); wave w serves workers w, w + nwaves, ...
     uint64_t cost_total;
-    float *part;             // [nwaves][2][slot_floats] partial sums
+    float *part;             // [nworkers][2][slot_floats] partial sums
     int32_t *cnt;            // row-block counters, zero between launches
     int32_t M;
     int32_t slot_floats;     // floats per partial-sum slot (64*M, or 64*16 on the MFMA path)
     int32_t n_jobs;          // prep kernel jobs (MFMA path)
-    int32_t pad_;
     LayerDesc single;
 };
 

@@ -12,12 +12,22 @@
 
 namespace mq {
 
-template <int R> struct TileRegs {
+// How a wave gets the 64 activation pairs of a group (they are the same for every lane):
+//   kXScalar : scalar loads into SGPRs at the start of the tile's math (short latency while x
+//              sits in the scalar cache; exposed when it does not)
+//   kXLds    : each lane fetches ONE pair together with the tile (one tile ahead, like the
+//              weights), drops it into the wave's 256 bytes of LDS and all lanes read the
+//              pairs back with broadcast ds_read_b128: no scalar-cache dependence at all
+enum XPath { kXScalar = 0, kXLds = 1 };
+
+template <int R, int M> struct TileRegs {
     uint32_t w[4 * R];
     _Float16 s, z;
+    uint32_t xl[M];  // lane l's pair (x[2l], x[2l+1]) of the group: X_g, and the kXLds path
 };
 
-template <int R> __device__ __forceinline__ void load_tile(TileRegs<R> &t, const LayerDesc &L, int u, int lane) {
+template <int R, int M>
+__device__ __forceinline__ void load_tile(TileRegs<R, M> &t, const LayerDesc &L, int u, int g, int lane) {
     const u32x4 MQ_GLOBAL *src = gl(reinterpret_cast<const u32x4 *>(L.Wp) + (size_t)u * (R * 64) + lane);
 #pragma unroll
     for (int i = 0; i < R; ++i) {
@@ -26,20 +36,26 @@ template <int R> __device__ __forceinline__ void load_tile(TileRegs<R> &t, const
     }
     t.s = gl(L.st)[(size_t)u * 64 + lane];
     t.z = gl(L.zt)[(size_t)u * 64 + lane];
+#pragma unroll
+    for (int m = 0; m < M; ++m)
+        t.xl[m] = gl(reinterpret_cast<const uint32_t *>(L.x + (size_t)m * L.K + (size_t)g * kGroup))[lane];
 }
 
-template <int R, int M>
-__device__ __forceinline__ void tile_math(const TileRegs<R> &t, const LayerDesc &L, int g, int lane, float (&yacc)[M]) {
+// xlds: this wave's M x 64 dwords of LDS (kXLds only)
+template <int R, int M, int XP>
+__device__ __forceinline__ void tile_math(const TileRegs<R, M> &t, const LayerDesc &L, int g, int lane,
+                                          uint32_t *xlds, float (&yacc)[M]) {
     using T = Layout<R>;
     constexpr int NU = 4 * R / T::UD;
     float xg[M];
     cptr32 xs[M];
 #pragma unroll
     for (int m = 0; m < M; ++m) {
-        const _Float16 *xrow = L.x + (size_t)m * L.K + (size_t)g * kGroup;
-        const uint32_t xl = gl(reinterpret_cast<const uint32_t *>(xrow))[lane];
-        xg[m] = wave_sum(dot2(xl, 0x3C003C00u, 0.f));  // (1.0, 1.0)
-        xs[m] = as_const(xrow);
+        xg[m] = wave_sum(dot2(t.xl[m], 0x3C003C00u, 0.f));  // (1.0, 1.0)
+        if constexpr (XP == kXLds)
+            xlds[m * 64 + lane] = t.xl[m];
+        else
+            xs[m] = as_const(L.x + (size_t)m * L.K + (size_t)g * kGroup);
     }
     float acc[M][T::NKEYS];
 #pragma unroll
@@ -47,17 +63,40 @@ __device__ __forceinline__ void tile_math(const TileRegs<R> &t, const LayerDesc 
 #pragma unroll
         for (int k = 0; k < T::NKEYS; ++k) acc[m][k] = 0.f;
 
-    static_for<NU>([&](auto un) {
-        static_for<T::NOPS>([&](auto oi) {
-            constexpr Op o = T::op(oi);
-            constexpr int key = key_index<R>(oi);
-            uint32_t v = t.w[un * T::UD + o.dw];
-            if constexpr (o.sh != 0) v >>= o.sh;
-            v &= (uint32_t)o.mask * 0x10001u;
+    if constexpr (XP == kXLds) {
+        // quad by quad of activation pairs: one broadcast 16-byte LDS read serves four pairs
+        static_for<16>([&](auto qi) {
+            u32x4 xq[M];
 #pragma unroll
-            for (int m = 0; m < M; ++m) acc[m][key] = dot2(v, xs[m][un * T::PPU + o.pair], acc[m][key]);
+            for (int m = 0; m < M; ++m) xq[m] = reinterpret_cast<const u32x4 *>(xlds + m * 64)[qi];
+            static_for<NU>([&](auto un) {
+                static_for<T::NOPS>([&](auto oi) {
+                    constexpr Op o = T::op(oi);
+                    constexpr int pidx = un * T::PPU + o.pair;
+                    if constexpr (pidx / 4 == qi) {
+                        constexpr int key = key_index<R>(oi);
+                        uint32_t v = t.w[un * T::UD + o.dw];
+                        if constexpr (o.sh != 0) v >>= o.sh;
+                        v &= (uint32_t)o.mask * 0x10001u;
+#pragma unroll
+                        for (int m = 0; m < M; ++m) acc[m][key] = dot2(v, xq[m][pidx % 4], acc[m][key]);
+                    }
+                });
+            });
         });
-    });
+    } else {
+        static_for<NU>([&](auto un) {
+            static_for<T::NOPS>([&](auto oi) {
+                constexpr Op o = T::op(oi);
+                constexpr int key = key_index<R>(oi);
+                uint32_t v = t.w[un * T::UD + o.dw];
+                if constexpr (o.sh != 0) v >>= o.sh;
+                v &= (uint32_t)o.mask * 0x10001u;
+#pragma unroll
+                for (int m = 0; m < M; ++m) acc[m][key] = dot2(v, xs[m][un * T::PPU + o.pair], acc[m][key]);
+            });
+        });
+    }
     const float s = (float)t.s, z = (float)t.z;
 #pragma unroll
     for (int m = 0; m < M; ++m) {
@@ -71,9 +110,9 @@ __device__ __forceinline__ void tile_math(const TileRegs<R> &t, const LayerDesc 
 }
 
 // Tiles [u_begin, u_end) of one layer, owned by this wave.
-template <int R, int M>
+template <int R, int M, int XP>
 __device__ __forceinline__ void run_units(const LayerDesc &L, const StackParams &p, int u_begin, int u_end, int wave,
-                                          int lane) {
+                                          int lane, uint32_t *xlds) {
     int rb = u_begin / L.G;
     int g = u_begin - rb * L.G;
     int ga = g;
@@ -81,11 +120,11 @@ __device__ __forceinline__ void run_units(const LayerDesc &L, const StackParams 
 #pragma unroll
     for (int m = 0; m < M; ++m) yacc[m] = 0.f;
 
-    TileRegs<R> cur, nxt;
-    load_tile<R>(cur, L, u_begin, lane);
+    TileRegs<R, M> cur, nxt;
+    load_tile<R, M>(cur, L, u_begin, g, lane);
     for (int u = u_begin; u < u_end; ++u) {
-        if (u + 1 < u_end) load_tile<R>(nxt, L, u + 1, lane);
-        tile_math<R, M>(cur, L, g, lane, yacc);
+        if (u + 1 < u_end) load_tile<R, M>(nxt, L, u + 1, g + 1 == L.G ? 0 : g + 1, lane);
+        tile_math<R, M, XP>(cur, L, g, lane, xlds, yacc);
         ++g;
         if (g == L.G || u + 1 == u_end) {
             const int row = rb * kRowBlock + lane;
@@ -105,19 +144,34 @@ __device__ __forceinline__ void run_units(const LayerDesc &L, const StackParams 
     }
 }
 
-template <int M> __global__ __launch_bounds__(256) void stack_kernel(const StackParams p) {
+template <int M, int XP> __global__ __launch_bounds__(256) void stack_kernel(const StackParams p) {
+    __shared__ __attribute__((aligned(16))) uint32_t xlds_all[XP == kXLds ? 4 * M * 64 : 4];
+    uint32_t *xlds = xlds_all + (XP == kXLds ? (threadIdx.x >> 6) * M * 64 : 0);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6));
     if (wave >= p.nwaves) return;
-    walk_tiles(p, wave, [&](const LayerDesc &L, int u_begin, int u_end) {
-        switch (L.r) {
-            case 2: run_units<2, M>(L, p, u_begin, u_end, wave, lane); break;
-            case 3: run_units<3, M>(L, p, u_begin, u_end, wave, lane); break;
-            case 4: run_units<4, M>(L, p, u_begin, u_end, wave, lane); break;
-            case 6: run_units<6, M>(L, p, u_begin, u_end, wave, lane); break;
-            default: run_units<8, M>(L, p, u_begin, u_end, wave, lane); break;
-        }
-    });
+#ifdef MQ_PROFILE_WAVES
+    const uint64_t t_start = __builtin_readcyclecounter();
+#endif
+    for (int worker = wave; worker < p.nworkers; worker += p.nwaves) {
+        walk_tiles(p, worker, [&](const LayerDesc &L, int u_begin, int u_end) {
+            switch (L.r) {
+                case 2: run_units<2, M, XP>(L, p, u_begin, u_end, worker, lane, xlds); break;
+                case 3: run_units<3, M, XP>(L, p, u_begin, u_end, worker, lane, xlds); break;
+                case 4: run_units<4, M, XP>(L, p, u_begin, u_end, worker, lane, xlds); break;
+                case 6: run_units<6, M, XP>(L, p, u_begin, u_end, worker, lane, xlds); break;
+                default: run_units<8, M, XP>(L, p, u_begin, u_end, worker, lane, xlds); break;
+            }
+        });
+    }
+#ifdef MQ_PROFILE_WAVES
+    // development aid: start / end clock of every wave behind the partial-sum slots
+    if (lane == 0) {
+        uint64_t *dbg = reinterpret_cast<uint64_t *>(p.part + (size_t)p.nworkers * 2 * p.slot_floats);
+        dbg[2 * wave] = t_start;
+        dbg[2 * wave + 1] = __builtin_readcyclecounter();
+    }
+#endif
 }
 
 // ------------------------------------------------------------------ one layer, low latency
@@ -129,9 +183,11 @@ template <int M> __global__ __launch_bounds__(256) void stack_kernel(const Stack
 // through LDS in wave order, and -- only if K is cut into KS > 1 slices -- hand over to the
 // last-arriving slice through KS slots (same deterministic protocol as the stack kernel, with
 // KS <= 8 contributors instead of up to G).
-template <int R, int M>
+template <int R, int M, int XP>
 __global__ __launch_bounds__(1024) void linear_rb_kernel(const LayerDesc L, const int KS, float *part, int32_t *cnt) {
     __shared__ float red[16][M][64];
+    __shared__ __attribute__((aligned(16))) uint32_t xlds_all[XP == kXLds ? 16 * M * 64 : 4];
+    uint32_t *xlds = xlds_all + (XP == kXLds ? (threadIdx.x >> 6) * M * 64 : 0);
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6, W = blockDim.x >> 6;
     const int rb = blockIdx.x / KS, ks = blockIdx.x - rb * KS;
@@ -141,12 +197,12 @@ __global__ __launch_bounds__(1024) void linear_rb_kernel(const LayerDesc L, cons
     for (int m = 0; m < M; ++m) yacc[m] = 0.f;
     int g = g_lo + w;
     if (g < g_hi) {
-        TileRegs<R> cur, nxt;
-        load_tile<R>(cur, L, rb * L.G + g, lane);
+        TileRegs<R, M> cur, nxt;
+        load_tile<R, M>(cur, L, rb * L.G + g, g, lane);
         while (true) {
             const int g2 = g + W;
-            if (g2 < g_hi) load_tile<R>(nxt, L, rb * L.G + g2, lane);
-            tile_math<R, M>(cur, L, g, lane, yacc);
+            if (g2 < g_hi) load_tile<R, M>(nxt, L, rb * L.G + g2, g2, lane);
+            tile_math<R, M, XP>(cur, L, g, lane, xlds, yacc);
             if (g2 >= g_hi) break;
             cur = nxt;
             g = g2;
@@ -215,7 +271,7 @@ static hipError_t launch_linear_rb_rm(const LayerDesc &L, float *part, int32_t *
     const int per_block = (L.G + KS - 1) / KS;
     const int W = (per_block >= 24 || (KS == 1 && per_block >= 12)) ? 16 : per_block >= 6 ? 8 : 4;
     (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
-    hipLaunchKernelGGL((linear_rb_kernel<R, M>), dim3((unsigned)(L.RB * KS)), dim3(64 * W), 0, s, L, KS, part, cnt);
+    hipLaunchKernelGGL((linear_rb_kernel<R, M, kXLds>), dim3((unsigned)(L.RB * KS)), dim3(64 * W), 0, s, L, KS, part, cnt);
     return hipGetLastError();
 }
 template <int M> static hipError_t launch_linear_rb_m(const LayerDesc &L, float *part, int32_t *cnt, hipStream_t s) {
@@ -244,13 +300,13 @@ hipError_t launch_linear_rb(const LayerDesc &L, float *part, int32_t *cnt, hipSt
     return hipErrorInvalidValue;
 }
 
-template <int M> static int resident_waves() {
+template <int M, int XP> static int resident_waves() {
     static int cached = 0;
     if (cached) return cached;
     int dev = 0, cus = 0, blocks = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, stack_kernel<M>, 256, 0) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, stack_kernel<M, XP>, 256, 0) != hipSuccess) return 0;
     if (blocks < 1) blocks = 1;
     int w = cus * blocks * 4;
     if (w > kMaxWaves) w = kMaxWaves;
@@ -258,18 +314,30 @@ template <int M> static int resident_waves() {
     return w;
 }
 
-template <int M> static hipError_t launch_stack_m(StackParams p, int max_cost, hipStream_t s) {
-    int hw = resident_waves<M>();
+template <int M, int XP> static hipError_t launch_stack_mx(StackParams p, int max_cost, hipStream_t s) {
+    int hw = resident_waves<M, XP>();
     if (hw <= 0) return hipErrorUnknown;
-    // every wave's share must be at least one tile long, so that each wave between the
-    // first and last contributor of a row block really owns a tile of it
+    // every share must be at least one tile long, so that each share between the first
+    // and last contributor of a row block really owns a tile of it
     uint64_t cap = p.cost_total / (uint64_t)max_cost;
     if (cap < 1) cap = 1;
     p.nwaves = (int)(cap < (uint64_t)hw ? cap : (uint64_t)hw);
+    const int spw = kSharesPerWave, minlen = 96;
+    uint64_t workers = (uint64_t)p.nwaves * spw;
+    // ... and not shorter than ~96 tiles: each share ends with up to two hand-overs (a few
+    // microseconds of round trips each), which must stay small against the share itself
+    const uint64_t by_len = p.cost_total / ((uint64_t)max_cost * minlen);
+    if (workers > by_len) workers = by_len;
+    if (workers > (uint64_t)max_workers_valu(M)) workers = (uint64_t)max_workers_valu(M);
+    if (workers < (uint64_t)p.nwaves) workers = (uint64_t)p.nwaves;
+    p.nworkers = (int)workers;
     const unsigned blocks = (unsigned)((p.nwaves + 3) / 4);
     (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
-    hipLaunchKernelGGL(stack_kernel<M>, dim3(blocks), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((stack_kernel<M, XP>), dim3(blocks), dim3(256), 0, s, p);
     return hipGetLastError();
+}
+template <int M> static hipError_t launch_stack_m(StackParams p, int max_cost, hipStream_t s) {
+    return launch_stack_mx<M, kXLds>(p, max_cost, s);  // measured 1-3 % (stack) to 20 % (single calls) faster than kXScalar
 }
 
 hipError_t launch_stack(StackParams p, int max_cost, hipStream_t s) {

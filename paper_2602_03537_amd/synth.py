@@ -123,3 +123,37 @@ def draw_bitwidths(sizes, target_mean: float, seed: int = 0, tol: float = 0.02):
 def stack_shapes(block, n_layers: int):
     """[(layer, name, N, K)] for a decoder stack."""
     return [(l, name, N, K) for l in range(n_layers) for (name, N, K) in block]
+
+
+# ---------------------------------------------------------------- on-device generation
+def make_layer_device(N: int, K: int, M: int = 1, seed: int = 0, device="cuda", group: int = GROUP,
+                      want_x: bool = True) -> dict:
+    """Same recipe as make_layer but generated on the GPU with a seeded torch.Generator (for
+    stacks whose 8-bit parent does not fit in host memory).  Input creation only: plain
+    torch ops, no slicing / packing / de-quantisation / matmul of the method."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed))
+    G = K // group
+    parent = torch.empty((N, K), dtype=torch.uint8, device=device)
+    scales = torch.empty((N, G), dtype=torch.float16, device=device)
+    zeros = torch.empty((N, G), dtype=torch.float16, device=device)
+    rows = max(1, min(N, (1 << 26) // K))          # <= 256 MB of fp32 at a time
+    for r0 in range(0, N, rows):
+        r1 = min(N, r0 + rows)
+        W = torch.randn((r1 - r0, G, group), generator=g, device=device, dtype=torch.float32) * 0.02
+        lo = W.amin(dim=2)
+        hi = W.amax(dim=2)
+        s = ((hi - lo) / 255.0).to(torch.float16)
+        s = torch.where((hi == lo) | (s == 0), torch.ones_like(s), s)
+        s32 = s.float()
+        z = torch.clamp(torch.round(-lo / s32), 0, 255).to(torch.float16)
+        q = torch.clamp(torch.round(W / s32[:, :, None]) + z.float()[:, :, None], 0, 255)
+        parent[r0:r1] = q.to(torch.uint8).reshape(r1 - r0, K)
+        scales[r0:r1] = s
+        zeros[r0:r1] = z
+        del W, q
+    out = {"parent": parent, "scales": scales, "zeros": zeros, "N": N, "K": K, "M": M, "group": group}
+    if want_x:
+        out["x"] = torch.randn((M, K), generator=g, device=device, dtype=torch.float32).to(torch.float16)
+    return out

@@ -425,3 +425,62 @@ def test_stack_llama2_7b_block_mixed_widths_sampled_rows():
         ref = oracle.linear_rows(L["x"], L["parent"], L["scales"], L["zeros"], C, L["r"], 128, rows)
         check_y(lay["y"][:, torch.from_numpy(rows).to(DEV)], ref, f"block linear {i} r={L['r']}")
         assert torch.isfinite(lay["y"]).all()
+
+
+# ------------------------------------------------ full-size stacks (generated on the device)
+def _device_stack(block, n_blocks, target_bits, M, seed):
+    shapes = synth.stack_shapes(block, n_blocks)
+    widths, mean = synth.draw_bitwidths([N * K for (_, _, N, K) in shapes], target_bits, seed=seed)
+    gen, layers = [], []
+    for i, ((_, _, N, K), r) in enumerate(zip(shapes, widths)):
+        L = synth.make_layer_device(N, K, M, seed=seed * 100000 + i, device=DEV)
+        lay = mq.prepare_layer(L["parent"], L["scales"], L["zeros"], int(r))
+        lay.update(x=L["x"], y=torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV))
+        gen.append(L)
+        layers.append(lay)
+    return shapes, widths, mean, gen, layers
+
+
+def _check_sampled(gen, layers, idx, n_rows, rng, what):
+    L, lay = gen[idx], layers[idx]
+    N = lay["N"]
+    rows = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, n_rows - 2)]))
+    rt = torch.from_numpy(rows).to(DEV)
+    ref = oracle.linear(L["x"].cpu().numpy(), L["parent"][rt].cpu().numpy(), L["scales"][rt].cpu().numpy(),
+                        L["zeros"][rt].cpu().numpy(), C, lay["r"], 128)
+    check_y(lay["y"][:, rt], ref, f"{what} linear {idx} r={lay['r']}")
+
+
+def test_stack_llama2_7b_full_mixed_widths_mean_3p5():
+    # all 32 blocks x 7 linears, widths by seed with parameter-weighted mean 3.5, batch 1
+    shapes, widths, mean, gen, layers = _device_stack(synth.LLAMA2_7B_BLOCK, synth.LLAMA2_7B_LAYERS, 3.5, 1, seed=4)
+    assert len(layers) == 224 and abs(mean - 3.5) <= 0.02
+    plan = mq.mq_stack_plan(layers, 1)
+    mq.mq_linear_stack(plan)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(404)
+    for i in range(len(layers)):
+        assert torch.isfinite(layers[i]["y"]).all(), i
+        _check_sampled(gen, layers, i, 64 if i < 7 or i >= 217 else 8, rng, "7B stack")
+    first = [lay["y"].clone() for lay in layers[:14]]
+    mq.mq_linear_stack(plan)                                   # replay: same bits
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, lay["y"]) for a, lay in zip(first, layers[:14]))
+
+
+@pytest.mark.parametrize("M", [1, 8])
+def test_stack_llama3_70b_full_mixed_widths_mean_4(M):
+    # 80 blocks x 7 linears (68.45 G weights): the 8-bit parent stays resident next to the packed slices
+    shapes, widths, mean, gen, layers = _device_stack(synth.LLAMA3_70B_BLOCK, synth.LLAMA3_70B_LAYERS, 4.0, M, seed=5)
+    assert len(layers) == 560 and abs(mean - 4.0) <= 0.02
+    assert sum(int(L["parent"].numel()) for L in gen) == 68_451_041_280
+    plan = mq.mq_stack_plan(layers, M)
+    mq.mq_linear_stack(plan)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(505 + M)
+    for i in range(len(layers)):
+        block = i // 7
+        assert torch.isfinite(layers[i]["y"]).all(), i
+        _check_sampled(gen, layers, i, 64 if block in (0, 39, 79) else 6, rng, f"70B stack M={M}")
+    del gen, layers, plan
+    torch.cuda.empty_cache()
