@@ -14,7 +14,7 @@ constexpr int kMaxWaves = 8192;
 constexpr int kMaxWavesMfma = 4096;  // the MFMA kernel runs at most 2 waves per SIMD
 // Vector-ALU stack kernel: each wave serves several interleaved shares of the schedule, so that
 // layers of different widths (different speed per byte) even out over the waves.
-constexpr int kSharesPerWave = 1;  // >1 only pays once hand-overs between shares stop stalling the wave
+constexpr int kSharesPerWave = 8;
 constexpr size_t kMaxSlotBytes = (size_t)32 << 20;
 inline int max_workers_valu(int64_t M) {
     const size_t by_mem = kMaxSlotBytes / (2 * (size_t)M * 64 * sizeof(float));

@@ -109,10 +109,19 @@ __device__ __forceinline__ void tile_math(const TileRegs<R, M> &t, const LayerDe
     }
 }
 
-// Tiles [u_begin, u_end) of one layer, owned by this wave.
+// Tiles a wave keeps in flight ahead of the one it is working on.  A wave with one small tile
+// in flight cannot pull more than tile_bytes / memory_latency (1.3 GB/s at r = 2), less than
+// its fair share of HBM once wider layers free bandwidth, so narrow tiles are fetched deeper:
+// about 8 KB per wave in flight at every width.
+template <int R> struct PrefetchDepth {
+    static constexpr int value = R <= 2 ? 4 : R == 3 ? 3 : R <= 6 ? 2 : 1;
+};
+
+// Tiles [u_begin, u_end) of one layer, owned by share `wave`.
 template <int R, int M, int XP>
 __device__ __forceinline__ void run_units(const LayerDesc &L, const StackParams &p, int u_begin, int u_end, int wave,
                                           int lane, uint32_t *xlds) {
+    constexpr int D = PrefetchDepth<R>::value, NB = D + 1;
     int rb = u_begin / L.G;
     int g = u_begin - rb * L.G;
     int ga = g;
@@ -120,27 +129,42 @@ __device__ __forceinline__ void run_units(const LayerDesc &L, const StackParams 
 #pragma unroll
     for (int m = 0; m < M; ++m) yacc[m] = 0.f;
 
-    TileRegs<R, M> cur, nxt;
-    load_tile<R, M>(cur, L, u_begin, g, lane);
-    for (int u = u_begin; u < u_end; ++u) {
-        if (u + 1 < u_end) load_tile<R, M>(nxt, L, u + 1, g + 1 == L.G ? 0 : g + 1, lane);
-        tile_math<R, M, XP>(cur, L, g, lane, xlds, yacc);
-        ++g;
-        if (g == L.G || u + 1 == u_end) {
-            const int row = rb * kRowBlock + lane;
-            finish_row_block<M>(L, p, p.cnt + L.cnt_off + rb, L.cost_start + (uint64_t)rb * L.G * L.cost, ga, g, yacc,
-                                wave, lane, [&](const float(&tot)[M]) {
-#pragma unroll
-                                    for (int m = 0; m < M; ++m)
-                                        if (row < L.N) gl(L.y)[(size_t)m * L.N + row] = (_Float16)tot[m];
-                                });
-            ++rb;
-            g = 0;
-            ga = 0;
-#pragma unroll
-            for (int m = 0; m < M; ++m) yacc[m] = 0.f;
+    // ring of NB tile buffers with compile-time indices (no register copies, which would wait
+    // for the loads); past the end of the run the last tile is fetched again instead of
+    // branching around the loads
+    TileRegs<R, M> buf[NB];
+    int u_pf = u_begin, g_pf = g;
+    auto prefetch = [&](TileRegs<R, M> &t) {
+        load_tile<R, M>(t, L, u_pf, g_pf, lane);
+        if (u_pf + 1 < u_end) {
+            ++u_pf;
+            g_pf = g_pf + 1 == L.G ? 0 : g_pf + 1;
         }
-        cur = nxt;
+    };
+    static_for<D>([&](auto j) { prefetch(buf[j]); });
+    int u = u_begin;
+    while (u < u_end) {
+        static_for<NB>([&](auto j) {
+            if (u >= u_end) return;
+            prefetch(buf[(j + D) % NB]);
+            tile_math<R, M, XP>(buf[j], L, g, lane, xlds, yacc);
+            ++g;
+            ++u;
+            if (g == L.G || u == u_end) {
+                const int row = rb * kRowBlock + lane;
+                finish_row_block<M>(L, p, p.cnt + L.cnt_off + rb, L.cost_start + (uint64_t)rb * L.G * L.cost, ga, g,
+                                    yacc, wave, lane, [&](const float(&tot)[M]) {
+#pragma unroll
+                                        for (int m = 0; m < M; ++m)
+                                            if (row < L.N) gl(L.y)[(size_t)m * L.N + row] = (_Float16)tot[m];
+                                    });
+                ++rb;
+                g = 0;
+                ga = 0;
+#pragma unroll
+                for (int m = 0; m < M; ++m) yacc[m] = 0.f;
+            }
+        });
     }
 }
 
@@ -300,40 +324,45 @@ hipError_t launch_linear_rb(const LayerDesc &L, float *part, int32_t *cnt, hipSt
     return hipErrorInvalidValue;
 }
 
-template <int M, int XP> static int resident_waves() {
-    static int cached = 0;
-    if (cached) return cached;
-    int dev = 0, cus = 0, blocks = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 0;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, stack_kernel<M, XP>, 256, 0) != hipSuccess) return 0;
-    if (blocks < 1) blocks = 1;
-    int w = cus * blocks * 4;
-    if (w > kMaxWaves) w = kMaxWaves;
-    cached = w;
-    return w;
+// blocks (of 4 waves) the device keeps resident per compute unit, and the number of units
+template <int M, int XP> static bool residency(int &cus, int &blocks) {
+    static int c_cus = 0, c_blocks = 0;
+    if (!c_cus) {
+        int dev = 0, a = 0, b = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return false;
+        if (hipDeviceGetAttribute(&a, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&b, stack_kernel<M, XP>, 256, 0) != hipSuccess) return false;
+        if (b < 1) b = 1;
+        while (a * b * 4 > kMaxWaves) --b;
+        c_cus = a;
+        c_blocks = b;
+    }
+    cus = c_cus;
+    blocks = c_blocks;
+    return true;
 }
 
 template <int M, int XP> static hipError_t launch_stack_mx(StackParams p, int max_cost, hipStream_t s) {
-    int hw = resident_waves<M, XP>();
-    if (hw <= 0) return hipErrorUnknown;
+    int cus = 0, blocks = 0;
+    if (!residency<M, XP>(cus, blocks)) return hipErrorUnknown;
+    const int hw = cus * blocks * 4;
     // every share must be at least one tile long, so that each share between the first
     // and last contributor of a row block really owns a tile of it
     uint64_t cap = p.cost_total / (uint64_t)max_cost;
     if (cap < 1) cap = 1;
     p.nwaves = (int)(cap < (uint64_t)hw ? cap : (uint64_t)hw);
-    const int spw = kSharesPerWave, minlen = 96;
-    uint64_t workers = (uint64_t)p.nwaves * spw;
-    // ... and not shorter than ~96 tiles: each share ends with up to two hand-overs (a few
-    // microseconds of round trips each), which must stay small against the share itself
-    const uint64_t by_len = p.cost_total / ((uint64_t)max_cost * minlen);
-    if (workers > by_len) workers = by_len;
-    if (workers > (uint64_t)max_workers_valu(M)) workers = (uint64_t)max_workers_valu(M);
-    if (workers < (uint64_t)p.nwaves) workers = (uint64_t)p.nwaves;
-    p.nworkers = (int)workers;
-    const unsigned blocks = (unsigned)((p.nwaves + 3) / 4);
+    // Several interleaved shares per wave even out layers of different width (a wave serves
+    // shares w, w + nwaves, ...), but every share ends with up to two hand-overs of a few
+    // microseconds, so shares stay at least ~128 tiles long (measured: Llama-2-7B stacks are
+    // best with one share per wave, Llama-3-70B stacks gain 15 % from eight).
+    uint64_t spw = p.cost_total / ((uint64_t)max_cost * 128 * (uint64_t)p.nwaves);  // whole shares per wave
+    if (spw > (uint64_t)kSharesPerWave) spw = kSharesPerWave;
+    while (spw > 1 && spw * (uint64_t)p.nwaves > (uint64_t)max_workers_valu(M)) --spw;
+    if (spw < 1) spw = 1;
+    p.nworkers = (int)(spw * (uint64_t)p.nwaves);
+    const unsigned nblocks = (unsigned)((p.nwaves + 3) / 4);
     (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
-    hipLaunchKernelGGL((stack_kernel<M, XP>), dim3(blocks), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((stack_kernel<M, XP>), dim3(nblocks), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 template <int M> static hipError_t launch_stack_m(StackParams p, int max_cost, hipStream_t s) {
