@@ -43,28 +43,33 @@ template <int R> struct Mfma {
 
 // ------------------------------------------------------------------ activation prep
 // One wave per (layer, chunk, group): writes the B operands of the NMF MFMAs of a tile
-// (16 columns x 8 halves each) and the per-column group sums X_g.
+// (16 columns x 8 halves each) and the per-column group sums X_g.  Branch-free: columns
+// beyond M read column 0 and are masked to zero, all loads are issued before the stores.
 template <int R> __device__ __forceinline__ void xprep_job(const LayerDesc &L, int c, int g, int lane) {
     using T = Layout<R>;
     constexpr int NMF = Mfma<R>::NMF;
     const int m = lane >> 2, j = lane & 3;
     const int col = c * kChunkCols + m;
-    const bool live = col < L.M;
+    const uint32_t live = col < L.M ? 0xFFFFFFFFu : 0u;
     const uint32_t MQ_GLOBAL *xrow =
         gl(reinterpret_cast<const uint32_t *>(L.x + (size_t)(live ? col : 0) * L.K) + (size_t)g * 64);
     uint32_t MQ_GLOBAL *out =
         gl(reinterpret_cast<uint32_t *>(const_cast<uint4 *>(L.xt)) + ((size_t)(c * L.G + g) * NMF) * 64 + lane);
+    uint32_t v[NMF];
     static_for<NMF>([&](auto mf) {
         constexpr int Q = mf / T::NOPS;
         constexpr Op o = T::op(mf % T::NOPS);
         // dword j of the lane's operand = activation pair of unit 4Q+j, field o
-        const uint32_t v = live ? xrow[(4 * Q + j) * T::PPU + o.pair] : 0u;
-        out[mf * 64] = v;
+        v[mf] = xrow[(4 * Q + j) * T::PPU + o.pair];
     });
+    uint32_t q[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) q[i] = xrow[j * 16 + i];
+    static_for<NMF>([&](auto mf) { out[mf * 64] = v[mf] & live; });
     // X_g for column m: lanes 4m..4m+3 each sum a quarter of the group
     float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) s = dot2(live ? xrow[j * 16 + i] : 0u, 0x3C003C00u, s);
+    for (int i = 0; i < 16; ++i) s = dot2(q[i] & live, 0x3C003C00u, s);
     s = dpp_add<0xB1>(s);
     s = dpp_add<0x4E>(s);
     if (j == 0) gl(const_cast<float *>(L.xsum))[(size_t)(c * L.G + g) * kChunkCols + m] = s;
@@ -156,44 +161,72 @@ template <int R> struct GemmCtx {
     }
 };
 
-// One tile: MFMAs key by key (one 32x32 accumulator live at a time), then the per-group
-// scale / zero step.  B comes from LDS stage `stage`.
+// MFMA order of a tile: key by key (so that one 32x32 accumulator is live at a time).
+template <int R> struct MfmaOrder {
+    using T = Layout<R>;
+    static constexpr int NMF = Mfma<R>::NMF;
+    // i-th MFMA in issue order -> index mf = Q * NOPS + oi
+    static constexpr int at(int i) {
+        int n = 0;
+        for (int key = 0; key < T::NKEYS; ++key)
+            for (int mf = 0; mf < NMF; ++mf)
+                if (key_index<R>(mf % T::NOPS) == key) {
+                    if (n == i) return mf;
+                    ++n;
+                }
+        return -1;
+    }
+    static constexpr int key_of(int i) { return key_index<R>(at(i) % T::NOPS); }
+    static constexpr bool last_of_key(int i) { return i + 1 == NMF || key_of(i + 1) != key_of(i); }
+    static constexpr bool first_of_key(int i) { return i == 0 || key_of(i - 1) != key_of(i); }
+};
+
+// One tile: NMF MFMAs, then the per-group scale / zero step.  B comes from LDS stage `stage`,
+// read four MFMAs ahead of its use so that the LDS latency overlaps the previous MFMAs.
 template <int R>
 __device__ __forceinline__ void gemm_tile_math(const GemmCtx<R> &cx, const uint32_t (&w)[4 * R], int stage,
                                                const u32x2 (&s4)[4], const u32x2 (&z4)[4], float xg,
                                                float (&yacc)[16]) {
     using T = Layout<R>;
     using MF = Mfma<R>;
+    using Ord = MfmaOrder<R>;
+    constexpr int kAhead = 4;
     const u32x4 *bsrc = cx.lm.b_live ? reinterpret_cast<const u32x4 *>(cx.lds + stage * kStageBytes) + cx.lm.col
                                      : reinterpret_cast<const u32x4 *>(cx.zero);
     const int bstep = cx.lm.b_live ? 16 : 0;  // u32x4 elements per MFMA block (256 bytes)
+    u32x4 bq[kAhead];                          // ring of B operands in flight
+    static_for<kAhead>([&](auto i) {
+        if constexpr (i < MF::NMF) bq[i] = bsrc[Ord::at(i) * bstep];
+    });
     // field value = digit * 2^(key-24): back to code units, then Eq. 1's rescale 2^(8-r)
     float dsum[16];
-    static_for<T::NKEYS>([&](auto key) {
-        float16_t D;
+    float16_t D;
+    static_for<MF::NMF>([&](auto i) {
+        constexpr int mf = Ord::at(i);
+        constexpr int Q = mf / T::NOPS;
+        constexpr Op o = T::op(mf % T::NOPS);
+        constexpr int key = Ord::key_of(i);
+        if constexpr (Ord::first_of_key(i)) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) D[v] = 0.f;
-        static_for<MF::NMF>([&](auto mf) {
-            constexpr int Q = mf / T::NOPS;
-            constexpr int oi = mf % T::NOPS;
-            constexpr Op o = T::op(oi);
-            if constexpr (key_index<R>(oi) == key) {
-                uint32_t a[4];
+            for (int v = 0; v < 16; ++v) D[v] = 0.f;
+        }
+        uint32_t a[4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    uint32_t v = w[(4 * Q + j) * T::UD + o.dw];
-                    if constexpr (o.sh != 0) v >>= o.sh;
-                    a[j] = v & ((uint32_t)o.mask * 0x10001u);
-                }
-                const u32x4 av = {a[0], a[1], a[2], a[3]};
-                const u32x4 bv = bsrc[mf * bstep];
-                D = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, av),
-                                                           __builtin_bit_cast(half8_t, bv), D, 0, 0, 0);
-            }
-        });
-        const float ck = __builtin_ldexpf(1.f, 24 - T::key(key) + kC - R);
+        for (int j = 0; j < 4; ++j) {
+            uint32_t v = w[(4 * Q + j) * T::UD + o.dw];
+            if constexpr (o.sh != 0) v >>= o.sh;
+            a[j] = v & ((uint32_t)o.mask * 0x10001u);
+        }
+        const u32x4 av = {a[0], a[1], a[2], a[3]};
+        const u32x4 bv = bq[i % kAhead];
+        if constexpr (i + kAhead < MF::NMF) bq[i % kAhead] = bsrc[Ord::at(i + kAhead) * bstep];
+        D = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, av), __builtin_bit_cast(half8_t, bv), D,
+                                                   0, 0, 0);
+        if constexpr (Ord::last_of_key(i)) {
+            const float ck = __builtin_ldexpf(1.f, 24 - T::key(key) + kC - R);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) dsum[v] = key == 0 ? D[v] * ck : fmaf(D[v], ck, dsum[v]);
+            for (int v = 0; v < 16; ++v) dsum[v] = key == 0 ? D[v] * ck : fmaf(D[v], ck, dsum[v]);
+        }
     });
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
@@ -202,12 +235,18 @@ __device__ __forceinline__ void gemm_tile_math(const GemmCtx<R> &cx, const uint3
     }
 }
 
+// Weight tiles a wave keeps in flight ahead of the one it is working on (about 8 KB).
+template <int R> struct GemmDepth {
+    static constexpr int value = R <= 3 ? 4 : R == 4 ? 3 : 2;
+};
+
 // Tiles [u_begin, u_end) of chunk c of one layer (tile index u = rb*G + g).
 template <int R>
 __device__ __forceinline__ void run_gemm_units(const LayerDesc &L, const StackParams &p, int c, int u_begin, int u_end,
                                                int wave, int lane, uint8_t *lds_wave, uint8_t *lds_zero) {
     using MF = Mfma<R>;
     using Ctx = GemmCtx<R>;
+    constexpr int D = GemmDepth<R>::value, NB = D + 1;
     const uint32_t xt_bytes = (uint32_t)L.CB * L.G * MF::NMF * 256u;
     const Ctx cx{L, lane_map(lane), lane, c,
                  __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(L.xt), 0, (int)xt_bytes, 0x00020000), lds_wave,
@@ -222,67 +261,73 @@ __device__ __forceinline__ void run_gemm_units(const LayerDesc &L, const StackPa
     const int col = c * kChunkCols + lm.col;
     const bool fast_store = (L.N & 3) == 0 && (reinterpret_cast<uintptr_t>(L.y) & 7) == 0;
 
-    uint32_t w[2][4 * R];
+    // ring of NB weight buffers with compile-time indices (no register copies); past the end
+    // of the run the last tile is fetched again instead of branching around the loads
+    uint32_t w[NB][4 * R];
+    int u_pf = u_begin;
+    auto prefetch_w = [&](uint32_t (&dst)[4 * R]) {
+        cx.load_w(dst, u_pf);
+        if (u_pf + 1 < u_end) ++u_pf;
+    };
     {
         u32x4 xb[Ctx::NXL];
         cx.load_x(xb, g);
-        cx.load_w(w[0], u_begin);
+        static_for<D>([&](auto j) { prefetch_w(w[j]); });
         cx.store_x(xb, 0);
     }
     int u = u_begin;
-    // one tile: compute on wc from LDS stage `st`, prefetch the next tile into wn / stage st^1
-    auto body = [&](const uint32_t (&wc)[4 * R], uint32_t (&wn)[4 * R], int st) {
-        // the last tile of the run prefetches itself again: no branch, so no full wait at a join
-        const bool more = u + 1 < u_end;
-        const int g_next = more ? (g + 1 == L.G ? 0 : g + 1) : g;
-        u32x4 xb[Ctx::NXL];
-        cx.load_x(xb, g_next);                 // first: it is awaited first (loads return in order)
-        cx.load_w(wn, more ? u + 1 : u);
-        u32x2 s4[4], z4[4];
-        const u32x2 MQ_GLOBAL *sp = gl(reinterpret_cast<const u32x2 *>(L.st + (size_t)u * 64 + lm.rowbase));
-        const u32x2 MQ_GLOBAL *zp = gl(reinterpret_cast<const u32x2 *>(L.zt + (size_t)u * 64 + lm.rowbase));
-#pragma unroll
-        for (int q = 0; q < 4; ++q) { s4[q] = sp[2 * q]; z4[q] = zp[2 * q]; }
-        const float xg = gl(L.xsum)[(size_t)(c * L.G + g) * kChunkCols + lm.col];
-        __builtin_amdgcn_sched_barrier(0);     // keep the loads up here, ahead of the math
-        gemm_tile_math<R>(cx, wc, st, s4, z4, xg, yacc);
-        cx.store_x(xb, st ^ 1);
-        ++g;
-        if (g == L.G || u + 1 == u_end) {
-            const uint64_t a = L.cost_start + ((uint64_t)c * L.RB * L.G + (uint64_t)rb * L.G) * L.cost;
-            const int row0 = rb * kRowBlock + lm.rowbase;
-            finish_row_block<16>(L, p, p.cnt + L.cnt_off + c * L.RB + rb, a, ga, g, yacc, wave, lane,
-                                 [&](const float(&tot)[16]) {
-                                     if (col >= L.M) return;
-                                     _Float16 MQ_GLOBAL *yrow = gl(L.y + (size_t)col * L.N);
-#pragma unroll
-                                     for (int q = 0; q < 4; ++q) {
-                                         const int row = row0 + 8 * q;
-                                         if (fast_store && row + 3 < L.N) {
-                                             const half2_t lo = {(_Float16)tot[4 * q], (_Float16)tot[4 * q + 1]};
-                                             const half2_t hi = {(_Float16)tot[4 * q + 2], (_Float16)tot[4 * q + 3]};
-                                             const u32x2 pk = {__builtin_bit_cast(uint32_t, lo),
-                                                               __builtin_bit_cast(uint32_t, hi)};
-                                             *(u32x2 MQ_GLOBAL *)(yrow + row) = pk;
-                                         } else {
-#pragma unroll
-                                             for (int e = 0; e < 4; ++e)
-                                                 if (row + e < L.N) yrow[row + e] = (_Float16)tot[4 * q + e];
-                                         }
-                                     }
-                                 });
-            ++rb;
-            g = 0;
-            ga = 0;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) yacc[v] = 0.f;
-        }
-        ++u;
-    };
+    int st = 0;  // LDS stage holding the current tile's activations
     while (u < u_end) {
-        body(w[0], w[1], 0);
-        if (u >= u_end) break;
-        body(w[1], w[0], 1);
+        static_for<NB>([&](auto j) {
+            if (u >= u_end) return;
+            const bool more = u + 1 < u_end;
+            const int g_next = more ? (g + 1 == L.G ? 0 : g + 1) : g;
+            u32x4 xb[Ctx::NXL];
+            cx.load_x(xb, g_next);              // first: it is awaited first (loads return in order)
+            __builtin_amdgcn_sched_barrier(0);  // ... and must really be issued first
+            prefetch_w(w[(j + D) % NB]);
+            u32x2 s4[4], z4[4];
+            const u32x2 MQ_GLOBAL *sp = gl(reinterpret_cast<const u32x2 *>(L.st + (size_t)u * 64 + lm.rowbase));
+            const u32x2 MQ_GLOBAL *zp = gl(reinterpret_cast<const u32x2 *>(L.zt + (size_t)u * 64 + lm.rowbase));
+#pragma unroll
+            for (int q = 0; q < 4; ++q) { s4[q] = sp[2 * q]; z4[q] = zp[2 * q]; }
+            const float xg = gl(L.xsum)[(size_t)(c * L.G + g) * kChunkCols + lm.col];
+            __builtin_amdgcn_sched_barrier(0);  // keep the loads up here, ahead of the math
+            gemm_tile_math<R>(cx, w[j], st, s4, z4, xg, yacc);
+            cx.store_x(xb, st ^ 1);
+            st ^= 1;
+            ++g;
+            ++u;
+            if (g == L.G || u == u_end) {
+                const uint64_t a = L.cost_start + ((uint64_t)c * L.RB * L.G + (uint64_t)rb * L.G) * L.cost;
+                const int row0 = rb * kRowBlock + lm.rowbase;
+                finish_row_block<16>(L, p, p.cnt + L.cnt_off + c * L.RB + rb, a, ga, g, yacc, wave, lane,
+                                     [&](const float(&tot)[16]) {
+                                         if (col >= L.M) return;
+                                         _Float16 MQ_GLOBAL *yrow = gl(L.y + (size_t)col * L.N);
+#pragma unroll
+                                         for (int q = 0; q < 4; ++q) {
+                                             const int row = row0 + 8 * q;
+                                             if (fast_store && row + 3 < L.N) {
+                                                 const half2_t lo = {(_Float16)tot[4 * q], (_Float16)tot[4 * q + 1]};
+                                                 const half2_t hi = {(_Float16)tot[4 * q + 2], (_Float16)tot[4 * q + 3]};
+                                                 const u32x2 pk = {__builtin_bit_cast(uint32_t, lo),
+                                                                   __builtin_bit_cast(uint32_t, hi)};
+                                                 *(u32x2 MQ_GLOBAL *)(yrow + row) = pk;
+                                             } else {
+#pragma unroll
+                                                 for (int e = 0; e < 4; ++e)
+                                                     if (row + e < L.N) yrow[row + e] = (_Float16)tot[4 * q + e];
+                                             }
+                                         }
+                                     });
+                ++rb;
+                g = 0;
+                ga = 0;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) yacc[v] = 0.f;
+            }
+        });
     }
 }
 

@@ -174,9 +174,6 @@ template <int M, int XP> __global__ __launch_bounds__(256) void stack_kernel(con
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6));
     if (wave >= p.nwaves) return;
-#ifdef MQ_PROFILE_WAVES
-    const uint64_t t_start = __builtin_readcyclecounter();
-#endif
     for (int worker = wave; worker < p.nworkers; worker += p.nwaves) {
         walk_tiles(p, worker, [&](const LayerDesc &L, int u_begin, int u_end) {
             switch (L.r) {
@@ -188,14 +185,6 @@ template <int M, int XP> __global__ __launch_bounds__(256) void stack_kernel(con
             }
         });
     }
-#ifdef MQ_PROFILE_WAVES
-    // development aid: start / end clock of every wave behind the partial-sum slots
-    if (lane == 0) {
-        uint64_t *dbg = reinterpret_cast<uint64_t *>(p.part + (size_t)p.nworkers * 2 * p.slot_floats);
-        dbg[2 * wave] = t_start;
-        dbg[2 * wave + 1] = __builtin_readcyclecounter();
-    }
-#endif
 }
 
 // ------------------------------------------------------------------ one layer, low latency
