@@ -13,7 +13,7 @@ streams from HBM.
 Prints ONE JSON line: effective HBM GB/s over the step (algorithmic bytes:
 r/8 per weight + fp16 scale and zero per group + activations in and out), the
 per-r microseconds and GB/s, the roofline object of the dominant kernel
-(mq::stack_kernel<1>, HBM-bound) measured with events on the launch stream, and
+(mq::stack_kernel<1, 1>, HBM-bound) measured with events on the launch stream, and
 the CPU oracle timed on the host cores on a bounded sample.
 """
 from __future__ import annotations
@@ -29,10 +29,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-# HBM bytes per launch of mq::stack_kernel<1> on the default workload (mean over the five widths),
+# HBM bytes per launch of mq::stack_kernel<1, 1> on the default workload (mean over the five widths),
 # from the two rocprofv3 --pmc runs summarised in profiles/stack_kernel_llama2_7b_m1_hbm_traffic.txt
 # (FETCH_SIZE scaled by 1.9987, WRITE_SIZE by 1.0, both calibrated on a 45 MB copy in the same run).
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 3936200739
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 3936979164
 WIDTHS = (2, 3, 4, 6, 8)
 
 
@@ -159,12 +159,12 @@ def main() -> int:
                          "frac_of_8TBps": round(gbps / HBM_PEAK_GBPS, 4), "algorithmic_MB": round(stacks[r]["bytes"] / 1e6, 1)}
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # roofline of the dominant kernel (mq::stack_kernel<1>): algorithmic bytes per launch / mean launch duration
+    # roofline of the dominant kernel (mq::stack_kernel<1, 1>): algorithmic bytes per launch / mean launch duration
     launches = [u for r in WIDTHS for u in per_r_us[r]]
     avg_launch_us = float(np.mean(launches))
     bytes_per_launch = step_bytes / len(WIDTHS)
     achieved = bytes_per_launch / avg_launch_us / 1e3
-    roofline = {"bound": "hbm", "kernel": "mq::stack_kernel<1>", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+    roofline = {"bound": "hbm", "kernel": "mq::stack_kernel<1, 1>", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                 "avg_launch_us": round(avg_launch_us, 1), "algorithmic_bytes_per_launch": int(bytes_per_launch),
                 "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH if args.layers == 32 else None}
@@ -202,25 +202,25 @@ def main() -> int:
                 single[f"{N}x{K}:r{r}"] = {"us": round(us, 2), "GBps": round(b / us / 1e3, 1), "copies": len(same)}
                 del g
 
-    # ---- CPU oracle on the host cores: one decoder block (7 linears) at every r
+    # ---- CPU oracle on the host cores: whole decoder blocks (7 linears at every r) until about 12 s of work
     cpu = None
     if not args.no_cpu:
         from oracle import c_oracle
-        cb, ct, cores = 0.0, 0.0, 1
-        t_cpu0 = time.perf_counter()
-        for r in WIDTHS:
-            for (name, N, K) in block:
-                L = host[(N, K)]
-                ta = time.perf_counter()
-                _, cores = c_oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], 8, r, 128)
-                ct += time.perf_counter() - ta
-                cb += algo_bytes(N, K, r, M)
-            if time.perf_counter() - t_cpu0 > 60:
-                break
+        cb, ct, cores, passes = 0.0, 0.0, 1, 0
+        while ct < 12.0 and passes < 64:
+            for r in WIDTHS:
+                for (name, N, K) in block:
+                    L = host[(N, K)]
+                    ta = time.perf_counter()
+                    _, cores = c_oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], 8, r, 128)
+                    ct += time.perf_counter() - ta
+                    cb += algo_bytes(N, K, r, M)
+            passes += 1
         cpu = {"value": round(cb / ct / 1e9, 3), "unit": "GB/s", "cores": int(cores), "kind": "oracle",
                "sample": "plain-C oracle (oracle/mq_oracle.c, slice+dequant+fp64 dot per weight, OpenMP over rows) on "
-                         "one Llama-2-7B decoder block (7 linears, M=1) at each r in {2,3,4,6,8}; same algorithmic-byte "
-                         "accounting as the GPU value", "seconds": round(ct, 2)}
+                         f"{passes} Llama-2-7B decoder blocks (7 linears each, M=1) at each r in {{2,3,4,6,8}} "
+                         f"= {passes}/{args.layers} of the timed workload; same algorithmic-byte accounting as the GPU value",
+               "seconds": round(ct, 2)}
 
     out = {
         "metric": "batch-1 sliced GEMV effective HBM GB/s (algorithmic bytes / time) over r in {2,3,4,6,8}",
@@ -284,7 +284,7 @@ def bench_mixed_stack(args, mq, synth, torch, np, dev):
                      ms, f"{'Llama-3-70B' if big else 'Llama-2-7B'}-shaped stack, {n_blocks} blocks ({len(layers)} linears), "
                      f"M={M}, per-layer r from {{2,3,4,6,8}} by seed, parameter-weighted mean {mean:.3f} bits",
                      {"M": M, "mean_bits": round(mean, 4), "algorithmic_GB_per_step": round(nbytes / 1e9, 3)})
-    kernel = "mq::stack_kernel<%d>" % M if M <= 4 else "mq::gemm_stack_kernel"
+    kernel = "mq::stack_kernel<%d, 1>" % M if M <= 4 else "mq::gemm_stack_kernel"
     ach = nbytes / float(np.mean(us)) / 1e3
     out["stack_us_median"] = round(float(np.median(us)), 1)
     out["stack_us_min"] = round(float(np.min(us)), 1)
