@@ -124,7 +124,8 @@ mq_status mq_pack_meta(const mq_half *scales, const mq_half *zeros, int64_t N, i
  * accumulation, fp16 output (round to nearest even).
  *   x        : device, fp16 [M, K], 4-byte aligned
  *   packed_W : device, from mq_pack with the same N, K, r; 16-byte aligned
- *   scales_t, zeros_t : device, from mq_pack_meta; 8-byte aligned when M > 4
+ *   scales_t, zeros_t : device, from mq_pack_meta; 8-byte aligned when M > 4,
+ *                       16-byte aligned when M > 16
  *   y        : device, fp16 [M, N]; fully overwritten
  *   ws       : device, 256-byte aligned, ws_bytes >= mq_workspace_bytes(M,N,K,r),
  *              initialised once with mq_workspace_init

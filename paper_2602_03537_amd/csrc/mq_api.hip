@@ -26,16 +26,27 @@ mq_status check_shape(int64_t N, int64_t K, int group) {
 
 size_t counter_bytes(int64_t row_blocks) { return align_up((size_t)row_blocks * 4, kCounterBytesAlign); }
 bool use_mfma(int64_t M) { return M > kValuMaxM; }
-int64_t chunks(int64_t M) { return use_mfma(M) ? (M + kChunkCols - 1) / kChunkCols : 1; }
-int slot_floats(int64_t M) { return use_mfma(M) ? 64 * kChunkCols : 64 * (int)M; }
-size_t partial_bytes(int64_t M) {
-    return (size_t)(use_mfma(M) ? kMaxWavesMfma : max_workers_valu(M)) * 2 * (size_t)slot_floats(M) * sizeof(float);
+// column blocks the schedule sees: 1 (vector ALUs), 16-column chunks (narrow MFMA), passes (wide MFMA)
+int64_t chunks(int64_t M) {
+    return use_wide(M) ? wide_passes(M) : use_mfma(M) ? (M + kChunkCols - 1) / kChunkCols : 1;
 }
-// MFMA path: re-ordered activations and their group sums for one layer
+int64_t counters_of(int64_t M, int64_t N) { return chunks(M) * (pad_rows(N) / kRowBlock); }
+int slot_floats(int64_t M) {
+    return use_wide(M) ? 4 * wide_chunks_per_pass(M) * 32 * 64 : use_mfma(M) ? 64 * kChunkCols : 64 * (int)M;
+}
+size_t partial_bytes(int64_t M) {
+    const size_t workers = use_wide(M)   ? (size_t)wide_max_groups(wide_chunks_per_pass(M))
+                           : use_mfma(M) ? (size_t)kMaxWavesMfma
+                                         : (size_t)max_workers_valu(M);
+    return workers * 2 * (size_t)slot_floats(M) * sizeof(float);
+}
+// MFMA paths: re-ordered activations and their group sums for one layer
 size_t xt_bytes(int64_t M, int64_t K, int r) {
+    if (use_wide(M)) return align_up((size_t)wide_chunks_padded(M) * (size_t)(K / kGroup) * kWideXtBlockBytes, 256);
     return use_mfma(M) ? (size_t)chunks(M) * (size_t)(K / kGroup) * (size_t)mfma_per_tile(r) * 256 : 0;
 }
 size_t xsum_bytes(int64_t M, int64_t K) {
+    if (use_wide(M)) return 0;  // the sums live inside the activation blocks
     return use_mfma(M) ? align_up((size_t)chunks(M) * (size_t)(K / kGroup) * kChunkCols * sizeof(float), 256) : 0;
 }
 
@@ -44,8 +55,8 @@ mq_status layer_status(const mq_layer &l, int64_t M) {
     if (!valid_pack_r(l.r)) return MQ_ERR_BAD_R;
     if (M < 1 || M > MQ_MAX_M) return MQ_ERR_BAD_SHAPE;
     if (mq_status st = check_shape(l.N, l.K, l.group)) return st;
-    // the MFMA path reads four scales / zeros with one 8-byte load
-    const size_t meta_align = use_mfma(M) ? 8 : 2;
+    // the MFMA paths read scales / zeros 8 bytes (M <= 16) or 16 bytes (M > 16) at a time
+    const size_t meta_align = use_wide(M) ? 16 : use_mfma(M) ? 8 : 2;
     if (!aligned(l.packed_W, 16) || !aligned(l.x, 4) || !aligned(l.scales_t, meta_align) ||
         !aligned(l.zeros_t, meta_align) || !aligned(l.y, 2))
         return MQ_ERR_ALIGN;
@@ -69,6 +80,10 @@ LayerDesc make_desc(const mq_layer &l, int64_t M, uint64_t cost_start, int cnt_o
     d.RB = (int32_t)(pad_rows(l.N) / kRowBlock);
     d.r = l.r;
     d.cost = tile_cost(l.r);
+    if (use_wide(M)) {  // scheduled in super-tiles of four row blocks; the matrix-core time of a tile grows with the chunks
+        d.RB = (d.RB + 3) / 4;
+        d.cost = tile_cost(l.r) + 6 * wide_chunks_per_pass(M);
+    }
     d.cnt_off = cnt_off;
     d.M = (int32_t)M;
     d.CB = (int32_t)chunks(M);
@@ -84,7 +99,7 @@ struct PlanHeader {
     int32_t n_layers, M, max_cost, n_jobs;
     uint64_t table_off, cnt_off, part_off, total_bytes;
 };
-constexpr uint64_t kPlanMagic = 0x4d51504c414e3032ull;  // "MQPLAN02"
+constexpr uint64_t kPlanMagic = 0x4d51504c414e3033ull;  // "MQPLAN03"
 
 // Host-side copies of the plan headers, keyed by device address, so that running
 // a stack needs no read-back.  mq_stack_plan overwrites the entry of its address.
@@ -98,7 +113,7 @@ PlanLayout plan_layout(const mq_layer *layers, int n_layers, int64_t M) {
     int64_t counters = 0;
     size_t act = 0;
     for (int i = 0; i < n_layers; ++i) {
-        counters += chunks(M) * (pad_rows(layers[i].N) / kRowBlock);
+        counters += counters_of(M, layers[i].N);
         act += xt_bytes(M, layers[i].K, layers[i].r) + xsum_bytes(M, layers[i].K);
     }
     PlanLayout p;
@@ -144,7 +159,7 @@ size_t mq_meta_bytes(int64_t N, int64_t K, int group) {
 
 size_t mq_workspace_bytes(int64_t M, int64_t N, int64_t K, int r) {
     if (!valid_pack_r(r) || check_shape(N, K, kGroup) != MQ_OK || M < 1 || M > MQ_MAX_M) return 0;
-    return counter_bytes(chunks(M) * (pad_rows(N) / kRowBlock)) + partial_bytes(M) + xt_bytes(M, K, r) +
+    return counter_bytes(counters_of(M, N)) + partial_bytes(M) + xt_bytes(M, K, r) +
            xsum_bytes(M, K);
 }
 
@@ -212,7 +227,7 @@ mq_status mq_linear(const mq_half *x, int64_t M, const void *packed_W, const mq_
     if (ws_bytes < mq_workspace_bytes(M, N, K, r)) return MQ_ERR_BUF_TOO_SMALL;
 
     char *base = static_cast<char *>(ws);
-    const size_t cnt_b = counter_bytes(chunks(M) * (pad_rows(N) / kRowBlock));
+    const size_t cnt_b = counter_bytes(counters_of(M, N));
     char *act = base + cnt_b + partial_bytes(M);
     StackParams p{};
     p.table = nullptr;
@@ -223,9 +238,11 @@ mq_status mq_linear(const mq_half *x, int64_t M, const void *packed_W, const mq_
     p.part = reinterpret_cast<float *>(base + cnt_b);
     p.M = (int32_t)M;
     p.slot_floats = slot_floats(M);
-    p.n_jobs = p.single.CB * p.single.G;
+    p.n_jobs = (use_wide(M) ? wide_chunks_padded(M) : p.single.CB) * p.single.G;
     hipError_t e;
-    if (use_mfma(M))
+    if (use_wide(M))
+        e = launch_stack_wide(p, p.single.cost, (hipStream_t)stream);
+    else if (use_mfma(M))
         e = launch_stack_mfma(p, p.single.cost, (hipStream_t)stream);
     else if (linear_rb_fits(p.single, partial_bytes(M)))
         e = launch_linear_rb(p.single, p.part, p.cnt, (hipStream_t)stream);
@@ -265,8 +282,8 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
                              xb ? base_dev + act + xb : nullptr);
         act += xb + sb;
         cost += (uint64_t)table[i].CB * table[i].RB * table[i].G * table[i].cost;
-        counters += (int64_t)table[i].CB * table[i].RB;
-        jobs += (int64_t)table[i].CB * table[i].G;
+        counters += counters_of(M, layers[i].N);
+        jobs += (int64_t)(use_wide(M) ? wide_chunks_padded(M) : table[i].CB) * table[i].G;
         if (table[i].cost > max_cost) max_cost = table[i].cost;
     }
     if (counters > INT32_MAX || jobs > INT32_MAX) return MQ_ERR_BAD_SHAPE;
@@ -324,8 +341,9 @@ mq_status mq_linear_stack(void *plan, mq_stream stream) {
     p.M = h.M;
     p.slot_floats = slot_floats(h.M);
     p.n_jobs = h.n_jobs;
-    const hipError_t e = use_mfma(h.M) ? launch_stack_mfma(p, h.max_cost, (hipStream_t)stream)
-                                       : launch_stack(p, h.max_cost, (hipStream_t)stream);
+    const hipError_t e = use_wide(h.M)   ? launch_stack_wide(p, h.max_cost, (hipStream_t)stream)
+                         : use_mfma(h.M) ? launch_stack_mfma(p, h.max_cost, (hipStream_t)stream)
+                                         : launch_stack(p, h.max_cost, (hipStream_t)stream);
     return e == hipSuccess ? MQ_OK : MQ_ERR_HIP;
 }
 

@@ -29,6 +29,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // them as generic ("flat") addresses, whose loads cannot be counted separately from LDS
 // traffic and force full waits.  Everything here lives in global memory: say so.
 #define MQ_GLOBAL __attribute__((address_space(1)))
+#define MQ_LDS __attribute__((address_space(3)))
 template <class T> __device__ __forceinline__ const T MQ_GLOBAL *gl(const T *p) { return (const T MQ_GLOBAL *)p; }
 template <class T> __device__ __forceinline__ T MQ_GLOBAL *gl(T *p) { return (T MQ_GLOBAL *)p; }
 typedef const uint32_t __attribute__((address_space(4))) *cptr32;  // scalar (SGPR) loads

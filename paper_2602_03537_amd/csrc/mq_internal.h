@@ -23,9 +23,23 @@ inline int max_workers_valu(int64_t M) {
 }
 constexpr int kCounterBytesAlign = 256;
 
-// Batches up to kValuMaxM run on the vector ALUs; larger ones on MFMA, 16 columns per chunk.
+// Batches up to kValuMaxM run on the vector ALUs; up to kNarrowMaxM on MFMA with 16 columns per
+// chunk and one wave per tile; larger ones on MFMA with 32 columns per chunk, four waves per
+// super-tile of 256 rows and up to kWideMaxChunks chunks against one unpacked tile.
 constexpr int kValuMaxM = 4;
 constexpr int kChunkCols = 16;
+constexpr int kNarrowMaxM = 16;
+constexpr int kWideCols = 32;
+constexpr int kWideMaxChunks = 4;
+constexpr int kWideXtBlockBytes = 8 * 1024;  // prepared activations of one (group, chunk of 32 columns)
+inline bool use_wide(int64_t M) { return M > kNarrowMaxM; }
+inline int wide_chunks(int64_t M) { return (int)((M + kWideCols - 1) / kWideCols); }
+inline int wide_passes(int64_t M) { return (wide_chunks(M) + kWideMaxChunks - 1) / kWideMaxChunks; }
+// chunks per pass (the kernel variant, 1..4); the chunk count is padded to passes * chunks per pass
+inline int wide_chunks_per_pass(int64_t M) { return (wide_chunks(M) + wide_passes(M) - 1) / wide_passes(M); }
+inline int wide_chunks_padded(int64_t M) { return wide_passes(M) * wide_chunks_per_pass(M); }
+// workgroups a wide launch may use (sizes the partial-sum slots): one per compute unit
+inline int wide_max_groups(int) { return 256; }
 
 // One layer as the persistent kernels see it.
 struct LayerDesc {
@@ -36,12 +50,12 @@ struct LayerDesc {
     _Float16 *y;
     const uint4 *xt;        // MFMA path: activations re-ordered per (chunk, group, MFMA) by the prep kernel
     const float *xsum;      // MFMA path: per (chunk, group, column) sums of x
-    int32_t N, K, G, RB;    // RB = row blocks = ceil(N/64)
+    int32_t N, K, G, RB;    // RB = row blocks = ceil(N/64); on the wide path super row blocks = ceil(N/256)
     int32_t r;
     int32_t cost;           // schedule cost of one (row block, group) tile
     int32_t cnt_off;        // index of this layer's first row-block counter (CB*RB counters)
     int32_t M;              // batch rows of x
-    int32_t CB;             // column chunks: 1 on the vector-ALU path, ceil(M/16) on the MFMA path
+    int32_t CB;             // column chunks: 1 on the vector-ALU path, ceil(M/16) on the MFMA path; wide path: passes
     int32_t job_start;      // prep kernel: sum of CB*G over the preceding layers
     uint64_t cost_start;    // sum of CB*RB*G*cost over the preceding layers
 };
@@ -89,5 +103,7 @@ bool linear_rb_fits(const LayerDesc &L, size_t part_bytes);
 hipError_t launch_linear_rb(const LayerDesc &L, float *part, int32_t *cnt, hipStream_t s);
 // MFMA path (M > kValuMaxM): activation prep kernel + persistent MFMA kernel.
 hipError_t launch_stack_mfma(StackParams p, int max_cost, hipStream_t s);
+// Wide MFMA path (M > kNarrowMaxM): activation prep kernel + persistent kernel, one workgroup per share.
+hipError_t launch_stack_wide(StackParams p, int max_cost, hipStream_t s);
 
 }  // namespace mq
