@@ -166,9 +166,7 @@ __global__ __launch_bounds__(256) void xprep_wide_kernel(const StackParams p) {
 // Workgroup barrier that orders LDS traffic only: a wave's global loads stay in flight across it.
 __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-#ifndef MQ_X_NO_BARRIER
     __builtin_amdgcn_s_barrier();
-#endif
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
@@ -267,18 +265,21 @@ __device__ __forceinline__ uint32_t wide_operand(const uint32_t (&e)[Wide<R>::NE
 constexpr int kJobStage[8] = {1, 1, 2, 1, 2, 1, 2, 2};
 constexpr int kJobPair[8] = {0, 1, 0, 2, 1, 3, 2, 3};
 
-// Split-K hand-over for many accumulators per lane: as finish_row_block, but the last
-// contributor sums and delivers BLK values at a time (final(block, values)).
-template <int NV, int BLK, class Final>
+// Split-K hand-over for many accumulators per lane: as finish_row_block, but the accumulators are
+// fetched block by block (block(b) = 16 values) and the last contributor sums and delivers 16 values
+// at a time (final(b, values)), so that only a block is ever held in vector registers.
+template <int NBK, class Block, class Final>
 __device__ __forceinline__ void finish_row_block_blocked(const LayerDesc &L, const StackParams &p, int32_t *cnt,
-                                                         uint64_t a, int ga, int gb, float (&acc)[NV], int worker,
+                                                         uint64_t a, int ga, int gb, Block &&block, int worker,
                                                          int lane, Final &&final) {
-    constexpr int NBK = NV / BLK;
+    constexpr int BLK = 16;
     if (ga == 0 && gb == L.G) {
         static_for<NBK>([&](auto b) {
+            __builtin_amdgcn_sched_barrier(0);  // one block in vector registers at a time
+            const float16_t v = block(b);
             float t[BLK];
 #pragma unroll
-            for (int v = 0; v < BLK; ++v) t[v] = acc[b * BLK + v];
+            for (int i = 0; i < BLK; ++i) t[i] = v[i];
             final(b, t);
         });
         return;
@@ -286,8 +287,13 @@ __device__ __forceinline__ void finish_row_block_blocked(const LayerDesc &L, con
     const int slot = ga == 0 ? 1 : 0;
     const size_t slot_floats = (size_t)p.slot_floats;
     float MQ_GLOBAL *mine = gl(p.part + (size_t)(worker * 2 + slot) * slot_floats + lane);
+    static_for<NBK>([&](auto b) {
+        __builtin_amdgcn_sched_barrier(0);  // one block in vector registers at a time
+        const float16_t v = block(b);
 #pragma unroll
-    for (int v = 0; v < NV; ++v) __hip_atomic_store(mine + v * 64, acc[v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int i = 0; i < BLK; ++i)
+            __hip_atomic_store(mine + (b * BLK + i) * 64, v[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    });
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     int old = 0;
@@ -297,16 +303,30 @@ __device__ __forceinline__ void finish_row_block_blocked(const LayerDesc &L, con
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     const int w_lo = wave_of(a, p.nworkers, p.cost_total);
     const int w_hi = wave_of(a + (uint64_t)(L.G - 1) * L.cost, p.nworkers, p.cost_total);
-    constexpr int kBatch = 4;
+    // Fixed summation order: slot 1 of share w_lo, then slot 0 of shares w_lo+1 .. w_hi.  A share spans many
+    // tiles here, so there are two contributors as a rule: their values of block b+1 are on their way while
+    // block b is summed and delivered; further contributors are fetched one after the other.
+    const bool two = w_lo < w_hi;
+    const float MQ_GLOBAL *first = gl(p.part + (size_t)(w_lo * 2 + 1) * slot_floats + lane);
+    const float MQ_GLOBAL *second = gl(p.part + (size_t)((two ? w_lo + 1 : w_lo) * 2) * slot_floats + lane);
+    float fv[2][BLK], sv[2][BLK];
+    auto fetch = [&](auto b) {
+#pragma unroll
+        for (int v = 0; v < BLK; ++v) {
+            fv[b % 2][v] = __hip_atomic_load(first + (b * BLK + v) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sv[b % 2][v] = __hip_atomic_load(second + (b * BLK + v) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    };
+    fetch(IntC<0>{});
     static_for<NBK>([&](auto b) {
+        if constexpr (b + 1 < NBK) fetch(IntC<b + 1>{});
         float tot[BLK];
-        const float MQ_GLOBAL *first = gl(p.part + (size_t)(w_lo * 2 + 1) * slot_floats + lane) + b * BLK * 64;
 #pragma unroll
-        for (int v = 0; v < BLK; ++v) tot[v] = __hip_atomic_load(first + v * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        for (int w0 = w_lo + 1; w0 <= w_hi; w0 += kBatch) {
-            float t[kBatch][BLK];
+        for (int v = 0; v < BLK; ++v) tot[v] = two ? fv[b % 2][v] + sv[b % 2][v] : fv[b % 2][v];
+        for (int w0 = w_lo + 2; w0 <= w_hi; w0 += 2) {  // two at a time, so that their round trips overlap
+            float t[2][BLK];
 #pragma unroll
-            for (int j = 0; j < kBatch; ++j) {
+            for (int j = 0; j < 2; ++j) {
                 const int w = w0 + j <= w_hi ? w0 + j : w_hi;
                 const float MQ_GLOBAL *src = gl(p.part + (size_t)(w * 2) * slot_floats + lane) + b * BLK * 64;
 #pragma unroll
@@ -314,11 +334,11 @@ __device__ __forceinline__ void finish_row_block_blocked(const LayerDesc &L, con
                     t[j][v] = __hip_atomic_load(src + v * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
 #pragma unroll
-            for (int j = 0; j < kBatch; ++j)
-                if (w0 + j <= w_hi) {
+            for (int v = 0; v < BLK; ++v) tot[v] += t[0][v];
+            if (w0 + 1 <= w_hi) {
 #pragma unroll
-                    for (int v = 0; v < BLK; ++v) tot[v] += t[j][v];
-                }
+                for (int v = 0; v < BLK; ++v) tot[v] += t[1][v];
+            }
         }
         final(b, tot);
     });
@@ -368,11 +388,7 @@ template <int N, int B> __device__ __forceinline__ void dma_block(const uint8_t 
 // (No wait states needed here: the A operand comes from LDS behind a counter wait, the B operand was
 // formed by vector instructions at least one slot earlier.)
 __device__ __forceinline__ void mfma_acc(float16_t &acc, const u32x4 &a, const u32x4 &b) {
-#ifdef MQ_X_NO_MFMA
-    asm volatile("" : "+a"(acc) : "v"(a), "v"(b));
-#else
     asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
-#endif
 }
 // acc = 0, also from the matrix core (0 * 0 + 0), so that the accumulators are never defined by a vector instruction
 __device__ __forceinline__ void mfma_zero(float16_t &acc) {
@@ -381,23 +397,22 @@ __device__ __forceinline__ void mfma_zero(float16_t &acc) {
     // compiler does not see a matrix instruction and inserts none
     asm volatile("s_nop 4\n\tv_mfma_f32_32x32x16_f16 %0, %1, %1, 0" : "=a"(acc) : "v"(z));
 }
+// One accumulator block out of the accumulation registers, at this point of the program and not earlier
+// (the compiler would otherwise fetch all C * 64 accumulators into vector registers ahead of the hand-over).
+__device__ __forceinline__ float16_t read_acc(const float16_t &acc) {
+    float16_t r;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        float x;
+        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(acc[v]) : "memory");
+        r[v] = x;
+    }
+    return r;
+}
 template <int N> __device__ __forceinline__ void wait_transfers() {
     static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
-
-#ifdef MQ_WIDE_TIMING
-__device__ unsigned long long g_wt[64 * 8];
-#ifndef MQ_WT_WAVE
-#define MQ_WT_WAVE 0
-#endif
-#ifndef MQ_WT_MASK
-#define MQ_WT_MASK 0xFF
-#endif
-#define MQ_WT(k) do { if (((MQ_WT_MASK >> (k)) & 1) && worker == 0 && wv == MQ_WT_WAVE && u - u_begin < 64) { unsigned long long t_ = __builtin_readcyclecounter(); if (lane == 0) g_wt[(u - u_begin) * 8 + (k)] = t_; } } while (0)
-#else
-#define MQ_WT(k) do { } while (0)
-#endif
 
 constexpr int kWideLdsBytes = 160 * 1024;
 constexpr int wide_slot_bytes(int R) { return R * 1024 + 256; }  // lane dwords of a tile + its 64 scales + 64 zeros
@@ -534,9 +549,7 @@ __device__ __forceinline__ void run_wide_units(const LayerDesc &L, const StackPa
         const bool more = u + 1 < u_end;
         const int slot_next = slot_cur + 1 == NBR ? 0 : slot_cur + 1;
         const int st_next = st + 1 == NST ? 0 : st + 1;
-        MQ_WT(0);
         const int st_fill = st == 0 ? NST - 1 : st - 1;
-        MQ_WT(1);
 
         const MQ_LDS u32x4 *abase = reinterpret_cast<const MQ_LDS u32x4 *>(lds + st * kStage) + lane;
         // A operands in the order of use: position i = s * C + c is chunk c of spec s
@@ -550,12 +563,9 @@ __device__ __forceinline__ void run_wide_units(const LayerDesc &L, const StackPa
             if constexpr (s == kWideSpecs - 1) {
                 // every field of tile u has been extracted: open tile u+1, which has landed once at most the
                 // transfers of the NBR-1 tile bodies after its own are in flight
-                MQ_WT(2);
                 wait_transfers<(NBR - 1) * (kXLines + kTileOps)>();
-                MQ_WT(3);
                 open_tile(slot_next);
                 __builtin_amdgcn_sched_barrier(0);
-                MQ_WT(4);
             }
             static_for<C>([&](auto c) {
                 static_for<2>([&](auto h) {
@@ -565,12 +575,7 @@ __device__ __forceinline__ void run_wide_units(const LayerDesc &L, const StackPa
                     __builtin_amdgcn_sched_barrier(0);
                     // this slot's share of the next spec's operands (after the last spec: spec 0 of tile u+1)
                     constexpr int j_lo = slot * 8 / kSpecSlots, j_hi = (slot + 1) * 8 / kSpecSlots;
-#ifdef MQ_X_NO_UNPACK
-                    constexpr int n_jobs = 0;
-#else
-                    constexpr int n_jobs = j_hi - j_lo;
-#endif
-                    static_for<n_jobs>([&](auto dj) {
+                    static_for<j_hi - j_lo>([&](auto dj) {
                         constexpr int j = j_lo + dj, pr = kJobPair[j];
                         constexpr int q0 = ((s + 1) % kWideSpecs) * 8 + 2 * pr;
                         if constexpr (kJobStage[j] == 1) {
@@ -598,11 +603,8 @@ __device__ __forceinline__ void run_wide_units(const LayerDesc &L, const StackPa
             });
         });
         // the next tile's activations were issued NST-2 bodies ago, before that body's weight tile
-        MQ_WT(5);
         wait_transfers<(NST - 2) * (kXLines + kTileOps) + kTileOps>();
-        MQ_WT(6);
         lds_barrier();  // next stage complete for every wave, current stage free
-        MQ_WT(7);
         st = st_next;
         slot_cur = slot_next;
         ++g;
@@ -614,16 +616,10 @@ __device__ __forceinline__ void run_wide_units(const LayerDesc &L, const StackPa
                 pw.part = p.part + (size_t)wv * (C * 32 * 64);
                 const int row0 = rb * kRowBlock + (lane & 31);
                 const int colq = 4 * (lane >> 5);
-                float yv[C * 32];
                 asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // the last MFMA's result must have left the matrix pipe
-#pragma unroll
-                for (int c = 0; c < C; ++c)
-#pragma unroll
-                    for (int h = 0; h < 2; ++h)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) yv[c * 32 + h * 16 + v] = acc[c][h][v];
-                finish_row_block_blocked<C * 32, 16>(
-                    L, pw, p.cnt + L.cnt_off + pass * rb_real + rb, a, ga, g, yv, worker, lane,
+                finish_row_block_blocked<2 * C>(
+                    L, pw, p.cnt + L.cnt_off + pass * rb_real + rb, a, ga, g,
+                    [&](auto b) { return read_acc(acc[b / 2][b % 2]); }, worker, lane,
                     [&](auto b, const float(&tot)[16]) {
                         // register v of lane l: batch column 8*(v/4) + 4*(l/32) + v%4 of the chunk, weight row l%32 of the half
                         constexpr int c = b / 2, hrow = b % 2;
@@ -727,12 +723,6 @@ template <int C> static hipError_t launch_wide_c(StackParams p, int max_cost, hi
     hipLaunchKernelGGL(wide_stack_kernel<C>, dim3((unsigned)p.nworkers), dim3(256), wide_lds_bytes_max(C), s, p);
     return hipGetLastError();
 }
-
-#ifdef MQ_WIDE_TIMING
-extern "C" int mq_debug_wide_timing(unsigned long long *out) {
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_wt), sizeof(g_wt));
-}
-#endif
 
 hipError_t launch_stack_wide(StackParams p, int max_cost, hipStream_t s) {
     switch (wide_chunks_per_pass(p.M)) {

@@ -318,6 +318,71 @@ def test_stack_mfma_mixed_widths(M):
             check_y(lay["y"], ref, f"mfma stack layer {i} rep {rep}")
 
 
+# ------------------------------------------------------------------ wide matrix-core path (M > 16)
+@pytest.mark.parametrize("r", WIDTHS)
+@pytest.mark.parametrize("shape_m", [(320, 640, 32), (256, 384, 40), (700, 1152, 96), (192, 512, 129), (130, 768, 160),
+                                     (1, 256, 31), (520, 256, 250)])
+def test_linear_wide_chunk_counts_passes_and_ragged_edges(r, shape_m):
+    # 1..4 chunks of 32 columns per pass, one and two passes (padded chunk counts: 129 -> 3+3, 160 -> 3+3, 250 -> 4+4),
+    # fewer rows than the four row blocks of a workgroup, N not a multiple of 64, several groups per share
+    N, K, M = shape_m
+    L = synth.make_layer(N, K, M=M, seed=[47, N, K, M])
+    y = run_linear(L, r)
+    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"wide {shape_m} r={r}")
+
+
+@pytest.mark.parametrize("r", WIDTHS)
+def test_linear_wide_uniform_random_codes_and_fractional_zeros(r):
+    # every code value, zeros with fraction bits: the fp16 step 2^(8-r)*code - zero of this path rounds then
+    L = synth.make_random_codes_layer(320, 1024, M=72, seed=[48, r])
+    y = run_linear(L, r)
+    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"wide random codes r={r}")
+
+
+def test_linear_wide_split_k_hand_over_deterministic_with_guard_bands():
+    # long K, few row blocks: every row block is shared by several workgroups
+    N, K, r, M = 256, 28672, 4, 48
+    L = synth.make_layer(N, K, M=M, seed=[49])
+    lay = mq.prepare_layer(dev(L["parent"]), dev(L["scales"]), dev(L["zeros"]), r)
+    x = dev(L["x"])
+    ws = mq.new_workspace(M, N, K, r)
+    buf = torch.full((M * N + 128,), float("nan"), dtype=torch.float16, device=DEV)
+    y = buf[64:64 + M * N].view(M, N)
+    outs = []
+    for _ in range(3):
+        y.fill_(float("nan"))
+        mq.mq_linear(x, lay["packed_W"], lay["scales_t"], lay["zeros_t"], N, K, r, 128, ws, y=y)
+        torch.cuda.synchronize()
+        outs.append(y.clone())
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    assert torch.isnan(buf[:64]).all() and torch.isnan(buf[64 + M * N:]).all()
+    check_y(outs[0], oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), "wide split-K")
+
+
+@pytest.mark.parametrize("M", [40, 200])
+def test_stack_wide_mixed_widths(M):
+    shapes_r = [(256, 512, 2), (64, 128, 8), (200, 1280, 3), (512, 256, 6), (130, 384, 4), (1024, 1024, 3), (320, 2048, 8)]
+    host, layers = _stack(shapes_r, M=M, seed=50)
+    plan = mq.mq_stack_plan(layers, M)
+    for rep in range(2):
+        for lay in layers:
+            lay["y"].fill_(float("nan"))
+        mq.mq_linear_stack(plan)
+        torch.cuda.synchronize()
+        for i, (lay, ref) in enumerate(zip(layers, oracle.linear_stack(host, C, 128))):
+            check_y(lay["y"], ref, f"wide stack layer {i} rep {rep}")
+
+
+def test_linear_wide_rejects_misaligned_meta():
+    L = synth.make_layer(64, 128, M=32, seed=[51])
+    lay = mq.prepare_layer(dev(L["parent"]), dev(L["scales"]), dev(L["zeros"]), 4)
+    ws = mq.new_workspace(32, 64, 128, 4)
+    shifted = torch.empty(lay["scales_t"].numel() + 4, dtype=torch.float16, device=DEV)[4:]  # 8-byte, not 16-byte aligned
+    shifted.copy_(lay["scales_t"].flatten())
+    with pytest.raises(mq.MqError):
+        mq.mq_linear(dev(L["x"]), lay["packed_W"], shifted, lay["zeros_t"], 64, 128, 4, 128, ws)
+
+
 def test_linear_llama3_70b_mlp_shape_batched_sampled_rows():
     # batched regime on the 8192 -> 28672 up-projection shape; rows sampled for the oracle
     N, K = 28672, 8192
