@@ -32,7 +32,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of mq::stack_kernel<1, 1> on the default workload (mean over the five widths),
 # from the two rocprofv3 --pmc runs summarised in profiles/stack_kernel_llama2_7b_m1_hbm_traffic.txt
 # (FETCH_SIZE scaled by 1.9987, WRITE_SIZE by 1.0, both calibrated on a 45 MB copy in the same run).
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 3936979164
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 3937117410
 WIDTHS = (2, 3, 4, 6, 8)
 
 
@@ -284,7 +284,8 @@ def bench_mixed_stack(args, mq, synth, torch, np, dev):
                      ms, f"{'Llama-3-70B' if big else 'Llama-2-7B'}-shaped stack, {n_blocks} blocks ({len(layers)} linears), "
                      f"M={M}, per-layer r from {{2,3,4,6,8}} by seed, parameter-weighted mean {mean:.3f} bits",
                      {"M": M, "mean_bits": round(mean, 4), "algorithmic_GB_per_step": round(nbytes / 1e9, 3)})
-    kernel = "mq::stack_kernel<%d, 1>" % M if M <= 4 else "mq::gemm_stack_kernel"
+    kernel = ("mq::stack_kernel<%d, 1>" % M if M <= 4 else "mq::gemm_stack_kernel" if M <= 16
+              else "mq::wide_stack_kernel")
     ach = nbytes / float(np.mean(us)) / 1e3
     out["stack_us_median"] = round(float(np.median(us)), 1)
     out["stack_us_min"] = round(float(np.min(us)), 1)
@@ -335,7 +336,13 @@ def bench_mlp_batched(args, mq, synth, torch, np, dev):
                      tot_t / 1e3, "Llama-3-70B MLP shapes (28672x8192, 8192x28672), M in {1,4,16,64,256}, r in {3,4,8}, "
                      "one mq_linear launch per call, 4 distinct weight copies cycled", {})
     out["table"] = table
-    out["roofline"] = None
+    # dense regime: the M = 256 calls (activation prep launch + mq::wide_stack_kernel<4>, timed together per call)
+    big = [v for k, v in table.items() if k.endswith(":M256")]
+    fl = float(np.mean([v["TFLOPs"] for v in big]))
+    out["roofline"] = {"bound": "mfma", "kernel": "mq::wide_stack_kernel<4>", "achieved": round(fl, 1), "peak": 2500.0,
+                       "unit": "TFLOP/s", "frac": round(fl / 2500.0, 4),
+                       "avg_launch_us": round(float(np.mean([v["us"] for v in big])), 1),
+                       "algorithmic_flops_per_launch": int(2 * 256 * 28672 * 8192), "traffic": None}
     out["cpu_baseline"] = None
     print(json.dumps(out))
     return 0

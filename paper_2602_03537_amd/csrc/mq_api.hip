@@ -82,7 +82,7 @@ LayerDesc make_desc(const mq_layer &l, int64_t M, uint64_t cost_start, int cnt_o
     d.cost = tile_cost(l.r);
     if (use_wide(M)) {  // scheduled in super-tiles of four row blocks; the matrix-core time of a tile grows with the chunks
         d.RB = (d.RB + 3) / 4;
-        d.cost = tile_cost(l.r) + 6 * wide_chunks_per_pass(M);
+        d.cost = tile_cost(l.r) + 60 * wide_chunks_per_pass(M);
     }
     d.cnt_off = cnt_off;
     d.M = (int32_t)M;
