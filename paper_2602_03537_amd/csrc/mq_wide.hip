@@ -112,9 +112,10 @@ static_assert(Wide<2>::ok() && Wide<3>::ok() && Wide<4>::ok() && Wide<6>::ok() &
               "inconsistent operand plan");
 
 // ------------------------------------------------------------------ activation prep
-// One wave per (layer, group, chunk of 32 columns): lane l = (column l%32, k-half l/32) writes
-// its A operand of every spec (16 bytes each).  Columns beyond M are zero.
-template <int R> __device__ __forceinline__ void xprep_wide_job(const LayerDesc &L, int g, int c, int nct, int lane) {
+// One workgroup per (layer, group, chunk of 32 columns), wave q of it for specs 2q and 2q+1: lane l =
+// (column l%32, k-half l/32) writes its A operand of those specs (16 bytes each).  Columns beyond M are zero.
+template <int R>
+__device__ __forceinline__ void xprep_wide_job(const LayerDesc &L, int g, int c, int nct, int sq, int lane) {
     const int j = lane & 31, h = lane >> 5;
     const int col = c * kWideCols + j;
     const uint32_t live = col < L.M ? 0xFFFFFFFFu : 0u;
@@ -122,22 +123,26 @@ template <int R> __device__ __forceinline__ void xprep_wide_job(const LayerDesc 
         gl(reinterpret_cast<const uint32_t *>(L.x + (size_t)(live ? col : 0) * L.K) + (size_t)g * 64);
     uint8_t *block = reinterpret_cast<uint8_t *>(const_cast<uint4 *>(L.xt)) + (size_t)(g * nct + c) * kWideBlockBytes;
     u32x4 MQ_GLOBAL *out = gl(reinterpret_cast<u32x4 *>(block)) + lane;
-    uint32_t v[kWideSpecs][4];
-    static_for<kWideSpecs>([&](auto s) {
-        static_for<4>([&](auto i) {
-            constexpr WField f = Wide<R>::fld(s, i);
-            v[s][i] = xrow[h ? f.pair_hi : f.pair_lo] & live;
+    static_for<kWideSpecs / 2>([&](auto q) {
+        if (q != sq) return;
+        uint32_t v[2][4];
+        static_for<2>([&](auto ds) {
+            static_for<4>([&](auto i) {
+                constexpr WField f = Wide<R>::fld(2 * q + ds, i);
+                v[ds][i] = xrow[h ? f.pair_hi : f.pair_lo] & live;
+            });
         });
-    });
-    static_for<kWideSpecs>([&](auto s) {
-        const u32x4 o = {v[s][0], v[s][1], v[s][2], v[s][3]};
-        out[s * 64] = o;
+        static_for<2>([&](auto ds) {
+            const u32x4 o = {v[ds][0], v[ds][1], v[ds][2], v[ds][3]};
+            out[(2 * q + ds) * 64] = o;
+        });
     });
 }
 
 __global__ __launch_bounds__(256) void xprep_wide_kernel(const StackParams p) {
     const int lane = threadIdx.x & 63;
-    const int job = __builtin_amdgcn_readfirstlane((int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6));
+    const int sq = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int job = blockIdx.x;
     if (job >= p.n_jobs) return;
     int li = 0;
     if (p.table) {
@@ -154,11 +159,11 @@ __global__ __launch_bounds__(256) void xprep_wide_kernel(const StackParams p) {
     const int local = job - L.job_start;
     const int g = local / nct, c = local - g * nct;
     switch (L.r) {
-        case 2: xprep_wide_job<2>(L, g, c, nct, lane); break;
-        case 3: xprep_wide_job<3>(L, g, c, nct, lane); break;
-        case 4: xprep_wide_job<4>(L, g, c, nct, lane); break;
-        case 6: xprep_wide_job<6>(L, g, c, nct, lane); break;
-        default: xprep_wide_job<8>(L, g, c, nct, lane); break;
+        case 2: xprep_wide_job<2>(L, g, c, nct, sq, lane); break;
+        case 3: xprep_wide_job<3>(L, g, c, nct, sq, lane); break;
+        case 4: xprep_wide_job<4>(L, g, c, nct, sq, lane); break;
+        case 6: xprep_wide_job<6>(L, g, c, nct, sq, lane); break;
+        default: xprep_wide_job<8>(L, g, c, nct, sq, lane); break;
     }
 }
 
@@ -422,8 +427,7 @@ constexpr int wide_slot_bytes(int R) { return R * 1024 + 256; }  // lane dwords 
 struct WidePlan { int nst, nbr; };
 constexpr int wide_plan_bytes(int R, int C, WidePlan q) { return q.nst * C * kWideBlockBytes + 4 * q.nbr * wide_slot_bytes(R); }
 constexpr WidePlan wide_plan(int R, int C) {
-    constexpr WidePlan order[] = {{4, 3}, {3, 3}, {4, 2}, {3, 2}, {2, 2}};
-    for (WidePlan q : order)
+    for (WidePlan q : {WidePlan{4, 3}, WidePlan{3, 3}, WidePlan{4, 2}, WidePlan{3, 2}, WidePlan{2, 2}})
         if (wide_plan_bytes(R, C, q) <= kWideLdsBytes) return q;
     return {2, 2};
 }
@@ -674,27 +678,41 @@ template <int C> __global__ __launch_bounds__(256, 1) void wide_stack_kernel(con
     });
 }
 
-template <int C> static int wide_resident_groups() {
-    static int cached = 0;
-    if (cached) return cached;
-    constexpr int lds_bytes = wide_lds_bytes_max(C);
+// workgroups the device keeps resident for a launch with lds_bytes of LDS per workgroup
+template <int C> static int wide_resident_groups(int lds_bytes) {
+    static int cached_bytes[2] = {0, 0}, cached[2] = {0, 0};
+    for (int i = 0; i < 2; ++i)
+        if (cached_bytes[i] == lds_bytes) return cached[i];
     int dev = 0, cus = 0, blocks = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(&wide_stack_kernel<C>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
+                            hipFuncAttributeMaxDynamicSharedMemorySize, wide_lds_bytes_max(C)) != hipSuccess)
         return 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, wide_stack_kernel<C>, 256, lds_bytes) != hipSuccess)
         return 0;
     if (blocks < 1) blocks = 1;
     int w = cus * blocks;
     if (w > wide_max_groups(C)) w = wide_max_groups(C);
-    cached = w;
+    const int slot = cached_bytes[0] == 0 ? 0 : 1;
+    cached_bytes[slot] = lds_bytes;
+    cached[slot] = w;
     return w;
 }
 
 template <int C> static hipError_t launch_wide_c(StackParams p, int max_cost, hipStream_t s) {
-    const int hw = wide_resident_groups<C>();
+    // LDS per workgroup: a single layer takes the plan of its width, a stack the largest plan
+    int lds_bytes = wide_lds_bytes_max(C);
+    if (!p.table) {
+        switch (p.single.r) {
+            case 2: lds_bytes = wide_lds_bytes(2, C); break;
+            case 3: lds_bytes = wide_lds_bytes(3, C); break;
+            case 4: lds_bytes = wide_lds_bytes(4, C); break;
+            case 6: lds_bytes = wide_lds_bytes(6, C); break;
+            default: lds_bytes = wide_lds_bytes(8, C); break;
+        }
+    }
+    const int hw = wide_resident_groups<C>(lds_bytes);
     if (hw <= 0) return hipErrorUnknown;
     uint64_t cap = p.cost_total / (uint64_t)max_cost;
     if (cap < 1) cap = 1;
@@ -717,10 +735,10 @@ template <int C> static hipError_t launch_wide_c(StackParams p, int max_cost, hi
     p.nwaves = p.nworkers * 4;
     p.slot_floats = 4 * C * 32 * 64;
     (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
-    hipLaunchKernelGGL(xprep_wide_kernel, dim3((unsigned)((p.n_jobs + 3) / 4)), dim3(256), 0, s, p);
+    hipLaunchKernelGGL(xprep_wide_kernel, dim3((unsigned)p.n_jobs), dim3(256), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(wide_stack_kernel<C>, dim3((unsigned)p.nworkers), dim3(256), wide_lds_bytes_max(C), s, p);
+    hipLaunchKernelGGL(wide_stack_kernel<C>, dim3((unsigned)p.nworkers), dim3(256), lds_bytes, s, p);
     return hipGetLastError();
 }
 
