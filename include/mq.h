@@ -130,7 +130,11 @@ mq_status mq_pack_meta(const mq_half *scales, const mq_half *zeros, int64_t N, i
  *   ws       : device, 256-byte aligned, ws_bytes >= mq_workspace_bytes(M,N,K,r),
  *              initialised once with mq_workspace_init
  * 1 <= M <= MQ_MAX_M.  Results do not depend on the launch shape run to run
- * (partial sums are combined in a fixed order).
+ * (partial sums are combined in a fixed order).  Up to M = 16 every product
+ * x * code is exact in fp32 and scale and zero are applied in fp32 once per
+ * group; for M > 16 the weights are de-quantised to fp16 first (the fp16 operands
+ * of the paper's TensorCore kernel): scale * (S - zero) carries one fp16 rounding,
+ * relative 2^-11, before the fp32 accumulation.
  * Errors: NULL, BAD_R, BAD_SHAPE, BAD_GROUP, ALIGN, BUF_TOO_SMALL, UNSUPPORTED, HIP. */
 mq_status mq_linear(const mq_half *x, int64_t M, const void *packed_W, const mq_half *scales_t,
                     const mq_half *zeros_t, int64_t N, int64_t K, int r, int group, mq_half *y,

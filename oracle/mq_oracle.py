@@ -13,7 +13,7 @@ definitions, in the paper's order, with no blocking, fusion or reordering:
                 product is accumulated in a wider type.  torch.nn.Linear
                 convention: W is [N_out, K_in], y = x @ W^T.
 
-Readings taken where the paper is silent (each is listed in the design doc):
+Readings taken where the paper is silent:
   * rounding mode of Eq. 1: round half up.  Section 3.1 ("Slicing") says the
     r-th bit is decided by the (r+1)-th bit alone and that values are pushed
     into the higher bucket, which is what adding half and flooring does.
