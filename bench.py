@@ -47,9 +47,11 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--layers", type=int, default=32, help="decoder blocks in the stack")
-    ap.add_argument("--workload", default="every-r", choices=["every-r", "mixed-7b", "mixed-70b", "mlp-70b"],
+    ap.add_argument("--workload", default="every-r", choices=["every-r", "mixed-7b", "mixed-70b", "mlp-70b", "parent-7b", "parent-70b"],
                     help="every-r: Llama-2-7B linears at each r (default, the headline); mixed-7b / mixed-70b: one "
-                         "mixed-width stack (mean 3.5 / 4 bits); mlp-70b: batched regime on the Llama-3-70B MLP shapes")
+                         "mixed-width stack (mean 3.5 / 4 bits); mlp-70b: batched regime on the Llama-3-70B MLP shapes; "
+                         "parent-7b / parent-70b: run-time re-slicing of a resident 8-bit parent (mq_reslice, "
+                         "mq_slice_pack) and the stack computed straight from the parent")
     ap.add_argument("--batch", type=int, default=1, help="M for the mixed-* workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-single", action="store_true", help="skip the per-call mq_linear table")
@@ -71,6 +73,8 @@ def main() -> int:
         return bench_mixed_stack(args, mq, synth, torch, np, dev)
     if args.workload == "mlp-70b":
         return bench_mlp_batched(args, mq, synth, torch, np, dev)
+    if args.workload in ("parent-7b", "parent-70b"):
+        return bench_resident_parent(args, mq, synth, torch, np, dev)
     block = synth.LLAMA2_7B_BLOCK
     M = 1
 
@@ -293,6 +297,98 @@ def bench_mixed_stack(args, mq, synth, torch, np, dev):
     out["roofline"] = {"bound": "hbm", "kernel": kernel, "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                        "frac": round(ach / HBM_PEAK_GBPS, 4), "avg_launch_us": round(float(np.mean(us)), 1),
                        "algorithmic_bytes_per_launch": int(nbytes), "traffic": None}
+    out["cpu_baseline"] = None
+    print(json.dumps(out))
+    return 0
+
+
+def bench_resident_parent(args, mq, synth, torch, np, dev):
+    """One resident 8-bit parent, every budget: the mixed-width stack computed from the parent (Eq. 1 in registers,
+    8 bits per weight streamed whatever r is), and the rate at which resident layers are re-sliced to another width."""
+    big = args.workload == "parent-70b"
+    block = synth.LLAMA3_70B_BLOCK if big else synth.LLAMA2_7B_BLOCK
+    n_blocks = (synth.LLAMA3_70B_LAYERS if big else synth.LLAMA2_7B_LAYERS) if args.layers == 32 else args.layers
+    M = args.batch
+    shapes = synth.stack_shapes(block, n_blocks)
+    widths, mean = synth.draw_bitwidths([N * K for (_, _, N, K) in shapes], 4.0 if big else 3.5, seed=0)
+    layers, nbytes, nweights = [], 0.0, 0
+    for i, ((_, _, N, K), r) in enumerate(zip(shapes, widths)):
+        L = synth.make_layer_device(N, K, M, seed=7000 + i, device=dev)
+        st, zt = mq.mq_pack_meta(L["scales"], L["zeros"], K, 128)
+        layers.append(dict(packed_W=mq.mq_pack(L["parent"], 8, 8), scales_t=st, zeros_t=zt, N=N, K=K, r=int(r),
+                           from_parent=1, x=L["x"], y=torch.empty((M, N), dtype=torch.float16, device=dev)))
+        nbytes += algo_bytes(N, K, 8, M)
+        nweights += N * K
+        del L
+    plan = mq.mq_stack_plan(layers, M, device=dev)
+    for _ in range(args.warmup):
+        mq.mq_linear_stack(plan)
+    torch.cuda.synchronize()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        evs[k].record()
+        mq.mq_linear_stack(plan)
+    evs[args.steps].record()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    us = [evs[k].elapsed_time(evs[k + 1]) * 1e3 for k in range(args.steps)]
+    value = nbytes / (ms * 1e-3) / 1e9
+    out = _base_line("stack computed from the resident 8-bit parent (Eq. 1 in registers), effective HBM GB/s", value,
+                     "GB/s", args, ms,
+                     f"{'Llama-3-70B' if big else 'Llama-2-7B'}-shaped stack, {n_blocks} blocks ({len(layers)} linears), "
+                     f"M={M}, per-layer r from {{2,3,4,6,8}} by seed (mean {mean:.3f} bits) applied to the resident parent",
+                     {"M": M, "mean_bits": round(mean, 4), "algorithmic_GB_per_step": round(nbytes / 1e9, 3)})
+    ach = nbytes / float(np.mean(us)) / 1e3
+    out["stack_us_median"] = round(float(np.median(us)), 1)
+    out["frac_of_hbm_peak"] = round(value / HBM_PEAK_GBPS, 4)
+    out["roofline"] = {"bound": "hbm", "kernel": "mq::stack_kernel<%d, 1, true>" % M, "achieved": round(ach, 1),
+                       "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
+                       "avg_launch_us": round(float(np.mean(us)), 1), "algorithmic_bytes_per_launch": int(nbytes),
+                       "traffic": None}
+
+    # re-slicing rate: every distinct shape of the block at every width, over all resident copies of that shape (cold)
+    table, tot = {}, {r: [0.0, 0.0] for r in WIDTHS}
+    for (N, K) in sorted({(N, K) for (_, N, K) in block}):
+        same = [L for L in layers if L["N"] == N and L["K"] == K][:16]
+        for r in WIDTHS:
+            outb = torch.empty(mq.mq_packed_bytes(N, K, r), dtype=torch.uint8, device=dev)
+            mq.mq_reslice(same[0]["packed_W"], N, K, 8, r, out=outb)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for L in same:
+                mq.mq_reslice(L["packed_W"], N, K, 8, r, out=outb)
+            e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) * 1e-3 / len(same)
+            b = (1.0 + r / 8.0) * N * K
+            table[f"reslice:{N}x{K}:r{r}"] = {"us": round(t * 1e6, 1), "GBps": round(b / t / 1e9, 1)}
+            cnt = sum(1 for (_, n, k) in block if (n, k) == (N, K)) * n_blocks
+            tot[r][0] += b * cnt
+            tot[r][1] += t * cnt
+            del outb
+    out["reslice"] = table
+    out["reslice_whole_model"] = {str(r): {"ms": round(tot[r][1] * 1e3, 2), "GBps": round(tot[r][0] / tot[r][1] / 1e9, 1),
+                                           "frac_of_8TBps": round(tot[r][0] / tot[r][1] / 1e9 / HBM_PEAK_GBPS, 4)}
+                                  for r in WIDTHS}
+    # fused slice + pack from a row-major parent (load-time form of the same step), largest shape of the block
+    N, K = max({(N, K) for (_, N, K) in block}, key=lambda nk: nk[0] * nk[1])
+    parent = mq.mq_unpack(layers[[i for i, L in enumerate(layers) if (L["N"], L["K"]) == (N, K)][0]]["packed_W"], N, K, 8, 8)
+    sp = {}
+    for r in WIDTHS:
+        outb = torch.empty(mq.mq_packed_bytes(N, K, r), dtype=torch.uint8, device=dev)
+        mq.mq_slice_pack(parent, 8, r, out=outb)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            mq.mq_slice_pack(parent, 8, r, out=outb)
+        e1.record()
+        torch.cuda.synchronize()
+        t = e0.elapsed_time(e1) * 1e-3 / 5
+        sp[str(r)] = {"us": round(t * 1e6, 1), "GBps": round((1.0 + r / 8.0) * N * K / t / 1e9, 1)}
+    out["slice_pack_%dx%d" % (N, K)] = sp
     out["cpu_baseline"] = None
     print(json.dumps(out))
     return 0

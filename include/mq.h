@@ -108,6 +108,29 @@ mq_status mq_pack(const uint8_t *S, int64_t N, int64_t K, int c, int r, void *pa
 mq_status mq_unpack(const void *packed, int64_t N, int64_t K, int c, int r, uint8_t *S_out,
                     mq_stream stream);
 
+/* ---------------------------------------------------------------- run-time re-slicing
+ * Abstract / Section 1: ONE resident parent checkpoint serves every width; the
+ * width of a layer is chosen when it is used, not when the file is written.
+ * The resident form of the parent is its own 8-bit pack, `packed_parent` =
+ * mq_pack(parent, c = 8, r = 8) (the unsliced codes in the tile layout above).
+ *
+ * mq_slice_pack : Eq. 1 + pack fused, from the row-major parent:
+ *                 packed == mq_pack(mq_slice_codes(parent, 8, r), 8, r), bit for bit,
+ *                 reading 1 byte and writing r/8 bytes per weight.
+ * mq_reslice    : the same result from `packed_parent` (tile layout in, tile
+ *                 layout out; both sides fully coalesced); this is the call that
+ *                 switches a resident layer to another width.
+ *   parent        : device, uint8 [N, K], 8-bit codes
+ *   packed_parent : device, 16-byte aligned, mq_packed_bytes(N,K,8) bytes
+ *   packed        : device, 16-byte aligned, packed_bytes >= mq_packed_bytes(N,K,r);
+ *                   must not overlap packed_parent
+ * Errors: NULL, BAD_R (r not in {2,3,4,6,8} or c != 8), BAD_SHAPE, BAD_GROUP, ALIGN,
+ * BUF_TOO_SMALL. */
+mq_status mq_slice_pack(const uint8_t *parent, int64_t N, int64_t K, int c, int r, void *packed,
+                        size_t packed_bytes, mq_stream stream);
+mq_status mq_reslice(const void *packed_parent, int64_t N, int64_t K, int c, int r, void *packed,
+                     size_t packed_bytes, mq_stream stream);
+
 /* Re-tile the per-group scale and zero-offset (Section 3.2 item 1: computed at
  * the master width c and shared by every r) to match the weight tiles:
  *   scales, zeros     : device, fp16 [N, K/group] row-major
@@ -140,13 +163,28 @@ mq_status mq_linear(const mq_half *x, int64_t M, const void *packed_W, const mq_
                     const mq_half *zeros_t, int64_t N, int64_t K, int r, int group, mq_half *y,
                     void *ws, size_t ws_bytes, mq_stream stream);
 
+/* The same layer computed straight from the resident 8-bit parent: Eq. 1 is
+ * applied to the codes in registers, so any r is served without a packed copy of
+ * its own (8 bits per weight are streamed whatever r is).  Same arithmetic as
+ * mq_linear at M <= 4 (exact products, fp32 accumulation, scale and zero once per
+ * group); the order of the fp32 additions differs from the r-bit layout's, so the
+ * two agree to rounding, not bit for bit.
+ *   packed_parent : device, 16-byte aligned, mq_pack(parent, 8, 8)
+ *   ws            : as for mq_linear, ws_bytes >= mq_workspace_bytes(M,N,K,8)
+ * 1 <= M <= 4 (the vector-ALU path); larger M returns MQ_ERR_UNSUPPORTED: re-slice
+ * with mq_reslice and call mq_linear.  Other arguments and errors as mq_linear. */
+mq_status mq_linear_from_parent(const mq_half *x, int64_t M, const void *packed_parent,
+                                const mq_half *scales_t, const mq_half *zeros_t, int64_t N,
+                                int64_t K, int r, int group, mq_half *y, void *ws,
+                                size_t ws_bytes, mq_stream stream);
+
 /* ---------------------------------------------------------------- stack
  * Sections 3.3 / 5.5: a model is the sliced layers stitched together, one r per
  * layer.  A stack is executed by ONE persistent launch that walks all layers.
  * Layers are independent: each has its own x and y (the attention / activation
  * code between Llama linears is outside this library). */
 typedef struct {
-    const void *packed_W;    /* device, mq_pack(N, K, r) */
+    const void *packed_W;    /* device, mq_pack(N, K, r); the 8-bit pack of the parent if from_parent */
     const mq_half *scales_t; /* device, mq_pack_meta */
     const mq_half *zeros_t;  /* device, mq_pack_meta */
     const mq_half *x;        /* device, fp16 [M, K] */
@@ -154,6 +192,10 @@ typedef struct {
     int64_t N, K;
     int32_t r;     /* 2, 3, 4, 6 or 8 */
     int32_t group; /* 128 */
+    int32_t from_parent; /* 0: packed_W holds r-bit codes.  1: packed_W is the resident 8-bit parent and
+                            Eq. 1 is applied in registers (as mq_linear_from_parent; M <= 4, and all
+                            layers of a stack must agree, else MQ_ERR_UNSUPPORTED) */
+    int32_t reserved;    /* 0 */
 } mq_layer;
 
 /* Bytes of plan workspace for a stack of these layers (host arithmetic; 0 on

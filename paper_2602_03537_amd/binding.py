@@ -12,6 +12,7 @@ __all__ = [
     "MqError", "lib", "lib_path", "MQ_ROW_BLOCK", "MQ_GROUP", "MQ_MAX_M", "STATUS",
     "mq_status_str", "mq_version", "mq_packed_bytes", "mq_meta_bytes", "mq_workspace_bytes",
     "mq_workspace_init", "mq_slice_codes", "mq_pack", "mq_unpack", "mq_pack_meta", "mq_linear",
+    "mq_slice_pack", "mq_reslice", "mq_linear_from_parent",
     "mq_stack_workspace_bytes", "mq_stack_plan", "mq_linear_stack", "MqLayer",
     "new_workspace", "prepare_layer",
 ]
@@ -41,6 +42,7 @@ class MqLayer(ctypes.Structure):
         ("packed_W", ctypes.c_void_p), ("scales_t", ctypes.c_void_p), ("zeros_t", ctypes.c_void_p),
         ("x", ctypes.c_void_p), ("y", ctypes.c_void_p),
         ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("r", ctypes.c_int32), ("group", ctypes.c_int32),
+        ("from_parent", ctypes.c_int32), ("reserved", ctypes.c_int32),
     ]
 
 
@@ -75,6 +77,9 @@ def lib():
         "mq_unpack": (i32, [vp, i64, i64, i32, i32, vp, vp]),
         "mq_pack_meta": (i32, [vp, vp, i64, i64, i32, vp, vp, sz, vp]),
         "mq_linear": (i32, [vp, i64, vp, vp, vp, i64, i64, i32, i32, vp, vp, sz, vp]),
+        "mq_slice_pack": (i32, [vp, i64, i64, i32, i32, vp, sz, vp]),
+        "mq_reslice": (i32, [vp, i64, i64, i32, i32, vp, sz, vp]),
+        "mq_linear_from_parent": (i32, [vp, i64, vp, vp, vp, i64, i64, i32, i32, vp, vp, sz, vp]),
         "mq_stack_workspace_bytes": (sz, [vp, i32, i64]),
         "mq_stack_plan": (i32, [vp, i32, i64, vp, sz, vp]),
         "mq_linear_stack": (i32, [vp, vp]),
@@ -186,11 +191,42 @@ def mq_linear(x, packed_W, scales_t, zeros_t, N: int, K: int, r: int, group: int
     return y
 
 
+def mq_slice_pack(parent, c: int, r: int, out=None, stream=None):
+    """Row-major 8-bit parent -> r-bit pack (Eq. 1 and the pack in one kernel)."""
+    import torch
+    N, K = parent.shape
+    if out is None:
+        out = torch.empty(max(mq_packed_bytes(N, K, r), 16), dtype=torch.uint8, device=parent.device)
+    _check(lib().mq_slice_pack(_ptr(parent), N, K, c, r, _ptr(out), out.numel(), _stream(stream)), "mq_slice_pack")
+    return out
+
+
+def mq_reslice(packed_parent, N: int, K: int, c: int, r: int, out=None, stream=None):
+    """Resident 8-bit pack of the parent -> r-bit pack."""
+    import torch
+    if out is None:
+        out = torch.empty(max(mq_packed_bytes(N, K, r), 16), dtype=torch.uint8, device=packed_parent.device)
+    _check(lib().mq_reslice(_ptr(packed_parent), N, K, c, r, _ptr(out), out.numel(), _stream(stream)), "mq_reslice")
+    return out
+
+
+def mq_linear_from_parent(x, packed_parent, scales_t, zeros_t, N: int, K: int, r: int, group: int, ws, y=None,
+                          stream=None):
+    import torch
+    M = x.shape[0]
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _check(lib().mq_linear_from_parent(_ptr(x), M, _ptr(packed_parent), _ptr(scales_t), _ptr(zeros_t), N, K, r, group,
+                                       _ptr(y), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)),
+           "mq_linear_from_parent")
+    return y
+
+
 def _layer_array(layers: Sequence[dict]):
     arr = (MqLayer * len(layers))()
     for i, L in enumerate(layers):
         arr[i] = MqLayer(_ptr(L["packed_W"]), _ptr(L["scales_t"]), _ptr(L["zeros_t"]), _ptr(L["x"]), _ptr(L["y"]),
-                         L["N"], L["K"], L["r"], L.get("group", MQ_GROUP))
+                         L["N"], L["K"], L["r"], L.get("group", MQ_GROUP), int(L.get("from_parent", 0)), 0)
     return arr
 
 

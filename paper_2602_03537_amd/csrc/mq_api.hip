@@ -55,6 +55,8 @@ mq_status layer_status(const mq_layer &l, int64_t M) {
     if (!valid_pack_r(l.r)) return MQ_ERR_BAD_R;
     if (M < 1 || M > MQ_MAX_M) return MQ_ERR_BAD_SHAPE;
     if (mq_status st = check_shape(l.N, l.K, l.group)) return st;
+    if ((l.from_parent != 0 && l.from_parent != 1) || l.reserved != 0) return MQ_ERR_UNSUPPORTED;
+    if (l.from_parent && use_mfma(M)) return MQ_ERR_UNSUPPORTED;  // slicing in registers: vector-ALU kernels only
     // the MFMA paths read scales / zeros 8 bytes (M <= 16) or 16 bytes (M > 16) at a time
     const size_t meta_align = use_wide(M) ? 16 : use_mfma(M) ? 8 : 2;
     if (!aligned(l.packed_W, 16) || !aligned(l.x, 4) || !aligned(l.scales_t, meta_align) ||
@@ -80,6 +82,11 @@ LayerDesc make_desc(const mq_layer &l, int64_t M, uint64_t cost_start, int cnt_o
     d.RB = (int32_t)(pad_rows(l.N) / kRowBlock);
     d.r = l.r;
     d.cost = tile_cost(l.r);
+    if (l.from_parent) {  // the tiles are those of the 8-bit parent; Eq. 1 to l.r bits happens in registers
+        d.r = kC;
+        d.rs = l.r;
+        d.cost = tile_cost(kC);
+    }
     if (use_wide(M)) {  // scheduled in super-tiles of four row blocks; the matrix-core time of a tile grows with the chunks
         d.RB = (d.RB + 3) / 4;
         d.cost = tile_cost(l.r) + 60 * wide_chunks_per_pass(M);
@@ -98,8 +105,9 @@ struct PlanHeader {
     uint64_t cost_total;
     int32_t n_layers, M, max_cost, n_jobs;
     uint64_t table_off, cnt_off, part_off, total_bytes;
+    int32_t from_parent, reserved;
 };
-constexpr uint64_t kPlanMagic = 0x4d51504c414e3033ull;  // "MQPLAN03"
+constexpr uint64_t kPlanMagic = 0x4d51504c414e3034ull;  // "MQPLAN04"
 
 // Host-side copies of the plan headers, keyed by device address, so that running
 // a stack needs no read-back.  mq_stack_plan overwrites the entry of its address.
@@ -126,6 +134,39 @@ PlanLayout plan_layout(const mq_layer *layers, int n_layers, int64_t M) {
     return p;
 }
 
+// One layer on its own workspace: [counters][partial sums][prepared activations]
+mq_status run_single(const mq_layer &l, int64_t M, void *ws, size_t ws_bytes, mq_stream stream) {
+    if (!ws) return MQ_ERR_NULL;
+    if (mq_status st = layer_status(l, M)) return st;
+    if (!aligned(ws, 256)) return MQ_ERR_ALIGN;
+    const int r_ws = l.from_parent ? kC : l.r;
+    if (ws_bytes < mq_workspace_bytes(M, l.N, l.K, r_ws)) return MQ_ERR_BUF_TOO_SMALL;
+
+    char *base = static_cast<char *>(ws);
+    const size_t cnt_b = counter_bytes(counters_of(M, l.N));
+    char *act = base + cnt_b + partial_bytes(M);
+    StackParams p{};
+    p.table = nullptr;
+    p.n_layers = 1;
+    p.single = make_desc(l, M, 0, 0, 0, use_mfma(M) ? act : nullptr, use_mfma(M) ? act + xt_bytes(M, l.K, l.r) : nullptr);
+    p.cost_total = (uint64_t)p.single.CB * p.single.RB * p.single.G * p.single.cost;
+    p.cnt = reinterpret_cast<int32_t *>(base);
+    p.part = reinterpret_cast<float *>(base + cnt_b);
+    p.M = (int32_t)M;
+    p.slot_floats = slot_floats(M);
+    p.n_jobs = (use_wide(M) ? wide_chunks_padded(M) : p.single.CB) * p.single.G;
+    hipError_t e;
+    if (use_wide(M))
+        e = launch_stack_wide(p, p.single.cost, (hipStream_t)stream);
+    else if (use_mfma(M))
+        e = launch_stack_mfma(p, p.single.cost, (hipStream_t)stream);
+    else if (linear_rb_fits(p.single, partial_bytes(M)))
+        e = launch_linear_rb(p.single, p.part, p.cnt, (hipStream_t)stream);
+    else
+        e = launch_stack(p, p.single.cost, l.from_parent != 0, (hipStream_t)stream);
+    return e == hipSuccess ? MQ_OK : MQ_ERR_HIP;
+}
+
 }  // namespace
 
 extern "C" {
@@ -145,7 +186,7 @@ const char *mq_status_str(int status) {
     return "unknown status";
 }
 
-int mq_version(void) { return 1; }
+int mq_version(void) { return 2; }
 
 size_t mq_packed_bytes(int64_t N, int64_t K, int r) {
     if (!valid_pack_r(r) || check_shape(N, K, kGroup) != MQ_OK) return 0;
@@ -220,35 +261,44 @@ mq_status mq_pack_meta(const mq_half *scales, const mq_half *zeros, int64_t N, i
 mq_status mq_linear(const mq_half *x, int64_t M, const void *packed_W, const mq_half *scales_t,
                     const mq_half *zeros_t, int64_t N, int64_t K, int r, int group, mq_half *y, void *ws,
                     size_t ws_bytes, mq_stream stream) {
-    if (!ws) return MQ_ERR_NULL;
-    mq_layer l{packed_W, scales_t, zeros_t, x, y, N, K, r, group};
-    if (mq_status st = layer_status(l, M)) return st;
-    if (!aligned(ws, 256)) return MQ_ERR_ALIGN;
-    if (ws_bytes < mq_workspace_bytes(M, N, K, r)) return MQ_ERR_BUF_TOO_SMALL;
+    const mq_layer l{packed_W, scales_t, zeros_t, x, y, N, K, r, group, 0, 0};
+    return run_single(l, M, ws, ws_bytes, stream);
+}
 
-    char *base = static_cast<char *>(ws);
-    const size_t cnt_b = counter_bytes(counters_of(M, N));
-    char *act = base + cnt_b + partial_bytes(M);
-    StackParams p{};
-    p.table = nullptr;
-    p.n_layers = 1;
-    p.single = make_desc(l, M, 0, 0, 0, use_mfma(M) ? act : nullptr, use_mfma(M) ? act + xt_bytes(M, K, r) : nullptr);
-    p.cost_total = (uint64_t)p.single.CB * p.single.RB * p.single.G * p.single.cost;
-    p.cnt = reinterpret_cast<int32_t *>(base);
-    p.part = reinterpret_cast<float *>(base + cnt_b);
-    p.M = (int32_t)M;
-    p.slot_floats = slot_floats(M);
-    p.n_jobs = (use_wide(M) ? wide_chunks_padded(M) : p.single.CB) * p.single.G;
-    hipError_t e;
-    if (use_wide(M))
-        e = launch_stack_wide(p, p.single.cost, (hipStream_t)stream);
-    else if (use_mfma(M))
-        e = launch_stack_mfma(p, p.single.cost, (hipStream_t)stream);
-    else if (linear_rb_fits(p.single, partial_bytes(M)))
-        e = launch_linear_rb(p.single, p.part, p.cnt, (hipStream_t)stream);
-    else
-        e = launch_stack(p, p.single.cost, (hipStream_t)stream);
-    return e == hipSuccess ? MQ_OK : MQ_ERR_HIP;
+mq_status mq_linear_from_parent(const mq_half *x, int64_t M, const void *packed_parent, const mq_half *scales_t,
+                                const mq_half *zeros_t, int64_t N, int64_t K, int r, int group, mq_half *y, void *ws,
+                                size_t ws_bytes, mq_stream stream) {
+    const mq_layer l{packed_parent, scales_t, zeros_t, x, y, N, K, r, group, 1, 0};
+    return run_single(l, M, ws, ws_bytes, stream);
+}
+
+mq_status mq_slice_pack(const uint8_t *parent, int64_t N, int64_t K, int c, int r, void *packed, size_t packed_bytes,
+                        mq_stream stream) {
+    if (!parent || !packed) return MQ_ERR_NULL;
+    if (c != kC || !valid_pack_r(r)) return MQ_ERR_BAD_R;
+    if (mq_status st = check_shape(N, K, kGroup)) return st;
+    if (!aligned(packed, 16)) return MQ_ERR_ALIGN;
+    if (packed_bytes < mq_packed_bytes(N, K, r)) return MQ_ERR_BUF_TOO_SMALL;
+    return launch_slice_pack(parent, N, K, r, static_cast<uint4 *>(packed), (hipStream_t)stream) == hipSuccess
+               ? MQ_OK
+               : MQ_ERR_HIP;
+}
+
+mq_status mq_reslice(const void *packed_parent, int64_t N, int64_t K, int c, int r, void *packed, size_t packed_bytes,
+                     mq_stream stream) {
+    if (!packed_parent || !packed) return MQ_ERR_NULL;
+    if (c != kC || !valid_pack_r(r)) return MQ_ERR_BAD_R;
+    if (mq_status st = check_shape(N, K, kGroup)) return st;
+    if (!aligned(packed_parent, 16) || !aligned(packed, 16)) return MQ_ERR_ALIGN;
+    if (packed_bytes < mq_packed_bytes(N, K, r)) return MQ_ERR_BUF_TOO_SMALL;
+    {  // every thread reads its whole tile before it writes, but tiles run in any order: no overlap at all
+        const char *a = static_cast<const char *>(packed_parent), *b = static_cast<const char *>(packed);
+        if (a < b + mq_packed_bytes(N, K, r) && b < a + mq_packed_bytes(N, K, kC)) return MQ_ERR_UNSUPPORTED;
+    }
+    return launch_reslice(static_cast<const uint4 *>(packed_parent), N, K, r, static_cast<uint4 *>(packed),
+                          (hipStream_t)stream) == hipSuccess
+               ? MQ_OK
+               : MQ_ERR_HIP;
 }
 
 size_t mq_stack_workspace_bytes(const mq_layer *layers, int n_layers, int64_t M) {
@@ -262,8 +312,10 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
                         mq_stream stream) {
     if (!layers || !plan) return MQ_ERR_NULL;
     if (n_layers < 1 || n_layers > (1 << 20)) return MQ_ERR_BAD_SHAPE;
-    for (int i = 0; i < n_layers; ++i)
+    for (int i = 0; i < n_layers; ++i) {
         if (mq_status st = layer_status(layers[i], M)) return st;
+        if (layers[i].from_parent != layers[0].from_parent) return MQ_ERR_UNSUPPORTED;  // one kernel variant per launch
+    }
     if (!aligned(plan, 256)) return MQ_ERR_ALIGN;
     const size_t need = mq_stack_workspace_bytes(layers, n_layers, M);
     if (need == 0) return MQ_ERR_BAD_SHAPE;
@@ -298,6 +350,7 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
     h.cnt_off = pl.cnt_off;
     h.part_off = pl.part_off;
     h.total_bytes = pl.total;
+    h.from_parent = layers[0].from_parent;
 
     hipStream_t s = (hipStream_t)stream;
     char *base = static_cast<char *>(plan);
@@ -343,7 +396,7 @@ mq_status mq_linear_stack(void *plan, mq_stream stream) {
     p.n_jobs = h.n_jobs;
     const hipError_t e = use_wide(h.M)   ? launch_stack_wide(p, h.max_cost, (hipStream_t)stream)
                          : use_mfma(h.M) ? launch_stack_mfma(p, h.max_cost, (hipStream_t)stream)
-                                         : launch_stack(p, h.max_cost, (hipStream_t)stream);
+                                         : launch_stack(p, h.max_cost, h.from_parent != 0, (hipStream_t)stream);
     return e == hipSuccess ? MQ_OK : MQ_ERR_HIP;
 }
 

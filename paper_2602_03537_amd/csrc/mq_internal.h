@@ -57,6 +57,8 @@ struct LayerDesc {
     int32_t M;              // batch rows of x
     int32_t CB;             // column chunks: 1 on the vector-ALU path, ceil(M/16) on the MFMA path; wide path: passes
     int32_t job_start;      // prep kernel: sum of CB*G over the preceding layers
+    int32_t rs;             // 0, or: Wp is the 8-bit parent (r == 8) and Eq. 1 to rs bits is applied in registers
+    int32_t reserved;
     uint64_t cost_start;    // sum of CB*RB*G*cost over the preceding layers
 };
 
@@ -96,11 +98,14 @@ inline int64_t pad_rows(int64_t N) { return (N + kRowBlock - 1) / kRowBlock * kR
 hipError_t launch_slice(const uint8_t *parent, int64_t n, int c, int r, uint8_t *out, hipStream_t s);
 hipError_t launch_pack(const uint8_t *S, int64_t N, int64_t K, int r, uint4 *packed, hipStream_t s);
 hipError_t launch_unpack(const uint4 *packed, int64_t N, int64_t K, int r, uint8_t *S, hipStream_t s);
+hipError_t launch_slice_pack(const uint8_t *parent, int64_t N, int64_t K, int r, uint4 *packed, hipStream_t s);
+hipError_t launch_reslice(const uint4 *parent8, int64_t N, int64_t K, int r, uint4 *packed, hipStream_t s);
 hipError_t launch_pack_meta(const _Float16 *sc, const _Float16 *zr, int64_t N, int64_t G, _Float16 *st,
                             _Float16 *zt, hipStream_t s);
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
 // Fills p.nwaves and launches (vector-ALU path, M <= kValuMaxM).  max_cost = largest tile cost in the stack.
-hipError_t launch_stack(StackParams p, int max_cost, hipStream_t s);
+// from_parent: every layer has rs != 0 (the kernel variant that slices in registers).
+hipError_t launch_stack(StackParams p, int max_cost, bool from_parent, hipStream_t s);
 // Single layer, M <= kValuMaxM: one workgroup per (row block, K slice); see mq_linear.hip.
 bool linear_rb_fits(const LayerDesc &L, size_t part_bytes);
 hipError_t launch_linear_rb(const LayerDesc &L, float *part, int32_t *cnt, hipStream_t s);

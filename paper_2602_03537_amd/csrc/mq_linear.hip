@@ -41,12 +41,33 @@ __device__ __forceinline__ void load_tile(TileRegs<R, M> &t, const LayerDesc &L,
         t.xl[m] = gl(reinterpret_cast<const uint32_t *>(L.x + (size_t)m * L.K + (size_t)g * kGroup))[lane];
 }
 
+// Eq. 1 on the two 8-bit codes of a masked pair (one per 16-bit half), in 8-bit units:
+//   S = min((q + 2^(sh-1)) & ~(2^sh - 1), 256 - 2^sh),  sh = 8 - rs
+// (rounding half up; q + 2^(sh-1) < 256 + 2^sh, so the only value above the top code is 256 itself).
+typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+struct SliceConst {
+    uint32_t half2, keep2;
+    u16x2 cap2;
+};
+__device__ __forceinline__ SliceConst slice_const(int rs) {
+    const uint32_t low = (1u << (kC - rs)) - 1;  // the bits Eq. 1 drops
+    const uint16_t cap = (uint16_t)(255u - low);
+    return {((low + 1) >> 1) * 0x10001u, (0x1FFu & ~low) * 0x10001u, {cap, cap}};
+}
+__device__ __forceinline__ uint32_t slice_pair(uint32_t v, const SliceConst &c) {
+    const u16x2 t = __builtin_bit_cast(u16x2, (v + c.half2) & c.keep2);
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(t, c.cap2));
+}
+
 // xlds: this wave's M x 64 dwords of LDS (kXLds only)
-template <int R, int M, int XP>
+// SL (R == 8 only): the tile holds the unsliced parent; its codes are sliced to L.rs bits first.
+template <int R, int M, int XP, bool SL = false>
 __device__ __forceinline__ void tile_math(const TileRegs<R, M> &t, const LayerDesc &L, int g, int lane,
                                           uint32_t *xlds, float (&yacc)[M]) {
     using T = Layout<R>;
+    static_assert(!SL || R == kC, "slicing in registers starts from the 8-bit parent");
     constexpr int NU = 4 * R / T::UD;
+    const SliceConst sc = slice_const(SL ? L.rs : kC);
     float xg[M];
     cptr32 xs[M];
 #pragma unroll
@@ -78,6 +99,7 @@ __device__ __forceinline__ void tile_math(const TileRegs<R, M> &t, const LayerDe
                         uint32_t v = t.w[un * T::UD + o.dw];
                         if constexpr (o.sh != 0) v >>= o.sh;
                         v &= (uint32_t)o.mask * 0x10001u;
+                        if constexpr (SL) v = slice_pair(v, sc);
 #pragma unroll
                         for (int m = 0; m < M; ++m) acc[m][key] = dot2(v, xq[m][pidx % 4], acc[m][key]);
                     }
@@ -92,6 +114,7 @@ __device__ __forceinline__ void tile_math(const TileRegs<R, M> &t, const LayerDe
                 uint32_t v = t.w[un * T::UD + o.dw];
                 if constexpr (o.sh != 0) v >>= o.sh;
                 v &= (uint32_t)o.mask * 0x10001u;
+                if constexpr (SL) v = slice_pair(v, sc);
 #pragma unroll
                 for (int m = 0; m < M; ++m) acc[m][key] = dot2(v, xs[m][un * T::PPU + o.pair], acc[m][key]);
             });
@@ -118,7 +141,7 @@ template <int R> struct PrefetchDepth {
 };
 
 // Tiles [u_begin, u_end) of one layer, owned by share `wave`.
-template <int R, int M, int XP>
+template <int R, int M, int XP, bool SL = false>
 __device__ __forceinline__ void run_units(const LayerDesc &L, const StackParams &p, int u_begin, int u_end, int wave,
                                           int lane, uint32_t *xlds) {
     constexpr int D = PrefetchDepth<R>::value, NB = D + 1;
@@ -147,7 +170,7 @@ __device__ __forceinline__ void run_units(const LayerDesc &L, const StackParams 
         static_for<NB>([&](auto j) {
             if (u >= u_end) return;
             prefetch(buf[(j + D) % NB]);
-            tile_math<R, M, XP>(buf[j], L, g, lane, xlds, yacc);
+            tile_math<R, M, XP, SL>(buf[j], L, g, lane, xlds, yacc);
             ++g;
             ++u;
             if (g == L.G || u == u_end) {
@@ -168,7 +191,8 @@ __device__ __forceinline__ void run_units(const LayerDesc &L, const StackParams 
     }
 }
 
-template <int M, int XP> __global__ __launch_bounds__(256) void stack_kernel(const StackParams p) {
+// SL: every layer of the stack is computed from its resident 8-bit parent (LayerDesc::rs).
+template <int M, int XP, bool SL = false> __global__ __launch_bounds__(256) void stack_kernel(const StackParams p) {
     __shared__ __attribute__((aligned(16))) uint32_t xlds_all[XP == kXLds ? 4 * M * 64 : 4];
     uint32_t *xlds = xlds_all + (XP == kXLds ? (threadIdx.x >> 6) * M * 64 : 0);
     const int lane = threadIdx.x & 63;
@@ -176,12 +200,16 @@ template <int M, int XP> __global__ __launch_bounds__(256) void stack_kernel(con
     if (wave >= p.nwaves) return;
     for (int worker = wave; worker < p.nworkers; worker += p.nwaves) {
         walk_tiles(p, worker, [&](const LayerDesc &L, int u_begin, int u_end) {
-            switch (L.r) {
-                case 2: run_units<2, M, XP>(L, p, u_begin, u_end, worker, lane, xlds); break;
-                case 3: run_units<3, M, XP>(L, p, u_begin, u_end, worker, lane, xlds); break;
-                case 4: run_units<4, M, XP>(L, p, u_begin, u_end, worker, lane, xlds); break;
-                case 6: run_units<6, M, XP>(L, p, u_begin, u_end, worker, lane, xlds); break;
-                default: run_units<8, M, XP>(L, p, u_begin, u_end, worker, lane, xlds); break;
+            if constexpr (SL) {
+                run_units<8, M, XP, true>(L, p, u_begin, u_end, worker, lane, xlds);
+            } else {
+                switch (L.r) {
+                    case 2: run_units<2, M, XP>(L, p, u_begin, u_end, worker, lane, xlds); break;
+                    case 3: run_units<3, M, XP>(L, p, u_begin, u_end, worker, lane, xlds); break;
+                    case 4: run_units<4, M, XP>(L, p, u_begin, u_end, worker, lane, xlds); break;
+                    case 6: run_units<6, M, XP>(L, p, u_begin, u_end, worker, lane, xlds); break;
+                    default: run_units<8, M, XP>(L, p, u_begin, u_end, worker, lane, xlds); break;
+                }
             }
         });
     }
@@ -196,7 +224,7 @@ template <int M, int XP> __global__ __launch_bounds__(256) void stack_kernel(con
 // through LDS in wave order, and -- only if K is cut into KS > 1 slices -- hand over to the
 // last-arriving slice through KS slots (same deterministic protocol as the stack kernel, with
 // KS <= 8 contributors instead of up to G).
-template <int R, int M, int XP>
+template <int R, int M, int XP, bool SL = false>
 __global__ __launch_bounds__(1024) void linear_rb_kernel(const LayerDesc L, const int KS, float *part, int32_t *cnt) {
     __shared__ float red[16][M][64];
     __shared__ __attribute__((aligned(16))) uint32_t xlds_all[XP == kXLds ? 16 * M * 64 : 4];
@@ -215,7 +243,7 @@ __global__ __launch_bounds__(1024) void linear_rb_kernel(const LayerDesc L, cons
         while (true) {
             const int g2 = g + W;
             if (g2 < g_hi) load_tile<R, M>(nxt, L, rb * L.G + g2, g2, lane);
-            tile_math<R, M, XP>(cur, L, g, lane, xlds, yacc);
+            tile_math<R, M, XP, SL>(cur, L, g, lane, xlds, yacc);
             if (g2 >= g_hi) break;
             cur = nxt;
             g = g2;
@@ -278,16 +306,18 @@ static int pick_k_slices(const LayerDesc &L) {
     return ks < 1 ? 1 : ks;
 }
 
-template <int R, int M>
+template <int R, int M, bool SL = false>
 static hipError_t launch_linear_rb_rm(const LayerDesc &L, float *part, int32_t *cnt, hipStream_t s) {
     const int KS = pick_k_slices(L);
     const int per_block = (L.G + KS - 1) / KS;
     const int W = (per_block >= 24 || (KS == 1 && per_block >= 12)) ? 16 : per_block >= 6 ? 8 : 4;
     (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
-    hipLaunchKernelGGL((linear_rb_kernel<R, M, kXLds>), dim3((unsigned)(L.RB * KS)), dim3(64 * W), 0, s, L, KS, part, cnt);
+    hipLaunchKernelGGL((linear_rb_kernel<R, M, kXLds, SL>), dim3((unsigned)(L.RB * KS)), dim3(64 * W), 0, s, L, KS, part,
+                       cnt);
     return hipGetLastError();
 }
 template <int M> static hipError_t launch_linear_rb_m(const LayerDesc &L, float *part, int32_t *cnt, hipStream_t s) {
+    if (L.rs) return launch_linear_rb_rm<8, M, true>(L, part, cnt, s);
     switch (L.r) {
         case 2: return launch_linear_rb_rm<2, M>(L, part, cnt, s);
         case 3: return launch_linear_rb_rm<3, M>(L, part, cnt, s);
@@ -314,13 +344,13 @@ hipError_t launch_linear_rb(const LayerDesc &L, float *part, int32_t *cnt, hipSt
 }
 
 // blocks (of 4 waves) the device keeps resident per compute unit, and the number of units
-template <int M, int XP> static bool residency(int &cus, int &blocks) {
+template <int M, int XP, bool SL> static bool residency(int &cus, int &blocks) {
     static int c_cus = 0, c_blocks = 0;
     if (!c_cus) {
         int dev = 0, a = 0, b = 0;
         if (hipGetDevice(&dev) != hipSuccess) return false;
         if (hipDeviceGetAttribute(&a, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&b, stack_kernel<M, XP>, 256, 0) != hipSuccess) return false;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&b, stack_kernel<M, XP, SL>, 256, 0) != hipSuccess) return false;
         if (b < 1) b = 1;
         while (a * b * 4 > kMaxWaves) --b;
         c_cus = a;
@@ -331,9 +361,9 @@ template <int M, int XP> static bool residency(int &cus, int &blocks) {
     return true;
 }
 
-template <int M, int XP> static hipError_t launch_stack_mx(StackParams p, int max_cost, hipStream_t s) {
+template <int M, int XP, bool SL> static hipError_t launch_stack_mx(StackParams p, int max_cost, hipStream_t s) {
     int cus = 0, blocks = 0;
-    if (!residency<M, XP>(cus, blocks)) return hipErrorUnknown;
+    if (!residency<M, XP, SL>(cus, blocks)) return hipErrorUnknown;
     const int hw = cus * blocks * 4;
     // every share must be at least one tile long, so that each share between the first
     // and last contributor of a row block really owns a tile of it
@@ -355,19 +385,20 @@ template <int M, int XP> static hipError_t launch_stack_mx(StackParams p, int ma
     p.nworkers = (int)(spw * (uint64_t)p.nwaves);
     const unsigned nblocks = (unsigned)((p.nwaves + 3) / 4);
     (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
-    hipLaunchKernelGGL((stack_kernel<M, XP>), dim3(nblocks), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((stack_kernel<M, XP, SL>), dim3(nblocks), dim3(256), 0, s, p);
     return hipGetLastError();
 }
-template <int M> static hipError_t launch_stack_m(StackParams p, int max_cost, hipStream_t s) {
-    return launch_stack_mx<M, kXLds>(p, max_cost, s);  // measured 1-3 % (stack) to 20 % (single calls) faster than kXScalar
+template <int M> static hipError_t launch_stack_m(StackParams p, int max_cost, bool from_parent, hipStream_t s) {
+    // kXLds: measured 1-3 % (stack) to 20 % (single calls) faster than kXScalar
+    return from_parent ? launch_stack_mx<M, kXLds, true>(p, max_cost, s) : launch_stack_mx<M, kXLds, false>(p, max_cost, s);
 }
 
-hipError_t launch_stack(StackParams p, int max_cost, hipStream_t s) {
+hipError_t launch_stack(StackParams p, int max_cost, bool from_parent, hipStream_t s) {
     switch (p.M) {
-        case 1: return launch_stack_m<1>(p, max_cost, s);
-        case 2: return launch_stack_m<2>(p, max_cost, s);
-        case 3: return launch_stack_m<3>(p, max_cost, s);
-        case 4: return launch_stack_m<4>(p, max_cost, s);
+        case 1: return launch_stack_m<1>(p, max_cost, from_parent, s);
+        case 2: return launch_stack_m<2>(p, max_cost, from_parent, s);
+        case 3: return launch_stack_m<3>(p, max_cost, from_parent, s);
+        case 4: return launch_stack_m<4>(p, max_cost, from_parent, s);
     }
     return hipErrorInvalidValue;
 }

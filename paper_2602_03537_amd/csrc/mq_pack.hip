@@ -1,6 +1,8 @@
-// Slice, pack, unpack and meta re-tiling kernels (load-time steps of the path).
-//   slice : Eq. 1 (Section 2), elementwise on bytes
-//   pack  : Section 4's offline reorder, into the tile layout of mq_layout.h
+// Slice, pack, unpack and meta re-tiling kernels (load-time steps of the path), and the
+// run-time re-slice of a resident parent.
+//   slice   : Eq. 1 (Section 2), elementwise on bytes
+//   pack    : Section 4's offline reorder, into the tile layout of mq_layout.h
+//   reslice : Eq. 1 + pack on a parent that is already in the tile layout (8-bit pack)
 #include "mq_internal.h"
 #include "mq_static_for.h"
 
@@ -51,7 +53,8 @@ hipError_t launch_slice(const uint8_t *parent, int64_t n, int c, int r, uint8_t 
 
 // ------------------------------------------------------------------ pack
 // One thread per (row block, group, lane): reads its row's 128 codes, emits 4R dwords.
-template <int R>
+// SL: the input is the unsliced 8-bit parent and Eq. 1 is applied on the way (slice + pack fused).
+template <int R, bool SL>
 __global__ __launch_bounds__(256) void pack_kernel(const uint8_t *__restrict__ S, uint4 *__restrict__ packed, int N,
                                                    int64_t K, int G, int64_t ntiles) {
     using T = Layout<R>;
@@ -67,7 +70,14 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint8_t *__restrict__ S
     if (n < N) {
         const uint8_t *src = S + n * K + (int64_t)g * kGroup;
 #pragma unroll
-        for (int i = 0; i < kGroup; ++i) code[i] = src[i] >> (kC - R);
+        for (int i = 0; i < kGroup; ++i) {
+            if constexpr (SL && R < kC) {
+                const uint32_t t = ((uint32_t)src[i] + (1u << (kC - R - 1))) >> (kC - R);
+                code[i] = (uint8_t)(t < (1u << R) - 1 ? t : (1u << R) - 1);
+            } else {
+                code[i] = src[i] >> (kC - R);
+            }
+        }
     } else {
 #pragma unroll
         for (int i = 0; i < kGroup; ++i) code[i] = 0;
@@ -87,6 +97,59 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint8_t *__restrict__ S
                 const uint32_t t = code[2 * (un * T::PPU + o.pair) + h];
                 dw[un * T::UD + o.dw] |= ((t >> o.d) & fm) << (p + o.sh + 16 * h);
             }
+        });
+    });
+    uint4 *dst = packed + tile * (R * 64) + lane;
+#pragma unroll
+    for (int i = 0; i < R; ++i) dst[i * 64] = make_uint4(dw[4 * i], dw[4 * i + 1], dw[4 * i + 2], dw[4 * i + 3]);
+}
+
+// ------------------------------------------------------------------ re-slice
+// Tile layout in (the 8-bit pack of the parent), tile layout out (r bits): one thread per (tile, lane).
+// A lane dword of the parent holds pair 2j in the low bytes of its halves and pair 2j+1 in the high
+// bytes; Eq. 1 is applied to both columns of a pair at once in their 16-bit containers, and the r-bit
+// indices go to their fields of Layout<R> with the same shifts for both halves.
+typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+template <int R> __device__ __forceinline__ uint32_t slice_pair_index(uint32_t v) {
+    if constexpr (R == kC) return v;
+    constexpr int sh = kC - R;
+    u16x2 t = __builtin_bit_cast(u16x2, v + (0x10001u << (sh - 1)));
+    t = t >> (uint16_t)sh;
+    const u16x2 cap = {(uint16_t)((1 << R) - 1), (uint16_t)((1 << R) - 1)};
+    t = __builtin_elementwise_min(t, cap);
+    return __builtin_bit_cast(uint32_t, t);
+}
+
+template <int R>
+__global__ __launch_bounds__(256) void reslice_kernel(const uint4 *__restrict__ parent8, uint4 *__restrict__ packed,
+                                                      int64_t ntiles) {
+    using T = Layout<R>;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int64_t tile = tid >> 6;
+    if (tile >= ntiles) return;
+    uint32_t q[4 * kC];
+    const uint4 *src = parent8 + tile * (kC * 64) + lane;
+#pragma unroll
+    for (int i = 0; i < kC; ++i) {
+        const uint4 v = src[i * 64];
+        q[4 * i] = v.x; q[4 * i + 1] = v.y; q[4 * i + 2] = v.z; q[4 * i + 3] = v.w;
+    }
+    uint32_t dw[4 * R];
+#pragma unroll
+    for (int i = 0; i < 4 * R; ++i) dw[i] = 0;
+    constexpr int NU = 4 * R / T::UD;
+    static_for<NU>([&](auto un) {
+        static_for<T::NOPS>([&](auto oi) {
+            constexpr Op o = T::op(oi);
+            constexpr int pidx = un * T::PPU + o.pair;  // activation pair of the group, 0..63
+            constexpr int p = ctz16(o.mask);
+            constexpr uint32_t fm = (uint32_t)(o.mask >> p) * 0x10001u;
+            const uint32_t two = pidx & 1 ? (q[pidx >> 1] >> 8) & 0x00FF00FFu : q[pidx >> 1] & 0x00FF00FFu;
+            uint32_t t = slice_pair_index<R>(two);
+            if constexpr (o.d != 0) t >>= o.d;
+            if constexpr (popc16(o.mask) != R) t &= fm;
+            dw[un * T::UD + o.dw] |= t << (p + o.sh);
         });
     });
     uint4 *dst = packed + tile * (R * 64) + lane;
@@ -135,13 +198,21 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint4 *__restrict__ p
     for (int i = 0; i < kGroup; ++i) dst[i] = (uint8_t)(code[i] << (kC - R));
 }
 
-template <int R>
+template <int R, bool SL>
 static hipError_t launch_pack_r(const uint8_t *S, int64_t N, int64_t K, uint4 *packed, hipStream_t s) {
     const int G = (int)(K / kGroup);
     const int64_t ntiles = pad_rows(N) / kRowBlock * G;
     const int64_t blocks = (ntiles * 64 + 255) / 256;
     (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
-    hipLaunchKernelGGL(pack_kernel<R>, dim3((unsigned)blocks), dim3(256), 0, s, S, packed, (int)N, K, G, ntiles);
+    hipLaunchKernelGGL((pack_kernel<R, SL>), dim3((unsigned)blocks), dim3(256), 0, s, S, packed, (int)N, K, G, ntiles);
+    return hipGetLastError();
+}
+template <int R>
+static hipError_t launch_reslice_r(const uint4 *parent8, int64_t N, int64_t K, uint4 *packed, hipStream_t s) {
+    const int64_t ntiles = pad_rows(N) / kRowBlock * (K / kGroup);
+    const int64_t blocks = (ntiles * 64 + 255) / 256;
+    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
+    hipLaunchKernelGGL(reslice_kernel<R>, dim3((unsigned)blocks), dim3(256), 0, s, parent8, packed, ntiles);
     return hipGetLastError();
 }
 template <int R>
@@ -156,11 +227,31 @@ static hipError_t launch_unpack_r(const uint4 *packed, int64_t N, int64_t K, uin
 
 hipError_t launch_pack(const uint8_t *S, int64_t N, int64_t K, int r, uint4 *packed, hipStream_t s) {
     switch (r) {
-        case 2: return launch_pack_r<2>(S, N, K, packed, s);
-        case 3: return launch_pack_r<3>(S, N, K, packed, s);
-        case 4: return launch_pack_r<4>(S, N, K, packed, s);
-        case 6: return launch_pack_r<6>(S, N, K, packed, s);
-        case 8: return launch_pack_r<8>(S, N, K, packed, s);
+        case 2: return launch_pack_r<2, false>(S, N, K, packed, s);
+        case 3: return launch_pack_r<3, false>(S, N, K, packed, s);
+        case 4: return launch_pack_r<4, false>(S, N, K, packed, s);
+        case 6: return launch_pack_r<6, false>(S, N, K, packed, s);
+        case 8: return launch_pack_r<8, false>(S, N, K, packed, s);
+    }
+    return hipErrorInvalidValue;
+}
+hipError_t launch_slice_pack(const uint8_t *parent, int64_t N, int64_t K, int r, uint4 *packed, hipStream_t s) {
+    switch (r) {
+        case 2: return launch_pack_r<2, true>(parent, N, K, packed, s);
+        case 3: return launch_pack_r<3, true>(parent, N, K, packed, s);
+        case 4: return launch_pack_r<4, true>(parent, N, K, packed, s);
+        case 6: return launch_pack_r<6, true>(parent, N, K, packed, s);
+        case 8: return launch_pack_r<8, true>(parent, N, K, packed, s);
+    }
+    return hipErrorInvalidValue;
+}
+hipError_t launch_reslice(const uint4 *parent8, int64_t N, int64_t K, int r, uint4 *packed, hipStream_t s) {
+    switch (r) {
+        case 2: return launch_reslice_r<2>(parent8, N, K, packed, s);
+        case 3: return launch_reslice_r<3>(parent8, N, K, packed, s);
+        case 4: return launch_reslice_r<4>(parent8, N, K, packed, s);
+        case 6: return launch_reslice_r<6>(parent8, N, K, packed, s);
+        case 8: return launch_reslice_r<8>(parent8, N, K, packed, s);
     }
     return hipErrorInvalidValue;
 }

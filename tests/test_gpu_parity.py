@@ -549,3 +549,143 @@ def test_stack_llama3_70b_full_mixed_widths_mean_4(M):
         _check_sampled(gen, layers, i, 64 if block in (0, 39, 79) else 6, rng, f"70B stack M={M}")
     del gen, layers, plan
     torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------ run-time re-slicing of a resident parent
+def _resident(L):
+    """host layer -> (8-bit pack of the unsliced parent, tiled scales, tiled zeros) on the device."""
+    N, K = L["parent"].shape
+    p8 = mq.mq_pack(dev(L["parent"]), C, 8)
+    st, zt = mq.mq_pack_meta(dev(L["scales"]), dev(L["zeros"]), K, 128)
+    return p8, st, zt
+
+
+def _every_code_parent(N, K, rng):
+    """all 256 code values next to each other, rounding ties and the clamp region of Eq. 1 in every row"""
+    q = (np.arange(N)[:, None] * 37 + np.arange(K)[None, :]) % 256
+    q[rng.integers(0, N, N // 2 + 1), rng.integers(0, K, N // 2 + 1)] = 255
+    return q.astype(np.uint8)
+
+
+@pytest.mark.parametrize("r", WIDTHS)
+@pytest.mark.parametrize("shape", [(64, 128), (1, 128), (130, 384), (200, 1280), (448, 2048)])
+def test_slice_pack_and_reslice_bit_exact(r, shape):
+    N, K = shape
+    rng = np.random.default_rng([60, r, N, K])
+    for name, parent in (("uniform", rng.integers(0, 256, (N, K), dtype=np.uint8)),
+                         ("every code", _every_code_parent(N, K, rng)),
+                         ("quantiser", synth.make_layer(N, K, seed=[60, N, K])["parent"])):
+        ref = pack_ref(oracle.slice_codes(parent, C, r), r)
+        fused = mq.mq_slice_pack(dev(parent), C, r)
+        assert np.array_equal(fused.cpu().numpy(), ref), ("slice_pack", name, r, shape)
+        p8 = mq.mq_pack(dev(parent), C, 8)
+        out = torch.full((ref.size + 32,), 0xAB, dtype=torch.uint8, device=DEV)
+        mq.mq_reslice(p8, N, K, C, r, out=out[16:16 + ref.size])
+        torch.cuda.synchronize()
+        o = out.cpu().numpy()
+        assert np.array_equal(o[16:16 + ref.size], ref), ("reslice", name, r, shape)
+        assert (o[:16] == 0xAB).all() and (o[16 + ref.size:] == 0xAB).all()     # guard bytes untouched
+
+
+def test_reslice_rejects_bad_arguments_loudly():
+    parent = np.zeros((64, 128), np.uint8)
+    p8 = mq.mq_pack(dev(parent), C, 8)
+    with pytest.raises(mq.MqError):
+        mq.mq_reslice(p8, 64, 128, C, 5)                          # width without a layout
+    with pytest.raises(mq.MqError):
+        mq.mq_reslice(p8, 64, 128, 7, 4)                          # c != 8
+    with pytest.raises(mq.MqError):
+        mq.mq_reslice(p8, 64, 128, C, 4, out=p8[:4096])           # in place is not supported
+    with pytest.raises(mq.MqError):
+        mq.mq_reslice(p8, 64, 128, C, 4, out=torch.empty(100, dtype=torch.uint8, device=DEV))
+    with pytest.raises(mq.MqError):
+        mq.mq_slice_pack(dev(parent), C, 4, out=torch.empty(100, dtype=torch.uint8, device=DEV))
+
+
+@pytest.mark.parametrize("r", WIDTHS)
+@pytest.mark.parametrize("shape_m", [(64, 128, 1), (1, 128, 1), (130, 384, 2), (200, 1280, 3), (448, 2048, 4),
+                                     (4096, 512, 1), (512, 14336, 1)])
+def test_linear_from_parent_matches_oracle_and_the_repacked_layer(r, shape_m):
+    # (4096, 512) runs the low-latency kernel unsplit, (512, 14336) the stream-K kernel with hand-over
+    N, K, M = shape_m
+    L = synth.make_layer(N, K, M=M, seed=[61, N, K])
+    p8, st, zt = _resident(L)
+    x = dev(L["x"])
+    ws = mq.new_workspace(M, N, K, 8)
+    y = mq.mq_linear_from_parent(x, p8, st, zt, N, K, r, 128, ws)
+    torch.cuda.synchronize()
+    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"from parent {shape_m} r={r}")
+    # the re-packed layer computes the same sums in another order: equal to fp32 rounding
+    pr = mq.mq_reslice(p8, N, K, C, r)
+    y2 = mq.mq_linear(x, pr, st, zt, N, K, r, 128, mq.new_workspace(M, N, K, r))
+    assert torch.allclose(y.float(), y2.float(), rtol=2e-3, atol=2e-3)
+
+
+@pytest.mark.parametrize("r", WIDTHS)
+def test_linear_from_parent_every_code_and_fractional_zeros(r):
+    L = synth.make_random_codes_layer(192, 640, M=2, seed=[62, r])
+    L["parent"] = _every_code_parent(192, 640, np.random.default_rng(62))
+    p8, st, zt = _resident(L)
+    y = mq.mq_linear_from_parent(dev(L["x"]), p8, st, zt, 192, 640, r, 128, mq.new_workspace(2, 192, 640, 8))
+    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"every code r={r}")
+
+
+def test_linear_from_parent_batch_above_four_is_refused():
+    L = synth.make_layer(64, 128, M=8, seed=[63])
+    p8, st, zt = _resident(L)
+    with pytest.raises(mq.MqError) as e:
+        mq.mq_linear_from_parent(dev(L["x"]), p8, st, zt, 64, 128, 4, 128, mq.new_workspace(8, 64, 128, 8))
+    assert e.value.status == 8
+
+
+@pytest.mark.parametrize("M", [1, 3])
+def test_stack_from_parent_mixed_widths(M):
+    shapes_r = [(256, 512, 2), (64, 128, 8), (200, 1280, 3), (512, 256, 6), (130, 384, 4), (1024, 1024, 3),
+                (63, 128, 2), (320, 640, 8)]
+    host, layers = [], []
+    for i, (N, K, r) in enumerate(shapes_r):
+        L = synth.make_layer(N, K, M=M, seed=[64, i, N, K])
+        p8, st, zt = _resident(L)
+        layers.append(dict(packed_W=p8, scales_t=st, zeros_t=zt, N=N, K=K, r=r, from_parent=1, x=dev(L["x"]),
+                           y=torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV)))
+        host.append(dict(L, r=r))
+    plan = mq.mq_stack_plan(layers, M)
+    refs = oracle.linear_stack(host, C, 128)
+    for rep in range(2):
+        for lay in layers:
+            lay["y"].fill_(float("nan"))
+        mq.mq_linear_stack(plan)
+        torch.cuda.synchronize()
+        for i, (lay, ref) in enumerate(zip(layers, refs)):
+            check_y(lay["y"], ref, f"from-parent stack layer {i} rep {rep}")
+    # a different budget from the same resident parents: only the plan changes
+    for lay, hl in zip(layers, host):
+        lay["r"] = hl["r"] = 4
+    plan4 = mq.mq_stack_plan(layers, M)
+    mq.mq_linear_stack(plan4)
+    torch.cuda.synchronize()
+    for i, (lay, ref) in enumerate(zip(layers, oracle.linear_stack(host, C, 128))):
+        check_y(lay["y"], ref, f"from-parent stack at 4 bits, layer {i}")
+    mixed = [dict(l) for l in layers]
+    mixed[1]["from_parent"] = 0
+    with pytest.raises(mq.MqError):
+        mq.mq_stack_plan(mixed, M)
+
+
+def test_from_parent_llama3_70b_down_projection_sampled_rows_and_full_reslice():
+    # 8192 x 28672: more tiles than the low-latency kernel takes, so the stream-K kernel with hand-over runs
+    N, K = 8192, 28672
+    L = synth.make_layer(N, K, M=2, seed=[65])
+    rng = np.random.default_rng(66)
+    rows = np.unique(np.concatenate([[0, 63, 64, N - 1], rng.integers(0, N, 124)]))
+    p8, st, zt = _resident(L)
+    for M in (1, 2):
+        ws = mq.new_workspace(M, N, K, 8)
+        for r in (2, 3, 6):
+            y = mq.mq_linear_from_parent(dev(L["x"][:M]), p8, st, zt, N, K, r, 128, ws)
+            ref = oracle.linear_rows(L["x"][:M], L["parent"], L["scales"], L["zeros"], C, r, 128, rows)
+            check_y(y[:, torch.from_numpy(rows).to(DEV)], ref, f"from parent 70B down r={r} M={M}")
+            assert torch.isfinite(y).all()
+    for r in (3, 4):                 # the whole re-sliced matrix, bit for bit, through the inverse of the pack
+        S = mq.mq_unpack(mq.mq_reslice(p8, N, K, C, r), N, K, C, r).cpu().numpy()
+        assert np.array_equal(S, oracle.slice_codes(L["parent"], C, r))

@@ -101,6 +101,46 @@ def test_pack_validation():
     assert L.mq_pack_meta(FAKE, FAKE + 1, 64, 256, 128, FAKE, FAKE, big, None) == _st("MQ_ERR_ALIGN")
 
 
+def test_reslice_validation():
+    L = mq.lib()
+    big = 1 << 30
+    for fn in (L.mq_slice_pack, L.mq_reslice):
+        assert fn(None, 64, 128, 8, 4, FAKE + (1 << 20), big, None) == _st("MQ_ERR_NULL")
+        assert fn(FAKE, 64, 128, 8, 4, None, big, None) == _st("MQ_ERR_NULL")
+        assert fn(FAKE, 64, 128, 8, 5, FAKE + (1 << 20), big, None) == _st("MQ_ERR_BAD_R")
+        assert fn(FAKE, 64, 128, 7, 4, FAKE + (1 << 20), big, None) == _st("MQ_ERR_BAD_R")
+        assert fn(FAKE, 0, 128, 8, 4, FAKE + (1 << 20), big, None) == _st("MQ_ERR_BAD_SHAPE")
+        assert fn(FAKE, 64, 100, 8, 4, FAKE + (1 << 20), big, None) == _st("MQ_ERR_BAD_GROUP")
+        assert fn(FAKE, 64, 128, 8, 4, FAKE + (1 << 20) + 4, big, None) == _st("MQ_ERR_ALIGN")
+        assert fn(FAKE, 64, 128, 8, 4, FAKE + (1 << 20), 64 * 128 // 2 - 1, None) == _st("MQ_ERR_BUF_TOO_SMALL")
+    assert L.mq_reslice(FAKE + 8, 64, 128, 8, 4, FAKE + (1 << 20), big, None) == _st("MQ_ERR_ALIGN")
+    # output overlapping the resident parent (8192 bytes here) is refused, adjacent buffers are not an overlap
+    assert L.mq_reslice(FAKE, 64, 128, 8, 4, FAKE, big, None) == _st("MQ_ERR_UNSUPPORTED")
+    assert L.mq_reslice(FAKE, 64, 128, 8, 4, FAKE + 8176, big, None) == _st("MQ_ERR_UNSUPPORTED")
+    assert L.mq_reslice(FAKE + 4096, 64, 128, 8, 4, FAKE + 16, big, None) == _st("MQ_ERR_UNSUPPORTED")
+
+
+def test_linear_from_parent_validation():
+    # every call below fails validation: nothing is ever launched with these fake pointers
+    L = mq.lib()
+    args = lambda **kw: _linear_args(**kw)  # noqa: E731
+    assert L.mq_linear_from_parent(*args(M=5)) == _st("MQ_ERR_UNSUPPORTED")
+    assert L.mq_linear_from_parent(*args(M=256)) == _st("MQ_ERR_UNSUPPORTED")
+    assert L.mq_linear_from_parent(*args(M=257)) == _st("MQ_ERR_BAD_SHAPE")
+    assert L.mq_linear_from_parent(*args(r=5)) == _st("MQ_ERR_BAD_R")
+    assert L.mq_linear_from_parent(*args(W=None)) == _st("MQ_ERR_NULL")
+    assert L.mq_linear_from_parent(*args(W=FAKE + 8)) == _st("MQ_ERR_ALIGN")
+    # the workspace is that of the 8-bit layout whatever r is
+    need = L.mq_workspace_bytes(1, 64, 128, 8)
+    assert L.mq_linear_from_parent(*args(r=2, wsb=need - 1)) == _st("MQ_ERR_BUF_TOO_SMALL")
+
+
+def _linear_args(**kw):
+    a = dict(x=FAKE, M=1, W=FAKE, st=FAKE, zt=FAKE, N=64, K=128, r=4, group=128, y=FAKE, ws=FAKE, wsb=1 << 30)
+    a.update(kw)
+    return (a["x"], a["M"], a["W"], a["st"], a["zt"], a["N"], a["K"], a["r"], a["group"], a["y"], a["ws"], a["wsb"], None)
+
+
 def _linear(L, **kw):
     a = dict(x=FAKE, M=1, W=FAKE, st=FAKE, zt=FAKE, N=64, K=128, r=4, group=128, y=FAKE, ws=FAKE, wsb=1 << 30)
     a.update(kw)
@@ -150,6 +190,13 @@ def test_workspace_and_stack_validation():
     lay[1].x = None
     assert L.mq_stack_plan(p, 2, 1, FAKE, need, None) == _st("MQ_ERR_NULL")
     assert L.mq_linear_stack(None, None) == _st("MQ_ERR_NULL")
+    lay[1].x = FAKE
+    lay[1].from_parent = 1                        # layers of one stack must agree
+    assert L.mq_stack_plan(p, 2, 1, FAKE, need, None) == _st("MQ_ERR_UNSUPPORTED")
+    lay[0].from_parent = 1
+    assert L.mq_stack_plan(p, 2, 8, FAKE, 1 << 40, None) == _st("MQ_ERR_UNSUPPORTED")   # batch above the ALU path
+    lay[0].from_parent = lay[1].from_parent = 2
+    assert L.mq_stack_plan(p, 2, 1, FAKE, need, None) == _st("MQ_ERR_UNSUPPORTED")
 
 
 # ------------------------------------------------------------ input recipe
