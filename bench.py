@@ -47,11 +47,12 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--layers", type=int, default=32, help="decoder blocks in the stack")
-    ap.add_argument("--workload", default="every-r", choices=["every-r", "mixed-7b", "mixed-70b", "mlp-70b", "parent-7b", "parent-70b"],
+    ap.add_argument("--workload", default="every-r", choices=["every-r", "mixed-7b", "mixed-70b", "mlp-70b", "parent-7b", "parent-70b", "quant-7b"],
                     help="every-r: Llama-2-7B linears at each r (default, the headline); mixed-7b / mixed-70b: one "
                          "mixed-width stack (mean 3.5 / 4 bits); mlp-70b: batched regime on the Llama-3-70B MLP shapes; "
                          "parent-7b / parent-70b: run-time re-slicing of a resident 8-bit parent (mq_reslice, "
-                         "mq_slice_pack) and the stack computed straight from the parent")
+                         "mq_slice_pack) and the stack computed straight from the parent; quant-7b: Algorithm 1 (cross-bit-width "
+                         "choice of the parent code) on the Llama-2-7B layer shapes")
     ap.add_argument("--batch", type=int, default=1, help="M for the mixed-* workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-single", action="store_true", help="skip the per-call mq_linear table")
@@ -75,6 +76,8 @@ def main() -> int:
         return bench_mlp_batched(args, mq, synth, torch, np, dev)
     if args.workload in ("parent-7b", "parent-70b"):
         return bench_resident_parent(args, mq, synth, torch, np, dev)
+    if args.workload == "quant-7b":
+        return bench_quant(args, mq, synth, torch, np, dev)
     block = synth.LLAMA2_7B_BLOCK
     M = 1
 
@@ -390,6 +393,71 @@ def bench_resident_parent(args, mq, synth, torch, np, dev):
         sp[str(r)] = {"us": round(t * 1e6, 1), "GBps": round((1.0 + r / 8.0) * N * K / t / 1e9, 1)}
     out["slice_pack_%dx%d" % (N, K)] = sp
     out["cpu_baseline"] = None
+    print(json.dumps(out))
+    return 0
+
+
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+
+
+def bench_quant(args, mq, synth, torch, np, dev):
+    """Algorithm 1 over whole layers: one mq_quant_matgptq launch per (shape, R); fp32 weights resident in HBM."""
+    sets = {"3,4,8": ((3, 4, 8), (1.0, 1.0, 1.0)), "2,3,4,6,8": ((2, 3, 4, 6, 8), (1.0,) * 5), "8": ((8,), (1.0,))}
+    table, tot_w, tot_t, tot_fl = {}, 0.0, 0.0, 0.0
+    g = torch.Generator(device=dev)
+    g.manual_seed(4242)
+    for (N, K) in ((4096, 4096), (11008, 4096), (4096, 11008)):
+        L = synth.make_layer_device(N, K, 1, seed=8000 + N, device=dev, want_x=False)
+        W = torch.randn((N, K), generator=g, device=dev, dtype=torch.float32) * 0.02
+        Q = torch.empty((N, K), dtype=torch.uint8, device=dev)
+        for name, (widths, lam) in sets.items():
+            for _ in range(max(1, args.warmup // 2)):
+                mq.mq_quant_matgptq(W, L["scales"], L["zeros"], widths, lam, out=Q)
+            torch.cuda.synchronize()
+            reps = max(2, args.steps // 4)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                mq.mq_quant_matgptq(W, L["scales"], L["zeros"], widths, lam, out=Q)
+            e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) * 1e-3 / reps
+            # the brute force as defined: per candidate and width sub, mul, sub, mul, mul, add; one compare per candidate
+            fl = (6.0 * len(widths) + 1.0) * 256.0 * N * K
+            table[f"{N}x{K}:R{{{name}}}"] = {"us": round(t * 1e6, 1), "Gweights_per_s": round(N * K / t / 1e9, 2),
+                                             "TFLOPs": round(fl / t / 1e12, 1)}
+            if name == "3,4,8":
+                tot_w += N * K
+                tot_t += t
+                tot_fl += fl
+        del W, Q, L
+    out = _base_line("Algorithm 1 (brute-force cross-bit-width code choice) throughput, R = {3,4,8}", tot_w / tot_t / 1e9,
+                     "Gweights/s", args, tot_t * 1e3,
+                     "Llama-2-7B layer shapes (4096x4096, 11008x4096, 4096x11008), fp32 weights, group 128, "
+                     "c = 8, R = {3,4,8} with lambda = 1 (the paper's setting); other R in `table`", {})
+    out["dtype"] = "f32"
+    out["table"] = table
+    ach = tot_fl / tot_t / 1e12
+    out["roofline"] = {"bound": "alu", "kernel": "mq::quant_kernel<140, 4>", "achieved": round(ach, 1),
+                       "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / FP32_VECTOR_PEAK_TFLOPS, 4),
+                       "avg_launch_us": round(tot_t / 3 * 1e6, 1),
+                       "algorithmic_flops_per_launch": int(tot_fl / 3), "traffic": None}
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        N, K, rows = 4096, 4096, 32
+        Wh = synth.make_weights(rows, K, [4242, 1])
+        _, sh, zh = synth.quantize_parent(Wh)
+        done, ct = 0, 0.0
+        while ct < 10.0:
+            ta = time.perf_counter()
+            oracle.quant_matgptq(Wh, sh, zh, 8, (3, 4, 8), (1.0, 1.0, 1.0), 128, np.float32)
+            ct += time.perf_counter() - ta
+            done += rows * K
+        cpu = {"value": round(done / ct / 1e9, 5), "unit": "Gweights/s", "cores": 1, "kind": "oracle",
+               "sample": f"numpy oracle (oracle/mq_quant_oracle.py, binary32) on {rows} rows of a 4096-column layer, "
+                         f"R = {{3,4,8}}, repeated for {ct:.1f} s", "seconds": round(ct, 2)}
+    out["cpu_baseline"] = cpu
     print(json.dumps(out))
     return 0
 

@@ -141,6 +141,28 @@ mq_status mq_pack_meta(const mq_half *scales, const mq_half *zeros, int64_t N, i
                        int group, mq_half *scales_t, mq_half *zeros_t, size_t meta_bytes,
                        mq_stream stream);
 
+/* ---------------------------------------------------------------- quantiser step
+ * Algorithm 1 ("Generate Q^c given weight matrix W, target bit-widths R, and weights
+ * lambda_R"; Section 3.2, item 2): for every weight the parent code q in 0 .. 2^c - 1 with the
+ * smallest  E(q) = sum_{r in R} lambda_r * (w - scale * (S(q, r) - zero))^2,  S = Eq. 1, scale
+ * and zero-offset those of the master width for every r.  All 256 candidates are evaluated (the
+ * paper's brute force).  The argmin is taken in IEEE binary32 with every operation rounded on its
+ * own, in the order  t = S - zero; D = scale * t; e = w - D; p = e * e; E = E + lambda_r * p,
+ * r ascending; the smallest q wins a tie.  Inputs must be finite.
+ *   W       : device, fp32, N rows of `ncols` weights, row stride ldw elements: columns
+ *             col0 .. col0+ncols-1 of a layer with K input features (ncols = 1 is the
+ *             column-at-a-time call of the GPTQ loop, ncols = K the whole matrix); 4-byte aligned
+ *   scales, zeros : device, fp16 [N, K/group] row-major (NOT tiled)
+ *   lambda  : HOST, 8 floats, lambda_r at [r-1] for r = 1..8; 0 = r is not a target width;
+ *             all finite and >= 0, at least one > 0
+ *   Q       : device, uint8, N rows of ncols codes, row stride ldq bytes
+ * Four columns per lane when W is 16-byte and Q 4-byte aligned and ldw, ldq, ncols, col0 are
+ * multiples of 4; one column per lane otherwise (same results).
+ * Errors: NULL, BAD_R (c != 8, or lambda), BAD_SHAPE, BAD_GROUP, ALIGN, HIP. */
+mq_status mq_quant_matgptq(const float *W, int64_t ldw, int64_t N, int64_t ncols, int64_t col0,
+                           const mq_half *scales, const mq_half *zeros, int64_t K, int group, int c,
+                           const float *lambda, uint8_t *Q, int64_t ldq, mq_stream stream);
+
 /* ---------------------------------------------------------------- linear
  * Section 4:  y[m,n] = sum_k x[m,k] * scale[n,k/group] * (S[n,k] - zero[n,k/group])
  * with S the r-bit slice of Eq. 1 in c-bit units, fp16 inputs, fp32

@@ -12,7 +12,7 @@ __all__ = [
     "MqError", "lib", "lib_path", "MQ_ROW_BLOCK", "MQ_GROUP", "MQ_MAX_M", "STATUS",
     "mq_status_str", "mq_version", "mq_packed_bytes", "mq_meta_bytes", "mq_workspace_bytes",
     "mq_workspace_init", "mq_slice_codes", "mq_pack", "mq_unpack", "mq_pack_meta", "mq_linear",
-    "mq_slice_pack", "mq_reslice", "mq_linear_from_parent",
+    "mq_slice_pack", "mq_reslice", "mq_linear_from_parent", "mq_quant_matgptq",
     "mq_stack_workspace_bytes", "mq_stack_plan", "mq_linear_stack", "MqLayer",
     "new_workspace", "prepare_layer",
 ]
@@ -80,6 +80,7 @@ def lib():
         "mq_slice_pack": (i32, [vp, i64, i64, i32, i32, vp, sz, vp]),
         "mq_reslice": (i32, [vp, i64, i64, i32, i32, vp, sz, vp]),
         "mq_linear_from_parent": (i32, [vp, i64, vp, vp, vp, i64, i64, i32, i32, vp, vp, sz, vp]),
+        "mq_quant_matgptq": (i32, [vp, i64, i64, i64, i64, vp, vp, i64, i32, i32, vp, vp, i64, vp]),
         "mq_stack_workspace_bytes": (sz, [vp, i32, i64]),
         "mq_stack_plan": (i32, [vp, i32, i64, vp, sz, vp]),
         "mq_linear_stack": (i32, [vp, vp]),
@@ -220,6 +221,28 @@ def mq_linear_from_parent(x, packed_parent, scales_t, zeros_t, N: int, K: int, r
                                        _ptr(y), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)),
            "mq_linear_from_parent")
     return y
+
+
+def mq_quant_matgptq(W, scales, zeros, widths, lam, K: Optional[int] = None, col0: int = 0, c: int = 8,
+                     group: int = MQ_GROUP, out=None, stream=None):
+    """Algorithm 1 on W (fp32 [N, ncols], possibly a column slab / strided view of a [N, K] layer).
+    widths / lam: the target widths R and their lambda_r.  Returns uint8 codes [N, ncols]."""
+    import torch
+    N, ncols = W.shape
+    K = ncols if K is None else K
+    if W.stride(1) != 1:
+        raise ValueError("columns of W must be contiguous")
+    if out is None:
+        out = torch.empty((N, ncols), dtype=torch.uint8, device=W.device)
+    lam8 = (ctypes.c_float * 8)()
+    for r, l in zip(widths, lam):
+        if not 1 <= int(r) <= 8:
+            raise MqError(2, "mq_quant_matgptq")
+        lam8[int(r) - 1] = float(l)
+    _check(lib().mq_quant_matgptq(_ptr(W), W.stride(0), N, ncols, col0, _ptr(scales), _ptr(zeros), K, group, c,
+                                  ctypes.cast(lam8, ctypes.c_void_p), _ptr(out), out.stride(0), _stream(stream)),
+           "mq_quant_matgptq")
+    return out
 
 
 def _layer_array(layers: Sequence[dict]):

@@ -1,6 +1,7 @@
 // C ABI of libmq: argument validation (host only, before anything is enqueued),
 // workspace arithmetic and dispatch to the kernel launchers.
 #include <climits>
+#include <cmath>
 #include <mutex>
 #include <unordered_map>
 #include <vector>
@@ -297,6 +298,30 @@ mq_status mq_reslice(const void *packed_parent, int64_t N, int64_t K, int c, int
     }
     return launch_reslice(static_cast<const uint4 *>(packed_parent), N, K, r, static_cast<uint4 *>(packed),
                           (hipStream_t)stream) == hipSuccess
+               ? MQ_OK
+               : MQ_ERR_HIP;
+}
+
+mq_status mq_quant_matgptq(const float *W, int64_t ldw, int64_t N, int64_t ncols, int64_t col0, const mq_half *scales,
+                           const mq_half *zeros, int64_t K, int group, int c, const float *lambda, uint8_t *Q,
+                           int64_t ldq, mq_stream stream) {
+    if (!W || !scales || !zeros || !lambda || !Q) return MQ_ERR_NULL;
+    if (c != kC) return MQ_ERR_BAD_R;
+    bool any = false;
+    for (int i = 0; i < kC; ++i) {
+        if (!std::isfinite(lambda[i]) || lambda[i] < 0.f) return MQ_ERR_BAD_R;
+        any = any || lambda[i] > 0.f;
+    }
+    if (!any) return MQ_ERR_BAD_R;  // no target width
+    if (mq_status st = check_shape(N, K, group)) return st;
+    if (ncols < 1 || col0 < 0 || col0 > K - ncols || ldw < ncols || ldq < ncols || ldw > ((int64_t)1 << 32) ||
+        ldq > ((int64_t)1 << 32))
+        return MQ_ERR_BAD_SHAPE;
+    if (!aligned(W, 4) || !aligned(scales, 2) || !aligned(zeros, 2)) return MQ_ERR_ALIGN;
+    const bool vec4 = aligned(W, 16) && aligned(Q, 4) && ldw % 4 == 0 && ldq % 4 == 0 && ncols % 4 == 0 && col0 % 4 == 0;
+    return launch_quant(W, ldw, N, ncols, col0, reinterpret_cast<const _Float16 *>(scales),
+                        reinterpret_cast<const _Float16 *>(zeros), K / group, lambda, Q, ldq, vec4,
+                        (hipStream_t)stream) == hipSuccess
                ? MQ_OK
                : MQ_ERR_HIP;
 }

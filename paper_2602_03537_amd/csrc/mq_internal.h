@@ -103,6 +103,10 @@ hipError_t launch_reslice(const uint4 *parent8, int64_t N, int64_t K, int r, uin
 hipError_t launch_pack_meta(const _Float16 *sc, const _Float16 *zr, int64_t N, int64_t G, _Float16 *st,
                             _Float16 *zt, hipStream_t s);
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
+// Algorithm 1 (mq_quant.hip).  lambda: host, kC floats (width r at [r-1]); vec4: four columns per lane (alignment checked by the caller)
+hipError_t launch_quant(const float *W, int64_t ldw, int64_t N, int64_t ncols, int64_t col0, const _Float16 *scales,
+                        const _Float16 *zeros, int64_t G, const float *lambda, uint8_t *Q, int64_t ldq, bool vec4,
+                        hipStream_t s);
 // Fills p.nwaves and launches (vector-ALU path, M <= kValuMaxM).  max_cost = largest tile cost in the stack.
 // from_parent: every layer has rs != 0 (the kernel variant that slices in registers).
 hipError_t launch_stack(StackParams p, int max_cost, bool from_parent, hipStream_t s);

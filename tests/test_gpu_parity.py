@@ -689,3 +689,110 @@ def test_from_parent_llama3_70b_down_projection_sampled_rows_and_full_reslice():
     for r in (3, 4):                 # the whole re-sliced matrix, bit for bit, through the inverse of the pack
         S = mq.mq_unpack(mq.mq_reslice(p8, N, K, C, r), N, K, C, r).cpu().numpy()
         assert np.array_equal(S, oracle.slice_codes(L["parent"], C, r))
+
+
+# ------------------------------------------------------------------ Algorithm 1: cross-bit-width choice of the parent code
+def _quant_inputs(N, K, seed, std=0.02):
+    """weights, and the min-max scale / zero-offset of the seeded recipe (fp16), on the host"""
+    W = synth.make_weights(N, K, seed, std)
+    _, s, z = synth.quantize_parent(W)
+    return W.astype(np.float32), s, z
+
+
+QUANT_SETS = [((8,), (1.0,)), ((3, 4, 8), (1.0, 1.0, 1.0)), ((3, 4, 8), (1.0, 0.5, 0.1)),
+              ((2, 3, 4, 6, 8), (0.1, 0.5, 1.0, 1.0, 0.25)), ((2, 5, 7), (1.0, 2.0, 0.5)), ((4,), (1.0,)),
+              ((1, 2, 3, 4, 5, 6, 7, 8), (1.0,) * 8)]
+
+
+@pytest.mark.parametrize("widths,lam", QUANT_SETS)
+@pytest.mark.parametrize("shape", [(64, 128), (3, 256), (130, 384), (257, 1280)])
+def test_quant_matgptq_whole_matrix_bit_exact(widths, lam, shape):
+    N, K = shape
+    W, s, z = _quant_inputs(N, K, [70, N, K])
+    W[0, :8] = [10.0, -10.0, 0.0, W[0, 3], 1e-30, -1e-30, 3.0, -3.0]       # far outside the grid, zero, tiny
+    ref = oracle.quant_matgptq(W, s, z, C, widths, lam, 128, np.float32)
+    got = mq.mq_quant_matgptq(dev(W), dev(s), dev(z), widths, lam)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), ref), (widths, lam, shape)
+
+
+def test_quant_matgptq_differs_from_plain_rounding_and_serves_the_low_widths_better():
+    # what the step is for: against round-to-nearest at 8 bits, the summed error over the target widths drops
+    N, K = 128, 512
+    W, s, z = _quant_inputs(N, K, [71])
+    widths, lam = (3, 4, 8), (1.0, 1.0, 1.0)
+    q = mq.mq_quant_matgptq(dev(W), dev(s), dev(z), widths, lam).cpu().numpy()
+    rtn = mq.mq_quant_matgptq(dev(W), dev(s), dev(z), (8,), (1.0,)).cpu().numpy()
+    recipe = synth.quantize_parent(W)[0].astype(int)                        # R = {8} is plain rounding to nearest:
+    assert np.abs(rtn.astype(int) - recipe).max() <= 1                      # the recipe's codes up to rounding ties
+    assert np.count_nonzero(rtn != recipe) < 1e-3 * rtn.size
+    assert 0 < np.count_nonzero(q != rtn) < q.size
+
+    def total(codes):
+        return sum(((W - oracle.dequant(oracle.slice_codes(codes, C, r), s, z, 128)) ** 2).sum() for r in widths)
+    assert total(q) < total(rtn)
+
+
+@pytest.mark.parametrize("ncols,col0", [(1, 0), (1, 131), (5, 126), (128, 256), (4, 124), (132, 4)])
+def test_quant_matgptq_column_slabs_strides_and_guard_bytes(ncols, col0):
+    # the column-at-a-time and block-at-a-time calls of the GPTQ loop: a strided view of W, codes into a strided view
+    N, K = 100, 512
+    W, s, z = _quant_inputs(N, K, [72, ncols, col0])
+    widths, lam = (3, 4, 8), (1.0, 0.5, 0.1)
+    ref = oracle.quant_matgptq(W, s, z, C, widths, lam, 128, np.float32)[:, col0:col0 + ncols]
+    Wd = dev(W)
+    out = torch.full((N, K + 8), 0xAB, dtype=torch.uint8, device=DEV)
+    for view_off in (0, 4, 3):              # 3: the codes land on an address that rules out four columns per lane
+        out.fill_(0xAB)
+        dst = out[:, view_off + col0: view_off + col0 + ncols]
+        mq.mq_quant_matgptq(Wd[:, col0:col0 + ncols], dev(s), dev(z), widths, lam, K=K, col0=col0, out=dst)
+        torch.cuda.synchronize()
+        o = out.cpu().numpy()
+        assert np.array_equal(o[:, view_off + col0: view_off + col0 + ncols], ref), (ncols, col0, view_off)
+        o[:, view_off + col0: view_off + col0 + ncols] = 0xAB
+        assert (o == 0xAB).all()                                           # nothing else was written
+
+
+def test_quant_matgptq_fractional_zero_offsets_constant_groups_and_ties():
+    N, K = 64, 256
+    rng = np.random.default_rng(73)
+    W = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+    s = rng.uniform(2e-4, 2e-3, (N, 2)).astype(np.float16)
+    z = rng.uniform(0, 255, (N, 2)).astype(np.float16)                     # not integers
+    W[1] = 0.0
+    s[1], z[1] = 1.0, 0.0                                                  # constant group: unit scale
+    W[2, :128] = (np.arange(128) + 0.5).astype(np.float32)                 # exact ties between neighbours at r = 8
+    s[2], z[2] = 1.0, 0.0
+    for widths, lam in QUANT_SETS[:4]:
+        ref = oracle.quant_matgptq(W, s, z, C, widths, lam, 128, np.float32)
+        got = mq.mq_quant_matgptq(dev(W), dev(s), dev(z), widths, lam).cpu().numpy()
+        assert np.array_equal(got, ref), (widths, lam)
+    assert np.array_equal(mq.mq_quant_matgptq(dev(W), dev(s), dev(z), (8,), (1.0,)).cpu().numpy()[2, :128],
+                          np.arange(128))                                  # the smaller code wins the tie
+
+
+def test_quant_matgptq_llama2_7b_layer_sampled_rows():
+    N, K = 4096, 4096
+    L = synth.make_layer_device(N, K, 1, seed=74, device=DEV)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(75)
+    W = torch.randn((N, K), generator=g, device=DEV, dtype=torch.float32) * 0.02
+    widths, lam = (3, 4, 8), (1.0, 1.0, 1.0)
+    q = mq.mq_quant_matgptq(W, L["scales"], L["zeros"], widths, lam)
+    rows = np.unique(np.concatenate([[0, 63, 64, N - 1], np.random.default_rng(76).integers(0, N, 28)]))
+    ridx = torch.from_numpy(rows).to(DEV)
+    ref = oracle.quant_matgptq(W[ridx].cpu().numpy(), L["scales"][ridx].cpu().numpy(), L["zeros"][ridx].cpu().numpy(),
+                               C, widths, lam, 128, np.float32)
+    assert np.array_equal(q[ridx].cpu().numpy(), ref)
+
+
+def test_quant_matgptq_rejects_bad_arguments_loudly():
+    W, s, z = _quant_inputs(64, 128, [77])
+    Wd, sd, zd = dev(W), dev(s), dev(z)
+    for widths, lam in [((8,), (0.0,)), ((3, 8), (1.0, -1.0)), ((4,), (float("nan"),)), ((9,), (1.0,))]:
+        with pytest.raises(mq.MqError):
+            mq.mq_quant_matgptq(Wd, sd, zd, widths, lam)
+    with pytest.raises(mq.MqError):
+        mq.mq_quant_matgptq(Wd, sd, zd, (8,), (1.0,), c=7)
+    with pytest.raises(mq.MqError):
+        mq.mq_quant_matgptq(Wd[:, :8], sd, zd, (8,), (1.0,), K=128, col0=124)        # slab runs past the last column

@@ -135,6 +135,32 @@ def test_linear_from_parent_validation():
     assert L.mq_linear_from_parent(*args(r=2, wsb=need - 1)) == _st("MQ_ERR_BUF_TOO_SMALL")
 
 
+def test_quant_validation():
+    # every call below fails validation: nothing is ever launched with these fake pointers
+    L = mq.lib()
+    lam = (ctypes.c_float * 8)(0, 0, 1, 1, 0, 0, 0, 1)
+    lp = ctypes.cast(lam, ctypes.c_void_p)
+
+    def call(W=FAKE, ldw=128, N=64, ncols=128, col0=0, s=FAKE, z=FAKE, K=128, group=128, c=8, lam=lp, Q=FAKE, ldq=128):
+        return L.mq_quant_matgptq(W, ldw, N, ncols, col0, s, z, K, group, c, lam, Q, ldq, None)
+    for k in ("W", "s", "z", "lam", "Q"):
+        assert call(**{k: None}) == _st("MQ_ERR_NULL"), k
+    assert call(c=7) == _st("MQ_ERR_BAD_R")
+    for bad in ((0,) * 8, (0, 0, -1, 0, 0, 0, 0, 1), (0, 0, float("nan"), 0, 0, 0, 0, 1), (float("inf"),) * 8):
+        arr = (ctypes.c_float * 8)(*bad)
+        assert call(lam=ctypes.cast(arr, ctypes.c_void_p)) == _st("MQ_ERR_BAD_R"), bad
+    assert call(N=0) == _st("MQ_ERR_BAD_SHAPE")
+    assert call(K=100) == _st("MQ_ERR_BAD_GROUP")
+    assert call(group=64) == _st("MQ_ERR_BAD_GROUP")
+    assert call(ncols=0) == _st("MQ_ERR_BAD_SHAPE")
+    assert call(ncols=8, col0=124) == _st("MQ_ERR_BAD_SHAPE")
+    assert call(col0=-4, ncols=4) == _st("MQ_ERR_BAD_SHAPE")
+    assert call(ldw=100) == _st("MQ_ERR_BAD_SHAPE")
+    assert call(ldq=100) == _st("MQ_ERR_BAD_SHAPE")
+    assert call(W=FAKE + 2) == _st("MQ_ERR_ALIGN")
+    assert call(s=FAKE + 1) == _st("MQ_ERR_ALIGN")
+
+
 def _linear_args(**kw):
     a = dict(x=FAKE, M=1, W=FAKE, st=FAKE, zt=FAKE, N=64, K=128, r=4, group=128, y=FAKE, ws=FAKE, wsb=1 << 30)
     a.update(kw)
