@@ -12,4 +12,4 @@ from .mq_oracle import (  # noqa: F401
     linear_rows,
     linear_stack,
 )
-from .mq_quant_oracle import quant_matgptq, quant_errors  # noqa: F401,E402
+from .mq_quant_oracle import quant_matgptq, quant_errors, matgptq_quantize  # noqa: F401,E402

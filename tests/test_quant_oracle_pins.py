@@ -151,3 +151,107 @@ def test_binary32_and_binary64_agree_except_at_near_ties():
         n, k = np.nonzero(diff)
         a, b = E[q32[n, k], n, k], E[q64[n, k], n, k]
         assert np.all(np.abs(a - b) <= 1e-5 * b)
+
+
+# ------------------------------------------------------------------ the column loop (Algorithm 2 of the appendix)
+def _hessian_factor(K, seed, samples=None):
+    """H = 2 X X^T + damping (the appendix' definition), U = upper Cholesky factor of H^-1 (numpy, float64)."""
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((K, samples or 4 * K)) * (1.0 + 3.0 * rng.random((K, 1)))   # uneven feature scales
+    X[:, :] += 0.5 * X[rng.permutation(K), :]                                            # correlated features
+    H = 2.0 * X @ X.T
+    H += 0.01 * np.mean(np.diag(H)) * np.eye(K)
+    Hinv = np.linalg.inv(H)
+    return H, Hinv, np.linalg.cholesky(Hinv).T
+
+
+def _layer(N, K, seed):
+    from paper_2602_03537_amd import synth
+    W = synth.make_weights(N, K, seed).astype(np.float32)
+    _, s, z = synth.quantize_parent(W)
+    return W, s, z
+
+
+def _mean_dequant(Q, s, z, widths):
+    return np.mean([oracle.dequant(oracle.slice_codes(Q, C, r), s, z, 128) for r in widths], axis=0)
+
+
+def test_column_loop_with_a_diagonal_factor_is_algorithm_1_per_column():
+    W, s, z = _layer(16, 256, [80])
+    U = np.diag(np.random.default_rng(80).uniform(0.5, 2.0, 256))
+    widths, lam = [3, 4, 8], [1.0, 0.5, 0.1]
+    for dtype in (np.float32, np.float64):
+        Q, E = oracle.matgptq_quantize(W, U, s, z, C, widths, lam, 128, 128, dtype)
+        assert np.array_equal(Q, oracle.quant_matgptq(W, s, z, C, widths, lam, 128, dtype))
+    want = (W.astype(np.float64) - _mean_dequant(Q, s, z, widths)) / np.diag(U)[None, :]
+    assert np.allclose(E, want, rtol=1e-12, atol=1e-15)
+
+
+def test_column_loop_telescopes_original_minus_quantised_equals_E_times_U():
+    # every update the loop applied, summed up: W - mean_r dequant(S(Q, r)) = E @ U (U upper triangular).
+    # A wrong sign, index range, transposed factor or missing division by the diagonal breaks this.
+    W, s, z = _layer(12, 384, [81])
+    _, _, U = _hessian_factor(384, 81)
+    for widths, lam in (([8], [1.0]), ([3, 4, 8], [1.0, 1.0, 1.0]), ([2, 6], [0.5, 2.0])):
+        Q, E = oracle.matgptq_quantize(W, U, s, z, C, widths, lam, 128, 128, np.float64)
+        lhs = W.astype(np.float64) - _mean_dequant(Q, s, z, widths)
+        assert np.abs(lhs - E @ U).max() <= 1e-12 * max(1.0, np.abs(lhs).max())
+        assert np.abs(E @ U - E @ np.triu(U)).max() == 0.0
+
+
+def test_column_loop_does_not_depend_on_the_block_size_bit_for_bit():
+    W, s, z = _layer(8, 256, [82])
+    _, _, U = _hessian_factor(256, 82)
+    ref = oracle.matgptq_quantize(W, U, s, z, C, [3, 4, 8], [1, 1, 1], 128, 128, np.float32)
+    for block in (32, 64, 256):
+        got = oracle.matgptq_quantize(W, U, s, z, C, [3, 4, 8], [1, 1, 1], 128, block, np.float32)
+        assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])
+
+
+def _obs_row_solver(w, Hinv, s, z, widths, lam):
+    """The same quantiser in its other textbook form: optimal-brain-surgeon updates with the explicit inverse
+    Hessian, eliminating one coordinate at a time (no Cholesky factor).  One row, float64."""
+    w = w.astype(np.float64).copy()
+    Hi = Hinv.copy()
+    K = w.size
+    q = np.zeros(K, dtype=np.uint8)
+    for j in range(K):
+        g = j // 128
+        qj = oracle.quant_matgptq(np.array([[w[j]]]), [[s[g]]], [[z[g]]], C, widths, lam, 1, np.float64)[0, 0]
+        q[j] = qj
+        deq = np.mean([float(s[g]) * (float(oracle.slice_codes(np.array([qj], np.uint8), C, r)[0]) - float(z[g]))
+                       for r in widths])
+        d = (w[j] - deq) / Hi[j, j]
+        w[j + 1:] -= d * Hi[j, j + 1:]
+        Hi[j + 1:, j + 1:] -= np.outer(Hi[j + 1:, j], Hi[j, j + 1:]) / Hi[j, j]
+    return q
+
+
+@pytest.mark.parametrize("widths,lam", [([8], [1.0]), ([3, 4, 8], [1.0, 1.0, 1.0])])
+def test_column_loop_against_the_explicit_inverse_formulation(widths, lam):
+    W, s, z = _layer(3, 256, [83])
+    _, Hinv, U = _hessian_factor(256, 83)
+    Q, _ = oracle.matgptq_quantize(W, U, s, z, C, widths, lam, 128, 128, np.float64)
+    for n in range(3):
+        assert np.array_equal(Q[n], _obs_row_solver(W[n], Hinv, s[n], z[n], widths, lam)), n
+
+
+def test_column_loop_lowers_the_hessian_weighted_error_of_plain_rounding():
+    W, s, z = _layer(16, 256, [84])
+    H, _, U = _hessian_factor(256, 84)
+    Q, _ = oracle.matgptq_quantize(W, U, s, z, C, [8], [1.0], 128, 128, np.float64)
+    rtn = oracle.quant_matgptq(W, s, z, C, [8], [1.0], 128, np.float64)
+
+    def loss(codes):
+        d = W.astype(np.float64) - oracle.dequant(codes, s, z, 128)
+        return np.trace(d @ H @ d.T)
+    assert loss(Q) < 0.8 * loss(rtn)
+    # and with several target widths the summed loss over those widths drops against Algorithm 1 without propagation
+    widths = [3, 4, 8]
+    Qm, _ = oracle.matgptq_quantize(W, U, s, z, C, widths, [1, 1, 1], 128, 128, np.float64)
+    Q1 = oracle.quant_matgptq(W, s, z, C, widths, [1, 1, 1], 128, np.float64)
+
+    def loss_mean(codes):
+        d = W.astype(np.float64) - _mean_dequant(codes, s, z, widths)
+        return np.trace(d @ H @ d.T)
+    assert loss_mean(Qm) < loss_mean(Q1)
