@@ -47,12 +47,13 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--layers", type=int, default=32, help="decoder blocks in the stack")
-    ap.add_argument("--workload", default="every-r", choices=["every-r", "mixed-7b", "mixed-70b", "mlp-70b", "parent-7b", "parent-70b", "quant-7b"],
+    ap.add_argument("--workload", default="every-r", choices=["every-r", "mixed-7b", "mixed-70b", "mlp-70b", "parent-7b", "parent-70b", "quant-7b", "gptq-7b"],
                     help="every-r: Llama-2-7B linears at each r (default, the headline); mixed-7b / mixed-70b: one "
                          "mixed-width stack (mean 3.5 / 4 bits); mlp-70b: batched regime on the Llama-3-70B MLP shapes; "
                          "parent-7b / parent-70b: run-time re-slicing of a resident 8-bit parent (mq_reslice, "
                          "mq_slice_pack) and the stack computed straight from the parent; quant-7b: Algorithm 1 (cross-bit-width "
-                         "choice of the parent code) on the Llama-2-7B layer shapes")
+                         "choice of the parent code) on the Llama-2-7B layer shapes; gptq-7b: the MatGPTQ column loop "
+                         "(Algorithm 2) on those shapes")
     ap.add_argument("--batch", type=int, default=1, help="M for the mixed-* workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-single", action="store_true", help="skip the per-call mq_linear table")
@@ -78,6 +79,8 @@ def main() -> int:
         return bench_resident_parent(args, mq, synth, torch, np, dev)
     if args.workload == "quant-7b":
         return bench_quant(args, mq, synth, torch, np, dev)
+    if args.workload == "gptq-7b":
+        return bench_gptq(args, mq, synth, torch, np, dev)
     block = synth.LLAMA2_7B_BLOCK
     M = 1
 
@@ -458,6 +461,51 @@ def bench_quant(args, mq, synth, torch, np, dev):
                "sample": f"numpy oracle (oracle/mq_quant_oracle.py, binary32) on {rows} rows of a 4096-column layer, "
                          f"R = {{3,4,8}}, repeated for {ct:.1f} s", "seconds": round(ct, 2)}
     out["cpu_baseline"] = cpu
+    print(json.dumps(out))
+    return 0
+
+
+def bench_gptq(args, mq, synth, torch, np, dev):
+    """The MatGPTQ column loop per layer: mq_matgptq_quantize on a working copy of W, U resident."""
+    widths, lam = (3, 4, 8), (1.0, 1.0, 1.0)
+    g = torch.Generator(device=dev)
+    g.manual_seed(777)
+    table, tot_w, tot_t = {}, 0.0, 0.0
+    for (N, K) in ((4096, 4096), (11008, 4096), (4096, 11008)):
+        L = synth.make_layer_device(N, K, 1, seed=8100 + N, device=dev, want_x=False)
+        W = torch.randn((N, K), generator=g, device=dev, dtype=torch.float32) * 0.02
+        # calibration statistics: H = 2 X X^T + 1 % damping on seeded features; U = chol(H^-1)^T (library calls: input creation)
+        X = torch.randn((K, 2 * K), generator=g, device=dev, dtype=torch.float32)
+        X *= 1.0 + 3.0 * torch.rand((K, 1), generator=g, device=dev)
+        H = (2.0 * X @ X.T).double()
+        del X
+        H += 0.01 * H.diagonal().mean() * torch.eye(K, device=dev, dtype=torch.float64)
+        U = torch.linalg.cholesky(torch.linalg.inv(H)).T.contiguous().float()
+        del H
+        Wc = torch.empty_like(W)
+        Q = torch.empty((N, K), dtype=torch.uint8, device=dev)
+        reps = max(1, args.steps // 10)
+        for it in range(1 + reps):
+            Wc.copy_(W)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            mq.mq_matgptq_quantize(Wc, U, L["scales"], L["zeros"], widths, lam, out=Q)
+            e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) * 1e-3                      # the last repetition is reported
+        table[f"{N}x{K}"] = {"ms": round(t * 1e3, 2), "Mweights_per_s": round(N * K / t / 1e6, 1),
+                             "us_per_column": round(t / K * 1e6, 2)}
+        tot_w += N * K
+        tot_t += t
+        del W, Wc, Q, U, L
+    out = _base_line("MatGPTQ column loop (Algorithm 2) throughput, R = {3,4,8}", tot_w / tot_t / 1e9, "Gweights/s", args,
+                     tot_t * 1e3, "Llama-2-7B layer shapes (4096x4096, 11008x4096, 4096x11008), fp32 weights, group 128, "
+                     "block 128, c = 8, R = {3,4,8}, lambda = 1; Cholesky factor of the inverse Hessian given", {})
+    out["dtype"] = "f32"
+    out["table"] = table
+    out["roofline"] = None
+    out["cpu_baseline"] = None
     print(json.dumps(out))
     return 0
 

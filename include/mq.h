@@ -163,6 +163,32 @@ mq_status mq_quant_matgptq(const float *W, int64_t ldw, int64_t N, int64_t ncols
                            const mq_half *scales, const mq_half *zeros, int64_t K, int group, int c,
                            const float *lambda, uint8_t *Q, int64_t ldq, mq_stream stream);
 
+/* The MatGPTQ column loop (Algorithm 2 of the appendix, "Quantize W given inverse Hessian ..."),
+ * from the point where U, the upper-triangular Cholesky factor of H^-1 (the listing's
+ * "H^-1 <- Cholesky(H^-1)^T"), is given.  In blocks of `block` columns, column by column j:
+ *     Q[:, j] = Algorithm 1 on the current W[:, j]           (as mq_quant_matgptq, bit for bit)
+ *     e       = mean over R of (W[:, j] - scale * (S(Q[:, j], r) - zero)),   E[:, j] = e / U[j, j]
+ *     W[:, j+1 : end of block] -= E[:, j] * U[j, j+1 : end of block]
+ * then W[:, after the block] -= E @ U[block rows, after the block].  lambda weighs Algorithm 1
+ * only; the propagated error is the plain mean over R = {r : lambda_r != 0}.  Scale and
+ * zero-offset are inputs fixed before the loop.  Arithmetic: binary32, every operation rounded on
+ * its own, error terms added over r ascending, then / |R|, then / U[j,j]; each update is
+ * w - (E * U[j,k]), applied in ascending j (the result does not depend on `block`).
+ *   W       : device, fp32 [N, K], row stride ldw; OVERWRITTEN (working copy of the loop)
+ *   U       : device, fp32 [K, K], row stride ldu; only the upper triangle is read
+ *   scales, zeros : device, fp16 [N, K/group] row-major (NOT tiled)
+ *   lambda  : HOST, 8 floats as for mq_quant_matgptq
+ *   block   : 16, 32, 64 or 128 (the paper's B)
+ *   Q       : device, uint8 [N, K], row stride ldq
+ *   ws      : device, 4-byte aligned, ws_bytes >= mq_matgptq_workspace_bytes(N, block)
+ * Enqueues 2 * K / block - 1 launches on `stream`; rows run in parallel, columns in sequence.
+ * Errors: NULL, BAD_R, BAD_SHAPE, BAD_GROUP, ALIGN, BUF_TOO_SMALL, HIP. */
+size_t mq_matgptq_workspace_bytes(int64_t N, int block);
+mq_status mq_matgptq_quantize(float *W, int64_t ldw, int64_t N, int64_t K, const float *U, int64_t ldu,
+                              const mq_half *scales, const mq_half *zeros, int group, int c,
+                              const float *lambda, int block, uint8_t *Q, int64_t ldq, void *ws,
+                              size_t ws_bytes, mq_stream stream);
+
 /* ---------------------------------------------------------------- linear
  * Section 4:  y[m,n] = sum_k x[m,k] * scale[n,k/group] * (S[n,k] - zero[n,k/group])
  * with S the r-bit slice of Eq. 1 in c-bit units, fp16 inputs, fp32

@@ -13,6 +13,7 @@ __all__ = [
     "mq_status_str", "mq_version", "mq_packed_bytes", "mq_meta_bytes", "mq_workspace_bytes",
     "mq_workspace_init", "mq_slice_codes", "mq_pack", "mq_unpack", "mq_pack_meta", "mq_linear",
     "mq_slice_pack", "mq_reslice", "mq_linear_from_parent", "mq_quant_matgptq",
+    "mq_matgptq_workspace_bytes", "mq_matgptq_quantize",
     "mq_stack_workspace_bytes", "mq_stack_plan", "mq_linear_stack", "MqLayer",
     "new_workspace", "prepare_layer",
 ]
@@ -81,6 +82,8 @@ def lib():
         "mq_reslice": (i32, [vp, i64, i64, i32, i32, vp, sz, vp]),
         "mq_linear_from_parent": (i32, [vp, i64, vp, vp, vp, i64, i64, i32, i32, vp, vp, sz, vp]),
         "mq_quant_matgptq": (i32, [vp, i64, i64, i64, i64, vp, vp, i64, i32, i32, vp, vp, i64, vp]),
+        "mq_matgptq_workspace_bytes": (sz, [i64, i32]),
+        "mq_matgptq_quantize": (i32, [vp, i64, i64, i64, vp, i64, vp, vp, i32, i32, vp, i32, vp, i64, vp, sz, vp]),
         "mq_stack_workspace_bytes": (sz, [vp, i32, i64]),
         "mq_stack_plan": (i32, [vp, i32, i64, vp, sz, vp]),
         "mq_linear_stack": (i32, [vp, vp]),
@@ -242,6 +245,42 @@ def mq_quant_matgptq(W, scales, zeros, widths, lam, K: Optional[int] = None, col
     _check(lib().mq_quant_matgptq(_ptr(W), W.stride(0), N, ncols, col0, _ptr(scales), _ptr(zeros), K, group, c,
                                   ctypes.cast(lam8, ctypes.c_void_p), _ptr(out), out.stride(0), _stream(stream)),
            "mq_quant_matgptq")
+    return out
+
+
+def _lambda8(widths, lam, where):
+    lam8 = (ctypes.c_float * 8)()
+    for r, l in zip(widths, lam):
+        if not 1 <= int(r) <= 8:
+            raise MqError(2, where)
+        lam8[int(r) - 1] = float(l)
+    return lam8
+
+
+def mq_matgptq_workspace_bytes(N: int, block: int = 128) -> int:
+    return lib().mq_matgptq_workspace_bytes(N, block)
+
+
+def mq_matgptq_quantize(W, U, scales, zeros, widths, lam, block: int = 128, c: int = 8, group: int = MQ_GROUP,
+                        out=None, stream=None):
+    """The MatGPTQ column loop on W (fp32 [N, K], OVERWRITTEN) given U, the upper Cholesky factor of H^-1.
+    Returns the uint8 parent codes [N, K]."""
+    import torch
+    N, K = W.shape
+    if W.stride(1) != 1 or U.stride(1) != 1:
+        raise ValueError("rows of W and U must be contiguous")
+    if tuple(U.shape) != (K, K):
+        raise ValueError("U must be [K, K]")
+    if out is None:
+        out = torch.empty((N, K), dtype=torch.uint8, device=W.device)
+    nbytes = mq_matgptq_workspace_bytes(N, block)
+    ws = torch.empty(max(nbytes, 4), dtype=torch.uint8, device=W.device)
+    if stream is not None:
+        ws.record_stream(stream)       # scratch of launches that are still running when this returns
+    lam8 = _lambda8(widths, lam, "mq_matgptq_quantize")
+    _check(lib().mq_matgptq_quantize(_ptr(W), W.stride(0), N, K, _ptr(U), U.stride(0), _ptr(scales), _ptr(zeros), group,
+                                     c, ctypes.cast(lam8, ctypes.c_void_p), block, _ptr(out), out.stride(0), _ptr(ws),
+                                     nbytes, _stream(stream)), "mq_matgptq_quantize")
     return out
 
 

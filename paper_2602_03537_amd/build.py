@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmq.so")
-SOURCES = ["mq_api.hip", "mq_pack.hip", "mq_linear.hip", "mq_gemm.hip", "mq_wide.hip", "mq_quant.hip"]
+SOURCES = ["mq_api.hip", "mq_pack.hip", "mq_linear.hip", "mq_gemm.hip", "mq_wide.hip", "mq_quant.hip", "mq_gptq.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

@@ -326,6 +326,36 @@ mq_status mq_quant_matgptq(const float *W, int64_t ldw, int64_t N, int64_t ncols
                : MQ_ERR_HIP;
 }
 
+size_t mq_matgptq_workspace_bytes(int64_t N, int block) {
+    if (N < 1 || N > kMaxDim || (block != 16 && block != 32 && block != 64 && block != 128)) return 0;
+    return align_up((size_t)N * (size_t)block * sizeof(float), 256);
+}
+
+mq_status mq_matgptq_quantize(float *W, int64_t ldw, int64_t N, int64_t K, const float *U, int64_t ldu,
+                              const mq_half *scales, const mq_half *zeros, int group, int c, const float *lambda,
+                              int block, uint8_t *Q, int64_t ldq, void *ws, size_t ws_bytes, mq_stream stream) {
+    if (!W || !U || !scales || !zeros || !lambda || !Q || !ws) return MQ_ERR_NULL;
+    if (c != kC) return MQ_ERR_BAD_R;
+    bool any = false;
+    for (int i = 0; i < kC; ++i) {
+        if (!std::isfinite(lambda[i]) || lambda[i] < 0.f) return MQ_ERR_BAD_R;
+        any = any || lambda[i] > 0.f;
+    }
+    if (!any) return MQ_ERR_BAD_R;
+    if (mq_status st = check_shape(N, K, group)) return st;
+    if (block != 16 && block != 32 && block != 64 && block != 128) return MQ_ERR_BAD_SHAPE;
+    if (ldw < K || ldu < K || ldq < K || ldw > ((int64_t)1 << 32) || ldu > ((int64_t)1 << 32) || ldq > ((int64_t)1 << 32))
+        return MQ_ERR_BAD_SHAPE;
+    if (!aligned(W, 4) || !aligned(U, 4) || !aligned(scales, 2) || !aligned(zeros, 2) || !aligned(ws, 4))
+        return MQ_ERR_ALIGN;
+    if (ws_bytes < mq_matgptq_workspace_bytes(N, block)) return MQ_ERR_BUF_TOO_SMALL;
+    return launch_gptq(W, ldw, N, K, U, ldu, reinterpret_cast<const _Float16 *>(scales),
+                       reinterpret_cast<const _Float16 *>(zeros), lambda, block, Q, ldq, static_cast<float *>(ws),
+                       (hipStream_t)stream) == hipSuccess
+               ? MQ_OK
+               : MQ_ERR_HIP;
+}
+
 size_t mq_stack_workspace_bytes(const mq_layer *layers, int n_layers, int64_t M) {
     if (!layers || n_layers < 1 || n_layers > (1 << 20) || M < 1 || M > MQ_MAX_M) return 0;
     for (int i = 0; i < n_layers; ++i)

@@ -104,6 +104,10 @@ hipError_t launch_pack_meta(const _Float16 *sc, const _Float16 *zr, int64_t N, i
                             _Float16 *zt, hipStream_t s);
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
 // Algorithm 1 (mq_quant.hip).  lambda: host, kC floats (width r at [r-1]); vec4: four columns per lane (alignment checked by the caller)
+// Algorithm 2 column loop (mq_gptq.hip): 2 * K / B launches on s.  E: device, N * B floats of scratch.
+hipError_t launch_gptq(float *W, int64_t ldw, int64_t N, int64_t K, const float *U, int64_t ldu, const _Float16 *scales,
+                       const _Float16 *zeros, const float *lambda, int B, uint8_t *Q, int64_t ldq, float *E,
+                       hipStream_t s);
 hipError_t launch_quant(const float *W, int64_t ldw, int64_t N, int64_t ncols, int64_t col0, const _Float16 *scales,
                         const _Float16 *zeros, int64_t G, const float *lambda, uint8_t *Q, int64_t ldq, bool vec4,
                         hipStream_t s);

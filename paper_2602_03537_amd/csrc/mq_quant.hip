@@ -1,96 +1,11 @@
 // Cross-bit-width choice of the parent code (Algorithm 1 of the paper): for every weight the code
 // q in 0..255 that minimises
 //     E(q) = sum_{r in R} lambda_r * (w - scale * (S(q, r) - zero))^2,      S = Eq. 1 (Section 2)
-// by brute force over all 256 candidates, as the paper does.
-//
-// The argmin is decided in floating point, so the operations are fixed: binary32, each rounded on
-// its own (contraction into fused multiply-adds is switched off here), in the order
-//     t = S - zero;  D = scale * t;  e = w - D;  p = e * e;  E = E + lambda_r * p      (r ascending)
-// and the smallest q wins a tie.  What the kernel saves against evaluating 256 x |R| terms is only
-// work whose result is the same bit for bit: S(q, r) is constant on runs of 2^(8-r) candidates, so
-// the term of width r is recomputed only where its slice changes, and the partial sum over the
-// widths below the lowest one that changed is reused.  The candidate loop is unrolled completely:
-// which slice changes at which q is known at compile time.
-#include "mq_internal.h"
-#include "mq_static_for.h"
+// by brute force over all 256 candidates, as the paper does (arithmetic: mq_quant_core.h).
+// One lane owns VEC consecutive weights of a row (same group: same scale and zero).
+#include "mq_quant_core.h"
 
 namespace mq {
-
-struct QuantLambda {
-    float v[kC];  // lambda of width r at v[r - 1]; 0 = not a target width
-};
-
-// the slice of candidate Q at width r changes against candidate Q - 1 (Eq. 1, round half up, clamp)
-constexpr int slice_index_of(int q, int r) {
-    const int sh = kC - r;
-    const int t = sh ? (q + (1 << (sh - 1))) >> sh : q;
-    return t < (1 << r) - 1 ? t : (1 << r) - 1;
-}
-constexpr bool slice_changes(int q, int r) { return q == 0 || slice_index_of(q, r) != slice_index_of(q - 1, r); }
-constexpr int popc8(uint32_t m) { int c = 0; for (int i = 0; i < 8; ++i) c += (m >> i) & 1; return c; }
-// position of width r among the widths of MASK, ascending
-constexpr int level_of(uint32_t mask, int r) { return popc8(mask & ((1u << (r - 1)) - 1)); }
-
-// MASK: bit r-1 set = the term of width r is evaluated (widths outside MASK must have lambda 0).
-// VEC consecutive weights of one row (same group: same scale and zero) per lane.
-template <uint32_t MASK, int VEC>
-__device__ __forceinline__ void choose_codes(const float (&w)[VEC], float s, float z, const QuantLambda &lam,
-                                             uint32_t (&qbest)[VEC]) {
-#pragma clang fp contract(off)
-    constexpr int NL = popc8(MASK);
-    float err[NL][VEC];   // lambda_r * (w - D_r)^2 of the current slice of each width
-    float pre[NL][VEC];   // pre[i] = err[0] + ... + err[i], added in this order
-    float best[VEC];
-#pragma unroll
-    for (int v = 0; v < VEC; ++v) {
-        best[v] = __builtin_inff();
-        qbest[v] = 0;
-    }
-    static_for<256>([&](auto qc) {
-#pragma clang fp contract(off)
-        constexpr int q = qc;
-        bool dirty = false;  // compile-time after unrolling: a lower width changed at this q
-        static_for<kC>([&](auto rc) {
-#pragma clang fp contract(off)
-            constexpr int r = rc + 1;
-            if constexpr ((MASK >> rc) & 1) {
-                constexpr int i = level_of(MASK, r);
-                constexpr bool ch = slice_changes(q, r);
-                if constexpr (ch) {
-                    constexpr float S = (float)(slice_index_of(q, r) << (kC - r));
-                    const float t = S - z;
-                    const float D = s * t;
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) {
-                        const float e = w[v] - D;
-                        const float p = e * e;
-                        err[i][v] = lam.v[rc] * p;
-                    }
-                }
-                if (ch || dirty) {
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) {
-                        if constexpr (i == 0)
-                            pre[i][v] = err[i][v];
-                        else
-                            pre[i][v] = pre[i - 1][v] + err[i][v];
-                    }
-                    dirty = true;
-                }
-            }
-        });
-        if (dirty) {  // otherwise E(q) == E(q - 1): cannot be a new strict minimum
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) {
-                const bool lt = pre[NL - 1][v] < best[v];
-                best[v] = lt ? pre[NL - 1][v] : best[v];
-                qbest[v] = lt ? (uint32_t)q : qbest[v];
-                // select now: the compiler would otherwise keep all 256 comparison masks for later
-                asm volatile("" : "+v"(qbest[v]));
-            }
-        }
-    });
-}
 
 template <uint32_t MASK, int VEC>
 __global__ __launch_bounds__(256) void quant_kernel(const float *__restrict__ W, int64_t ldw, int64_t N, int64_t ncols,
@@ -138,8 +53,6 @@ static hipError_t launch_quant_mask(const float *W, int64_t ldw, int64_t N, int6
     return hipGetLastError();
 }
 
-// Built variants: {8} (plain rounding to the nearest code), {3,4,8} (the paper's experiments),
-// {2,3,4,6,8} (the widths this library packs), and all eight widths for anything else.
 hipError_t launch_quant(const float *W, int64_t ldw, int64_t N, int64_t ncols, int64_t col0, const _Float16 *scales,
                         const _Float16 *zeros, int64_t G, const float *lambda, uint8_t *Q, int64_t ldq, bool vec4,
                         hipStream_t s) {
@@ -149,9 +62,11 @@ hipError_t launch_quant(const float *W, int64_t ldw, int64_t N, int64_t ncols, i
         lam.v[i] = lambda[i];
         if (lambda[i] != 0.f) need |= 1u << i;
     }
-    if (!(need & ~0x80u)) return launch_quant_mask<0x80u>(W, ldw, N, ncols, col0, scales, zeros, G, lam, Q, ldq, vec4, s);
-    if (!(need & ~0x8Cu)) return launch_quant_mask<0x8Cu>(W, ldw, N, ncols, col0, scales, zeros, G, lam, Q, ldq, vec4, s);
-    if (!(need & ~0xAEu)) return launch_quant_mask<0xAEu>(W, ldw, N, ncols, col0, scales, zeros, G, lam, Q, ldq, vec4, s);
+    switch (quant_variant_mask(need)) {
+        case 0x80u: return launch_quant_mask<0x80u>(W, ldw, N, ncols, col0, scales, zeros, G, lam, Q, ldq, vec4, s);
+        case 0x8Cu: return launch_quant_mask<0x8Cu>(W, ldw, N, ncols, col0, scales, zeros, G, lam, Q, ldq, vec4, s);
+        case 0xAEu: return launch_quant_mask<0xAEu>(W, ldw, N, ncols, col0, scales, zeros, G, lam, Q, ldq, vec4, s);
+    }
     return launch_quant_mask<0xFFu>(W, ldw, N, ncols, col0, scales, zeros, G, lam, Q, ldq, vec4, s);
 }
 

@@ -796,3 +796,101 @@ def test_quant_matgptq_rejects_bad_arguments_loudly():
         mq.mq_quant_matgptq(Wd, sd, zd, (8,), (1.0,), c=7)
     with pytest.raises(mq.MqError):
         mq.mq_quant_matgptq(Wd[:, :8], sd, zd, (8,), (1.0,), K=128, col0=124)        # slab runs past the last column
+
+
+# ------------------------------------------------------------------ Algorithm 2: the MatGPTQ column loop
+def _cholesky_factor(K, seed):
+    """U, the upper Cholesky factor of (2 X X^T + damping)^-1 for seeded correlated features (numpy float64 -> float32)."""
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((K, 4 * K)) * (1.0 + 3.0 * rng.random((K, 1)))
+    X += 0.5 * X[rng.permutation(K), :]
+    H = 2.0 * X @ X.T
+    H += 0.01 * np.mean(np.diag(H)) * np.eye(K)
+    return np.linalg.cholesky(np.linalg.inv(H)).T.astype(np.float32)
+
+
+@pytest.mark.parametrize("widths,lam", [((8,), (1.0,)), ((3, 4, 8), (1.0, 1.0, 1.0)), ((3, 4, 8), (1.0, 0.5, 0.1)),
+                                        ((2, 3, 4, 6, 8), (1.0,) * 5), ((2, 5), (1.0, 2.0))])
+@pytest.mark.parametrize("shape_block", [(64, 256, 128), (70, 384, 128), (3, 256, 32), (130, 256, 64), (16, 128, 16)])
+def test_matgptq_column_loop_bit_exact(widths, lam, shape_block):
+    N, K, block = shape_block
+    W, s, z = _quant_inputs(N, K, [90, N, K])
+    U = _cholesky_factor(K, [90, K])
+    ref, _ = oracle.matgptq_quantize(W, U, s, z, C, widths, lam, 128, block, np.float32)
+    Wd = dev(W.copy())
+    got = mq.mq_matgptq_quantize(Wd, dev(U), dev(s), dev(z), widths, lam, block=block)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), ref), (widths, lam, shape_block)
+
+
+def test_matgptq_column_loop_block_size_changes_nothing_and_beats_plain_rounding():
+    N, K = 96, 512
+    W, s, z = _quant_inputs(N, K, [91])
+    rng = np.random.default_rng(91)
+    X = rng.standard_normal((K, 4 * K)) * (1.0 + 3.0 * rng.random((K, 1)))
+    H = 2.0 * X @ X.T
+    H += 0.01 * np.mean(np.diag(H)) * np.eye(K)
+    U = np.linalg.cholesky(np.linalg.inv(H)).T.astype(np.float32)
+    widths, lam = (3, 4, 8), (1.0, 1.0, 1.0)
+    outs = [mq.mq_matgptq_quantize(dev(W.copy()), dev(U), dev(s), dev(z), widths, lam, block=b).cpu().numpy()
+            for b in (16, 32, 64, 128)]
+    for o in outs[1:]:
+        assert np.array_equal(o, outs[0])
+    q1 = mq.mq_quant_matgptq(dev(W), dev(s), dev(z), widths, lam).cpu().numpy()       # no error propagation
+
+    def loss(codes):
+        d = W.astype(np.float64) - np.mean([oracle.dequant(oracle.slice_codes(codes, C, r), s, z, 128) for r in widths], 0)
+        return np.trace(d @ H @ d.T)
+    assert loss(outs[0]) < loss(q1)
+
+
+def test_matgptq_column_loop_strided_buffers_and_guard_bytes():
+    N, K = 40, 256
+    W, s, z = _quant_inputs(N, K, [92])
+    U = _cholesky_factor(K, [92])
+    ref, _ = oracle.matgptq_quantize(W, U, s, z, C, (3, 4, 8), (1, 1, 1), 128, 128, np.float32)
+    Wbuf = torch.full((N, K + 24), float("nan"), dtype=torch.float32, device=DEV)
+    Wbuf[:, 8:8 + K] = dev(W)
+    Ubuf = torch.full((K, K + 8), float("nan"), dtype=torch.float32, device=DEV)
+    Ubuf[:, :K] = dev(U)
+    Qbuf = torch.full((N, K + 16), 0xAB, dtype=torch.uint8, device=DEV)
+    mq.mq_matgptq_quantize(Wbuf[:, 8:8 + K], Ubuf[:, :K], dev(s), dev(z), (3, 4, 8), (1, 1, 1), out=Qbuf[:, 4:4 + K])
+    torch.cuda.synchronize()
+    q = Qbuf.cpu().numpy()
+    assert np.array_equal(q[:, 4:4 + K], ref)
+    assert (q[:, :4] == 0xAB).all() and (q[:, 4 + K:] == 0xAB).all()
+    assert torch.isnan(Wbuf[:, :8]).all() and torch.isnan(Wbuf[:, 8 + K:]).all()      # the loop stays inside W
+
+
+def test_matgptq_column_loop_llama_width_sampled_rows():
+    # K = 4096 (32 blocks of 128 columns), rows are independent so the oracle runs on a sample of them
+    N, K = 512, 4096
+    g = torch.Generator(device=DEV)
+    g.manual_seed(93)
+    W = torch.randn((N, K), generator=g, device=DEV, dtype=torch.float32) * 0.02
+    L = synth.make_layer_device(N, K, 1, seed=93, device=DEV, want_x=False)
+    X = torch.randn((K, 2 * K), generator=g, device=DEV, dtype=torch.float32) * (1.0 + 3.0 * torch.rand((K, 1), generator=g, device=DEV))
+    H = (2.0 * X @ X.T).double()
+    H += 0.01 * H.diagonal().mean() * torch.eye(K, device=DEV, dtype=torch.float64)
+    U = torch.linalg.cholesky(torch.linalg.inv(H)).T.contiguous().float()
+    rows = np.array([0, 63, 64, 311, N - 1])
+    ridx = torch.from_numpy(rows).to(DEV)
+    Wh, sh, zh = W[ridx].cpu().numpy(), L["scales"][ridx].cpu().numpy(), L["zeros"][ridx].cpu().numpy()
+    q = mq.mq_matgptq_quantize(W.clone(), U, L["scales"], L["zeros"], (3, 4, 8), (1.0, 1.0, 1.0))
+    torch.cuda.synchronize()
+    ref, _ = oracle.matgptq_quantize(Wh, U.cpu().numpy(), sh, zh, C, (3, 4, 8), (1.0, 1.0, 1.0), 128, 128, np.float32)
+    assert np.array_equal(q[ridx].cpu().numpy(), ref)
+
+
+def test_matgptq_column_loop_rejects_bad_arguments_loudly():
+    W, s, z = _quant_inputs(64, 256, [94])
+    U = _cholesky_factor(256, [94])
+    Wd, Ud, sd, zd = dev(W), dev(U), dev(s), dev(z)
+    with pytest.raises(mq.MqError):
+        mq.mq_matgptq_quantize(Wd, Ud, sd, zd, (8,), (1.0,), block=48)
+    with pytest.raises(mq.MqError):
+        mq.mq_matgptq_quantize(Wd, Ud, sd, zd, (8,), (0.0,))
+    with pytest.raises(ValueError):
+        mq.mq_matgptq_quantize(Wd, Ud[:, :128], sd, zd, (8,), (1.0,))                 # factor narrower than K
+    with pytest.raises(mq.MqError):
+        mq.mq_matgptq_quantize(Wd, Ud, sd, zd, (8,), (1.0,), c=4)

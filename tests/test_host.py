@@ -161,6 +161,31 @@ def test_quant_validation():
     assert call(s=FAKE + 1) == _st("MQ_ERR_ALIGN")
 
 
+def test_matgptq_loop_validation():
+    # every call below fails validation: nothing is ever launched with these fake pointers
+    L = mq.lib()
+    lam = (ctypes.c_float * 8)(0, 0, 1, 1, 0, 0, 0, 1)
+    lp = ctypes.cast(lam, ctypes.c_void_p)
+    assert L.mq_matgptq_workspace_bytes(4096, 128) == 4096 * 128 * 4
+    assert L.mq_matgptq_workspace_bytes(4096, 48) == 0 and L.mq_matgptq_workspace_bytes(0, 128) == 0
+
+    def call(W=FAKE, ldw=256, N=64, K=256, U=FAKE, ldu=256, s=FAKE, z=FAKE, group=128, c=8, lam=lp, block=128, Q=FAKE,
+             ldq=256, ws=FAKE, wsb=1 << 30):
+        return L.mq_matgptq_quantize(W, ldw, N, K, U, ldu, s, z, group, c, lam, block, Q, ldq, ws, wsb, None)
+    for k in ("W", "U", "s", "z", "lam", "Q", "ws"):
+        assert call(**{k: None}) == _st("MQ_ERR_NULL"), k
+    assert call(c=7) == _st("MQ_ERR_BAD_R")
+    zero = (ctypes.c_float * 8)()
+    assert call(lam=ctypes.cast(zero, ctypes.c_void_p)) == _st("MQ_ERR_BAD_R")
+    assert call(block=48) == _st("MQ_ERR_BAD_SHAPE")
+    assert call(K=200) == _st("MQ_ERR_BAD_GROUP")
+    assert call(ldw=128) == _st("MQ_ERR_BAD_SHAPE")
+    assert call(ldu=128) == _st("MQ_ERR_BAD_SHAPE")
+    assert call(ldq=255) == _st("MQ_ERR_BAD_SHAPE")
+    assert call(U=FAKE + 2) == _st("MQ_ERR_ALIGN")
+    assert call(wsb=64 * 128 * 4 - 1) == _st("MQ_ERR_BUF_TOO_SMALL")
+
+
 def _linear_args(**kw):
     a = dict(x=FAKE, M=1, W=FAKE, st=FAKE, zt=FAKE, N=64, K=128, r=4, group=128, y=FAKE, ws=FAKE, wsb=1 << 30)
     a.update(kw)
