@@ -470,7 +470,7 @@ def bench_gptq(args, mq, synth, torch, np, dev):
     widths, lam = (3, 4, 8), (1.0, 1.0, 1.0)
     g = torch.Generator(device=dev)
     g.manual_seed(777)
-    table, tot_w, tot_t = {}, 0.0, 0.0
+    table, tot_w, tot_t, tot_fl = {}, 0.0, 0.0, 0.0
     for (N, K) in ((4096, 4096), (11008, 4096), (4096, 11008)):
         L = synth.make_layer_device(N, K, 1, seed=8100 + N, device=dev, want_x=False)
         W = torch.randn((N, K), generator=g, device=dev, dtype=torch.float32) * 0.02
@@ -494,17 +494,26 @@ def bench_gptq(args, mq, synth, torch, np, dev):
             e1.record()
             torch.cuda.synchronize()
             t = e0.elapsed_time(e1) * 1e-3                      # the last repetition is reported
+        # algorithmic flops: Algorithm 1's brute force per weight (256 x (6|R| + 1)), the error (3|R| + 1 per weight)
+        # and the updates (every weight receives one multiply and one subtract from each earlier column: N K (K-1))
+        fl = N * K * (256.0 * (6 * len(widths) + 1) + 3 * len(widths) + 1) + float(N) * K * (K - 1)
         table[f"{N}x{K}"] = {"ms": round(t * 1e3, 2), "Mweights_per_s": round(N * K / t / 1e6, 1),
-                             "us_per_column": round(t / K * 1e6, 2)}
+                             "us_per_column": round(t / K * 1e6, 2), "TFLOPs": round(fl / t / 1e12, 1)}
         tot_w += N * K
         tot_t += t
+        tot_fl += fl
         del W, Wc, Q, U, L
     out = _base_line("MatGPTQ column loop (Algorithm 2) throughput, R = {3,4,8}", tot_w / tot_t / 1e9, "Gweights/s", args,
                      tot_t * 1e3, "Llama-2-7B layer shapes (4096x4096, 11008x4096, 4096x11008), fp32 weights, group 128, "
                      "block 128, c = 8, R = {3,4,8}, lambda = 1; Cholesky factor of the inverse Hessian given", {})
     out["dtype"] = "f32"
     out["table"] = table
-    out["roofline"] = None
+    ach = tot_fl / tot_t / 1e12
+    # a dependent chain over the columns: the figure is low by construction (latency per column step x K)
+    out["roofline"] = {"bound": "alu", "kernel": "mq::gptq_block_kernel<140, LPR> + mq::gptq_trailing_kernel<true>",
+                       "achieved": round(ach, 1), "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                       "frac": round(ach / FP32_VECTOR_PEAK_TFLOPS, 4), "avg_launch_us": None,
+                       "algorithmic_flops_per_launch": None, "traffic": None}
     out["cpu_baseline"] = None
     print(json.dumps(out))
     return 0

@@ -91,6 +91,62 @@ __device__ __forceinline__ void choose_codes(const float (&w)[VEC], float s, flo
     });
 }
 
+// The same decision with the 256 candidates spread over several lanes: this lane evaluates the CPL
+// candidates q_base .. q_base + CPL - 1 (q_base a multiple of CPL) and returns its best (E, q);
+// the caller takes the lexicographic minimum of (E, q) over the lanes that share the weight, which
+// is the first minimum over all 256.  E(q) is computed by exactly the operations of choose_codes,
+// so the result is bit-identical.  A slice can change inside the run only at compile-time known
+// offsets (runs no longer than CPL) or at its start (longer runs), where every term is computed.
+template <uint32_t MASK, int CPL>
+__device__ __forceinline__ void choose_codes_part(float w, float s, float z, const QuantLambda &lam, uint32_t q_base,
+                                                  float &best, uint32_t &qbest) {
+#pragma clang fp contract(off)
+    constexpr int NL = popc8(MASK);
+    static_assert(CPL >= 1 && 256 % CPL == 0, "candidates per lane divide 256");
+    float err[NL], pre[NL];
+    best = __builtin_inff();
+    qbest = q_base;
+    static_for<CPL>([&](auto qc) {
+#pragma clang fp contract(off)
+        constexpr int ql = qc;
+        const uint32_t q = q_base + ql;
+        bool dirty = false;
+        static_for<kC>([&](auto rc) {
+#pragma clang fp contract(off)
+            constexpr int r = rc + 1;
+            if constexpr ((MASK >> rc) & 1) {
+                constexpr int i = level_of(MASK, r);
+                constexpr int sh = kC - r, step = 1 << sh;
+                constexpr bool ch = ql == 0 || (step <= CPL && (ql + step / 2) % step == 0);
+                if constexpr (ch) {
+                    uint32_t t = sh ? (q + (step >> 1)) >> sh : q;
+                    constexpr uint32_t top = (1u << r) - 1;
+                    t = t < top ? t : top;
+                    const float S = (float)(t << sh);
+                    const float d0 = S - z;
+                    const float D = s * d0;
+                    const float e = w - D;
+                    const float p = e * e;
+                    err[i] = lam.v[rc] * p;
+                }
+                if (ch || dirty) {
+                    if constexpr (i == 0)
+                        pre[i] = err[i];
+                    else
+                        pre[i] = pre[i - 1] + err[i];
+                    dirty = true;
+                }
+            }
+        });
+        if (dirty) {
+            const bool lt = pre[NL - 1] < best;
+            best = lt ? pre[NL - 1] : best;
+            qbest = lt ? q : qbest;
+            asm volatile("" : "+v"(qbest));
+        }
+    });
+}
+
 // Built variants: {8} (plain rounding to the nearest code), {3,4,8} (the paper's experiments),
 // {2,3,4,6,8} (the widths this library packs), and all eight widths for anything else.
 inline uint32_t quant_variant_mask(uint32_t need) {

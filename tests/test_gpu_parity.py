@@ -860,6 +860,15 @@ def test_matgptq_column_loop_strided_buffers_and_guard_bytes():
     assert np.array_equal(q[:, 4:4 + K], ref)
     assert (q[:, :4] == 0xAB).all() and (q[:, 4 + K:] == 0xAB).all()
     assert torch.isnan(Wbuf[:, :8]).all() and torch.isnan(Wbuf[:, 8 + K:]).all()      # the loop stays inside W
+    # odd strides and a base address that rules out 16-byte accesses: the one-column-per-lane update
+    Wodd = torch.full((N, K + 3), float("nan"), dtype=torch.float32, device=DEV)
+    Wodd[:, 1:1 + K] = dev(W)
+    Uodd = torch.full((K, K + 1), float("nan"), dtype=torch.float32, device=DEV)
+    Uodd[:, :K] = dev(U)
+    q2 = mq.mq_matgptq_quantize(Wodd[:, 1:1 + K], Uodd[:, :K], dev(s), dev(z), (3, 4, 8), (1, 1, 1), block=32)
+    torch.cuda.synchronize()
+    assert np.array_equal(q2.cpu().numpy(), ref)
+    assert torch.isnan(Wodd[:, :1]).all() and torch.isnan(Wodd[:, 1 + K:]).all()
 
 
 def test_matgptq_column_loop_llama_width_sampled_rows():
@@ -894,3 +903,16 @@ def test_matgptq_column_loop_rejects_bad_arguments_loudly():
         mq.mq_matgptq_quantize(Wd, Ud[:, :128], sd, zd, (8,), (1.0,))                 # factor narrower than K
     with pytest.raises(mq.MqError):
         mq.mq_matgptq_quantize(Wd, Ud, sd, zd, (8,), (1.0,), c=4)
+
+
+@pytest.mark.parametrize("N,K", [(4096, 256), (4100, 128), (16384, 128), (16390, 256)])   # 64, 16, 16, 4 lanes per row
+def test_matgptq_column_loop_many_rows_sampled(N, K):
+    # with more rows fewer lanes share a row (16, then 4): the same codes, checked on sampled rows
+    W, s, z = _quant_inputs(N, K, [95, N, K])
+    U = _cholesky_factor(K, [95, K])
+    rows = np.unique(np.concatenate([[0, 1, 3, 4, 15, 16, 63, 64, N - 2, N - 1],
+                                     np.random.default_rng(N).integers(0, N, 22)]))
+    for widths, lam in (((3, 4, 8), (1.0, 1.0, 1.0)), ((2, 3, 4, 6, 8), (0.1, 0.5, 1.0, 1.0, 0.25))):
+        q = mq.mq_matgptq_quantize(dev(W.copy()), dev(U), dev(s), dev(z), widths, lam).cpu().numpy()
+        ref, _ = oracle.matgptq_quantize(W[rows], U, s[rows], z[rows], C, widths, lam, 128, 128, np.float32)
+        assert np.array_equal(q[rows], ref), (N, K, widths)
