@@ -13,7 +13,7 @@ streams from HBM.
 Prints ONE JSON line: effective HBM GB/s over the step (algorithmic bytes:
 r/8 per weight + fp16 scale and zero per group + activations in and out), the
 per-r microseconds and GB/s, the roofline object of the dominant kernel
-(mq::stack_kernel<1, 1>, HBM-bound) measured with events on the launch stream, and
+(mq::stack_kernel<1, 1, false>, HBM-bound) measured with events on the launch stream, and
 the CPU oracle timed on the host cores on a bounded sample.
 """
 from __future__ import annotations
@@ -29,10 +29,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-# HBM bytes per launch of mq::stack_kernel<1, 1> on the default workload (mean over the five widths),
+# HBM bytes per launch of mq::stack_kernel<1, 1, false> on the default workload (mean over the five widths),
 # from the two rocprofv3 --pmc runs summarised in profiles/stack_kernel_llama2_7b_m1_hbm_traffic.txt
 # (FETCH_SIZE scaled by 1.9987, WRITE_SIZE by 1.0, both calibrated on a 45 MB copy in the same run).
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 3937064629
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 3937068656
 WIDTHS = (2, 3, 4, 6, 8)
 
 
@@ -169,12 +169,12 @@ def main() -> int:
                          "frac_of_8TBps": round(gbps / HBM_PEAK_GBPS, 4), "algorithmic_MB": round(stacks[r]["bytes"] / 1e6, 1)}
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # roofline of the dominant kernel (mq::stack_kernel<1, 1>): algorithmic bytes per launch / mean launch duration
+    # roofline of the dominant kernel (mq::stack_kernel<1, 1, false>): algorithmic bytes per launch / mean launch duration
     launches = [u for r in WIDTHS for u in per_r_us[r]]
     avg_launch_us = float(np.mean(launches))
     bytes_per_launch = step_bytes / len(WIDTHS)
     achieved = bytes_per_launch / avg_launch_us / 1e3
-    roofline = {"bound": "hbm", "kernel": "mq::stack_kernel<1, 1>", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+    roofline = {"bound": "hbm", "kernel": "mq::stack_kernel<1, 1, false>", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                 "avg_launch_us": round(avg_launch_us, 1), "algorithmic_bytes_per_launch": int(bytes_per_launch),
                 "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH if args.layers == 32 else None}
@@ -294,7 +294,7 @@ def bench_mixed_stack(args, mq, synth, torch, np, dev):
                      ms, f"{'Llama-3-70B' if big else 'Llama-2-7B'}-shaped stack, {n_blocks} blocks ({len(layers)} linears), "
                      f"M={M}, per-layer r from {{2,3,4,6,8}} by seed, parameter-weighted mean {mean:.3f} bits",
                      {"M": M, "mean_bits": round(mean, 4), "algorithmic_GB_per_step": round(nbytes / 1e9, 3)})
-    kernel = ("mq::stack_kernel<%d, 1>" % M if M <= 4 else "mq::gemm_stack_kernel" if M <= 16
+    kernel = ("mq::stack_kernel<%d, 1, false>" % M if M <= 4 else "mq::gemm_stack_kernel" if M <= 16
               else "mq::wide_stack_kernel")
     ach = nbytes / float(np.mean(us)) / 1e3
     out["stack_us_median"] = round(float(np.median(us)), 1)
