@@ -354,17 +354,19 @@ def bench_resident_parent(args, mq, synth, torch, np, dev):
                        "traffic": None}
 
     # re-slicing rate: every distinct shape of the block at every width, over all resident copies of that shape (cold)
+    # every layer has its own output buffer (sized for r = 8), as a real switch of budget would
+    for L in layers:
+        L["out"] = torch.empty(mq.mq_packed_bytes(L["N"], L["K"], 8), dtype=torch.uint8, device=dev)
     table, tot = {}, {r: [0.0, 0.0] for r in WIDTHS}
     for (N, K) in sorted({(N, K) for (_, N, K) in block}):
         same = [L for L in layers if L["N"] == N and L["K"] == K][:16]
         for r in WIDTHS:
-            outb = torch.empty(mq.mq_packed_bytes(N, K, r), dtype=torch.uint8, device=dev)
-            mq.mq_reslice(same[0]["packed_W"], N, K, 8, r, out=outb)
+            mq.mq_reslice(same[0]["packed_W"], N, K, 8, r, out=same[0]["out"])
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for L in same:
-                mq.mq_reslice(L["packed_W"], N, K, 8, r, out=outb)
+                mq.mq_reslice(L["packed_W"], N, K, 8, r, out=L["out"])
             e1.record()
             torch.cuda.synchronize()
             t = e0.elapsed_time(e1) * 1e-3 / len(same)
@@ -373,11 +375,26 @@ def bench_resident_parent(args, mq, synth, torch, np, dev):
             cnt = sum(1 for (_, n, k) in block if (n, k) == (N, K)) * n_blocks
             tot[r][0] += b * cnt
             tot[r][1] += t * cnt
-            del outb
     out["reslice"] = table
     out["reslice_whole_model"] = {str(r): {"ms": round(tot[r][1] * 1e3, 2), "GBps": round(tot[r][0] / tot[r][1] / 1e9, 1),
                                            "frac_of_8TBps": round(tot[r][0] / tot[r][1] / 1e9 / HBM_PEAK_GBPS, 4)}
                                   for r in WIDTHS}
+    # the whole model switched to one width with mq_reslice_many (one launch per 16 layers), every resident layer once
+    many = {}
+    for r in WIDTHS:
+        jobs = [dict(packed_parent=L["packed_W"], N=L["N"], K=L["K"], r=r, out=L["out"]) for L in layers]
+        mq.mq_reslice_many(jobs[:16])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        mq.mq_reslice_many(jobs)
+        e1.record()
+        torch.cuda.synchronize()
+        t = e0.elapsed_time(e1) * 1e-3
+        b = (1.0 + r / 8.0) * nweights
+        many[str(r)] = {"ms": round(t * 1e3, 2), "GBps": round(b / t / 1e9, 1),
+                        "frac_of_8TBps": round(b / t / 1e9 / HBM_PEAK_GBPS, 4)}
+    out["reslice_many_whole_model"] = many
     # fused slice + pack from a row-major parent (load-time form of the same step), largest shape of the block
     N, K = max({(N, K) for (_, N, K) in block}, key=lambda nk: nk[0] * nk[1])
     parent = mq.mq_unpack(layers[[i for i, L in enumerate(layers) if (L["N"], L["K"]) == (N, K)][0]]["packed_W"], N, K, 8, 8)

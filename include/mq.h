@@ -131,6 +131,21 @@ mq_status mq_slice_pack(const uint8_t *parent, int64_t N, int64_t K, int c, int 
 mq_status mq_reslice(const void *packed_parent, int64_t N, int64_t K, int c, int r, void *packed,
                      size_t packed_bytes, mq_stream stream);
 
+/* mq_reslice for many layers at once (one launch per 16 layers; small layers are launch-bound one
+ * by one): switches a whole resident model to another budget.  Each job as mq_reslice, with its
+ * own r; outputs of different jobs must not overlap each other or any parent.
+ *   jobs : HOST array of n_jobs entries; pointers inside are device pointers
+ * Errors: as mq_reslice, for the first offending job; nothing is enqueued on error. */
+typedef struct {
+    const void *packed_parent; /* device, mq_pack(parent, 8, 8) of this layer */
+    void *packed;              /* device, packed_bytes >= mq_packed_bytes(N, K, r) */
+    size_t packed_bytes;
+    int64_t N, K;
+    int32_t r;        /* 2, 3, 4, 6 or 8 */
+    int32_t reserved; /* 0 */
+} mq_reslice_job;
+mq_status mq_reslice_many(const mq_reslice_job *jobs, int n_jobs, int c, mq_stream stream);
+
 /* Re-tile the per-group scale and zero-offset (Section 3.2 item 1: computed at
  * the master width c and shared by every r) to match the weight tiles:
  *   scales, zeros     : device, fp16 [N, K/group] row-major

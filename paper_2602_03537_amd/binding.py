@@ -12,7 +12,7 @@ __all__ = [
     "MqError", "lib", "lib_path", "MQ_ROW_BLOCK", "MQ_GROUP", "MQ_MAX_M", "STATUS",
     "mq_status_str", "mq_version", "mq_packed_bytes", "mq_meta_bytes", "mq_workspace_bytes",
     "mq_workspace_init", "mq_slice_codes", "mq_pack", "mq_unpack", "mq_pack_meta", "mq_linear",
-    "mq_slice_pack", "mq_reslice", "mq_linear_from_parent", "mq_quant_matgptq",
+    "mq_slice_pack", "mq_reslice", "mq_reslice_many", "MqResliceJob", "mq_linear_from_parent", "mq_quant_matgptq",
     "mq_matgptq_workspace_bytes", "mq_matgptq_quantize",
     "mq_stack_workspace_bytes", "mq_stack_plan", "mq_linear_stack", "MqLayer",
     "new_workspace", "prepare_layer",
@@ -44,6 +44,14 @@ class MqLayer(ctypes.Structure):
         ("x", ctypes.c_void_p), ("y", ctypes.c_void_p),
         ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("r", ctypes.c_int32), ("group", ctypes.c_int32),
         ("from_parent", ctypes.c_int32), ("reserved", ctypes.c_int32),
+    ]
+
+
+class MqResliceJob(ctypes.Structure):
+    """mq_reslice_job of include/mq.h."""
+    _fields_ = [
+        ("packed_parent", ctypes.c_void_p), ("packed", ctypes.c_void_p), ("packed_bytes", ctypes.c_size_t),
+        ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("r", ctypes.c_int32), ("reserved", ctypes.c_int32),
     ]
 
 
@@ -80,6 +88,7 @@ def lib():
         "mq_linear": (i32, [vp, i64, vp, vp, vp, i64, i64, i32, i32, vp, vp, sz, vp]),
         "mq_slice_pack": (i32, [vp, i64, i64, i32, i32, vp, sz, vp]),
         "mq_reslice": (i32, [vp, i64, i64, i32, i32, vp, sz, vp]),
+        "mq_reslice_many": (i32, [vp, i32, i32, vp]),
         "mq_linear_from_parent": (i32, [vp, i64, vp, vp, vp, i64, i64, i32, i32, vp, vp, sz, vp]),
         "mq_quant_matgptq": (i32, [vp, i64, i64, i64, i64, vp, vp, i64, i32, i32, vp, vp, i64, vp]),
         "mq_matgptq_workspace_bytes": (sz, [i64, i32]),
@@ -212,6 +221,22 @@ def mq_reslice(packed_parent, N: int, K: int, c: int, r: int, out=None, stream=N
         out = torch.empty(max(mq_packed_bytes(N, K, r), 16), dtype=torch.uint8, device=packed_parent.device)
     _check(lib().mq_reslice(_ptr(packed_parent), N, K, c, r, _ptr(out), out.numel(), _stream(stream)), "mq_reslice")
     return out
+
+
+def mq_reslice_many(jobs: Sequence[dict], c: int = 8, stream=None):
+    """jobs: dicts with packed_parent (tensor), N, K, r and optionally out (tensor).  Returns the output tensors."""
+    import torch
+    arr = (MqResliceJob * len(jobs))()
+    outs = []
+    for i, J in enumerate(jobs):
+        out = J.get("out")
+        if out is None:
+            out = torch.empty(max(mq_packed_bytes(J["N"], J["K"], J["r"]), 16), dtype=torch.uint8,
+                              device=J["packed_parent"].device)
+        outs.append(out)
+        arr[i] = MqResliceJob(_ptr(J["packed_parent"]), _ptr(out), out.numel(), J["N"], J["K"], J["r"], 0)
+    _check(lib().mq_reslice_many(ctypes.cast(arr, ctypes.c_void_p), len(jobs), c, _stream(stream)), "mq_reslice_many")
+    return outs
 
 
 def mq_linear_from_parent(x, packed_parent, scales_t, zeros_t, N: int, K: int, r: int, group: int, ws, y=None,

@@ -302,6 +302,35 @@ mq_status mq_reslice(const void *packed_parent, int64_t N, int64_t K, int c, int
                : MQ_ERR_HIP;
 }
 
+mq_status mq_reslice_many(const mq_reslice_job *jobs, int n_jobs, int c, mq_stream stream) {
+    if (!jobs) return MQ_ERR_NULL;
+    if (n_jobs < 1 || n_jobs > (1 << 20)) return MQ_ERR_BAD_SHAPE;
+    if (c != kC) return MQ_ERR_BAD_R;
+    std::vector<const uint4 *> src((size_t)n_jobs);
+    std::vector<uint4 *> dst((size_t)n_jobs);
+    std::vector<int64_t> N((size_t)n_jobs), K((size_t)n_jobs);
+    std::vector<int> r((size_t)n_jobs);
+    for (int i = 0; i < n_jobs; ++i) {
+        const mq_reslice_job &j = jobs[i];
+        if (!j.packed_parent || !j.packed) return MQ_ERR_NULL;
+        if (!valid_pack_r(j.r) || j.reserved != 0) return MQ_ERR_BAD_R;
+        if (mq_status st = check_shape(j.N, j.K, kGroup)) return st;
+        if (!aligned(j.packed_parent, 16) || !aligned(j.packed, 16)) return MQ_ERR_ALIGN;
+        if (j.packed_bytes < mq_packed_bytes(j.N, j.K, j.r)) return MQ_ERR_BUF_TOO_SMALL;
+        const char *a = static_cast<const char *>(j.packed_parent), *b = static_cast<const char *>(j.packed);
+        if (a < b + mq_packed_bytes(j.N, j.K, j.r) && b < a + mq_packed_bytes(j.N, j.K, kC)) return MQ_ERR_UNSUPPORTED;
+        src[i] = static_cast<const uint4 *>(j.packed_parent);
+        dst[i] = static_cast<uint4 *>(j.packed);
+        N[i] = j.N;
+        K[i] = j.K;
+        r[i] = j.r;
+    }
+    return launch_reslice_many(src.data(), dst.data(), N.data(), K.data(), r.data(), n_jobs, (hipStream_t)stream) ==
+                   hipSuccess
+               ? MQ_OK
+               : MQ_ERR_HIP;
+}
+
 mq_status mq_quant_matgptq(const float *W, int64_t ldw, int64_t N, int64_t ncols, int64_t col0, const mq_half *scales,
                            const mq_half *zeros, int64_t K, int group, int c, const float *lambda, uint8_t *Q,
                            int64_t ldq, mq_stream stream) {

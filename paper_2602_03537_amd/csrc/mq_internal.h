@@ -100,6 +100,10 @@ hipError_t launch_pack(const uint8_t *S, int64_t N, int64_t K, int r, uint4 *pac
 hipError_t launch_unpack(const uint4 *packed, int64_t N, int64_t K, int r, uint8_t *S, hipStream_t s);
 hipError_t launch_slice_pack(const uint8_t *parent, int64_t N, int64_t K, int r, uint4 *packed, hipStream_t s);
 hipError_t launch_reslice(const uint4 *parent8, int64_t N, int64_t K, int r, uint4 *packed, hipStream_t s);
+// n layers in ceil(n / kResliceBatch) launches; all arrays are host arrays of n entries
+constexpr int kResliceBatch = 16;
+hipError_t launch_reslice_many(const uint4 *const *src, uint4 *const *dst, const int64_t *N, const int64_t *K,
+                               const int *r, int n, hipStream_t s);
 hipError_t launch_pack_meta(const _Float16 *sc, const _Float16 *zr, int64_t N, int64_t G, _Float16 *st,
                             _Float16 *zt, hipStream_t s);
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);

@@ -120,16 +120,11 @@ template <int R> __device__ __forceinline__ uint32_t slice_pair_index(uint32_t v
     return __builtin_bit_cast(uint32_t, t);
 }
 
+// one lane's share of a tile: 8 16-byte pieces of the parent in, R pieces out
 template <int R>
-__global__ __launch_bounds__(256) void reslice_kernel(const uint4 *__restrict__ parent8, uint4 *__restrict__ packed,
-                                                      int64_t ntiles) {
+__device__ __forceinline__ void reslice_tile(const uint4 *__restrict__ src, uint4 *__restrict__ dst) {
     using T = Layout<R>;
-    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int lane = threadIdx.x & 63;
-    const int64_t tile = tid >> 6;
-    if (tile >= ntiles) return;
     uint32_t q[4 * kC];
-    const uint4 *src = parent8 + tile * (kC * 64) + lane;
 #pragma unroll
     for (int i = 0; i < kC; ++i) {
         const uint4 v = src[i * 64];
@@ -152,9 +147,56 @@ __global__ __launch_bounds__(256) void reslice_kernel(const uint4 *__restrict__ 
             dw[un * T::UD + o.dw] |= t << (p + o.sh);
         });
     });
-    uint4 *dst = packed + tile * (R * 64) + lane;
 #pragma unroll
     for (int i = 0; i < R; ++i) dst[i * 64] = make_uint4(dw[4 * i], dw[4 * i + 1], dw[4 * i + 2], dw[4 * i + 3]);
+}
+
+template <int R>
+__global__ __launch_bounds__(256) void reslice_kernel(const uint4 *__restrict__ parent8, uint4 *__restrict__ packed,
+                                                      int64_t ntiles) {
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int64_t tile = tid >> 6;
+    if (tile >= ntiles) return;
+    reslice_tile<R>(parent8 + tile * (kC * 64) + lane, packed + tile * (R * 64) + lane);
+}
+
+// Several layers in one launch (small layers are launch-bound one by one): tiles of all jobs form one line,
+// a wave finds its job in the table that travels with the launch.
+struct ResliceJobs {
+    const uint4 *src[kResliceBatch];
+    uint4 *dst[kResliceBatch];
+    int64_t tile_end[kResliceBatch];  // running sum of tiles
+    int32_t r[kResliceBatch];
+    int32_t n;
+};
+__global__ __launch_bounds__(256) void reslice_many_kernel(const ResliceJobs jobs) {
+    const int lane = threadIdx.x & 63;
+    const int64_t tile = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    // the table is searched with compile-time indices only (a run-time index would move it to scratch memory)
+    const uint4 *src = nullptr;
+    uint4 *dst = nullptr;
+    int r = 0;
+    int64_t t = 0;
+#pragma unroll
+    for (int j = 0; j < kResliceBatch; ++j) {
+        const int64_t lo = j ? jobs.tile_end[j - 1] : 0;
+        if (j < jobs.n && tile >= lo && tile < jobs.tile_end[j]) {
+            src = jobs.src[j];
+            dst = jobs.dst[j];
+            r = jobs.r[j];
+            t = tile - lo;
+        }
+    }
+    if (!src) return;  // past the last tile
+    src += t * (kC * 64) + lane;
+    switch (r) {
+        case 2: reslice_tile<2>(src, dst + t * (2 * 64) + lane); break;
+        case 3: reslice_tile<3>(src, dst + t * (3 * 64) + lane); break;
+        case 4: reslice_tile<4>(src, dst + t * (4 * 64) + lane); break;
+        case 6: reslice_tile<6>(src, dst + t * (6 * 64) + lane); break;
+        default: reslice_tile<8>(src, dst + t * (8 * 64) + lane); break;
+    }
 }
 
 template <int R>
@@ -203,6 +245,7 @@ static hipError_t launch_pack_r(const uint8_t *S, int64_t N, int64_t K, uint4 *p
     const int G = (int)(K / kGroup);
     const int64_t ntiles = pad_rows(N) / kRowBlock * G;
     const int64_t blocks = (ntiles * 64 + 255) / 256;
+    if (blocks > (int64_t)0x7fffffff) return hipErrorInvalidValue;  // beyond one grid dimension
     (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
     hipLaunchKernelGGL((pack_kernel<R, SL>), dim3((unsigned)blocks), dim3(256), 0, s, S, packed, (int)N, K, G, ntiles);
     return hipGetLastError();
@@ -211,6 +254,7 @@ template <int R>
 static hipError_t launch_reslice_r(const uint4 *parent8, int64_t N, int64_t K, uint4 *packed, hipStream_t s) {
     const int64_t ntiles = pad_rows(N) / kRowBlock * (K / kGroup);
     const int64_t blocks = (ntiles * 64 + 255) / 256;
+    if (blocks > (int64_t)0x7fffffff) return hipErrorInvalidValue;  // beyond one grid dimension
     (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
     hipLaunchKernelGGL(reslice_kernel<R>, dim3((unsigned)blocks), dim3(256), 0, s, parent8, packed, ntiles);
     return hipGetLastError();
@@ -220,6 +264,7 @@ static hipError_t launch_unpack_r(const uint4 *packed, int64_t N, int64_t K, uin
     const int G = (int)(K / kGroup);
     const int64_t ntiles = pad_rows(N) / kRowBlock * G;
     const int64_t blocks = (ntiles * 64 + 255) / 256;
+    if (blocks > (int64_t)0x7fffffff) return hipErrorInvalidValue;  // beyond one grid dimension
     (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
     hipLaunchKernelGGL(unpack_kernel<R>, dim3((unsigned)blocks), dim3(256), 0, s, packed, S, (int)N, K, G, ntiles);
     return hipGetLastError();
@@ -244,6 +289,28 @@ hipError_t launch_slice_pack(const uint8_t *parent, int64_t N, int64_t K, int r,
         case 8: return launch_pack_r<8, true>(parent, N, K, packed, s);
     }
     return hipErrorInvalidValue;
+}
+hipError_t launch_reslice_many(const uint4 *const *src, uint4 *const *dst, const int64_t *N, const int64_t *K,
+                               const int *r, int n, hipStream_t s) {
+    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
+    for (int j0 = 0; j0 < n; j0 += kResliceBatch) {
+        ResliceJobs jobs{};
+        int64_t tiles = 0;
+        jobs.n = n - j0 < kResliceBatch ? n - j0 : kResliceBatch;
+        for (int j = 0; j < jobs.n; ++j) {
+            jobs.src[j] = src[j0 + j];
+            jobs.dst[j] = dst[j0 + j];
+            jobs.r[j] = r[j0 + j];
+            tiles += pad_rows(N[j0 + j]) / kRowBlock * (K[j0 + j] / kGroup);
+            jobs.tile_end[j] = tiles;
+        }
+        const int64_t blocks = (tiles * 64 + 255) / 256;
+        if (blocks > (int64_t)0x7fffffff) return hipErrorInvalidValue;  // beyond one grid dimension
+        hipLaunchKernelGGL(reslice_many_kernel, dim3((unsigned)blocks), dim3(256), 0, s, jobs);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 hipError_t launch_reslice(const uint4 *parent8, int64_t N, int64_t K, int r, uint4 *packed, hipStream_t s) {
     switch (r) {

@@ -43,6 +43,7 @@ static hipError_t launch_quant_mask(const float *W, int64_t ldw, int64_t N, int6
                                     uint8_t *Q, int64_t ldq, bool vec4, hipStream_t s) {
     const int64_t threads = vec4 ? N * (ncols / 4) : N * ncols;
     const int64_t blocks = (threads + 255) / 256;
+    if (blocks > (int64_t)0x7fffffff) return hipErrorInvalidValue;  // beyond one grid dimension
     (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
     if (vec4)
         hipLaunchKernelGGL((quant_kernel<MASK, 4>), dim3((unsigned)blocks), dim3(256), 0, s, W, ldw, N, ncols, col0, scales,

@@ -916,3 +916,31 @@ def test_matgptq_column_loop_many_rows_sampled(N, K):
         q = mq.mq_matgptq_quantize(dev(W.copy()), dev(U), dev(s), dev(z), widths, lam).cpu().numpy()
         ref, _ = oracle.matgptq_quantize(W[rows], U, s[rows], z[rows], C, widths, lam, 128, 128, np.float32)
         assert np.array_equal(q[rows], ref), (N, K, widths)
+
+
+def test_reslice_many_layers_in_few_launches_bit_exact():
+    # 37 layers of mixed shapes and widths (three launches of 16, 16 and 5 jobs), each checked against the
+    # independent packer applied to the oracle's slice; guard bytes around every output
+    rng = np.random.default_rng(97)
+    shapes = [(64, 128), (130, 384), (1, 128), (200, 1280), (448, 256), (63, 512)]
+    jobs, refs, bufs = [], [], []
+    for i in range(37):
+        N, K = shapes[i % len(shapes)]
+        r = WIDTHS[int(rng.integers(0, 5))]
+        parent = rng.integers(0, 256, (N, K), dtype=np.uint8)
+        ref = pack_ref(oracle.slice_codes(parent, C, r), r)
+        buf = torch.full((ref.size + 32,), 0xAB, dtype=torch.uint8, device=DEV)
+        jobs.append(dict(packed_parent=mq.mq_pack(dev(parent), C, 8), N=N, K=K, r=r, out=buf[16:16 + ref.size]))
+        refs.append(ref)
+        bufs.append(buf)
+    mq.mq_reslice_many(jobs)
+    torch.cuda.synchronize()
+    for i, (buf, ref) in enumerate(zip(bufs, refs)):
+        o = buf.cpu().numpy()
+        assert np.array_equal(o[16:16 + ref.size], ref), i
+        assert (o[:16] == 0xAB).all() and (o[16 + ref.size:] == 0xAB).all(), i
+    bad = [dict(jobs[0]), dict(jobs[1], r=5)]
+    with pytest.raises(mq.MqError):
+        mq.mq_reslice_many(bad)
+    with pytest.raises(mq.MqError):
+        mq.mq_reslice_many([dict(jobs[0], out=jobs[0]["packed_parent"][:jobs[0]["out"].numel()])])   # in place

@@ -120,6 +120,34 @@ def test_reslice_validation():
     assert L.mq_reslice(FAKE + 4096, 64, 128, 8, 4, FAKE + 16, big, None) == _st("MQ_ERR_UNSUPPORTED")
 
 
+def test_reslice_many_validation():
+    # every call below fails validation: nothing is ever launched with these fake pointers
+    L = mq.lib()
+    jobs = (mq.MqResliceJob * 2)()
+    jobs[0] = mq.MqResliceJob(FAKE, FAKE + (1 << 20), 1 << 30, 64, 128, 4, 0)
+    jobs[1] = mq.MqResliceJob(FAKE, FAKE + (2 << 20), 1 << 30, 64, 128, 3, 0)
+    p = ctypes.cast(jobs, ctypes.c_void_p)
+    assert L.mq_reslice_many(None, 2, 8, None) == _st("MQ_ERR_NULL")
+    assert L.mq_reslice_many(p, 0, 8, None) == _st("MQ_ERR_BAD_SHAPE")
+    assert L.mq_reslice_many(p, 2, 7, None) == _st("MQ_ERR_BAD_R")
+    jobs[1].r = 5
+    assert L.mq_reslice_many(p, 2, 8, None) == _st("MQ_ERR_BAD_R")
+    jobs[1].r = 3
+    jobs[1].packed = None
+    assert L.mq_reslice_many(p, 2, 8, None) == _st("MQ_ERR_NULL")
+    jobs[1].packed = FAKE + (2 << 20) + 8
+    assert L.mq_reslice_many(p, 2, 8, None) == _st("MQ_ERR_ALIGN")
+    jobs[1].packed = FAKE + (2 << 20)
+    jobs[1].packed_bytes = 100
+    assert L.mq_reslice_many(p, 2, 8, None) == _st("MQ_ERR_BUF_TOO_SMALL")
+    jobs[1].packed_bytes = 1 << 30
+    jobs[1].K = 100
+    assert L.mq_reslice_many(p, 2, 8, None) == _st("MQ_ERR_BAD_GROUP")
+    jobs[1].K = 128
+    jobs[1].packed = FAKE + 4096                    # inside its own parent
+    assert L.mq_reslice_many(p, 2, 8, None) == _st("MQ_ERR_UNSUPPORTED")
+
+
 def test_linear_from_parent_validation():
     # every call below fails validation: nothing is ever launched with these fake pointers
     L = mq.lib()
