@@ -148,9 +148,13 @@ template <int R> struct GemmCtx {
             w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
         }
     }
-    // activations of group g of this chunk: NXL coalesced 16-byte loads (past the end of the buffer -> 0)
+    // activations of group g of this chunk: NXL coalesced 16-byte loads (past the end of the buffer -> 0).
+    // A lane copies the 16 bytes of batch column lane % 16 of four MFMA blocks; columns beyond M hold zeros,
+    // so their lanes read out of range instead (0 comes back and no memory is touched: at M = 8 half the
+    // activation traffic, which is as large as a 4-bit weight tile, is never requested).
     __device__ __forceinline__ void load_x(u32x4 (&xb)[NXL], int g) const {
-        const uint32_t off = (uint32_t)(c * L.G + g) * (MF::NMF * 256u) + (uint32_t)lane * 16u;
+        const bool live = c * kChunkCols + (lane & 15) < L.M;
+        const uint32_t off = live ? (uint32_t)(c * L.G + g) * (MF::NMF * 256u) + (uint32_t)lane * 16u : 0x80000000u;
 #pragma unroll
         for (int i = 0; i < NXL; ++i) xb[i] = __builtin_amdgcn_raw_buffer_load_b128(xt, off + i * 1024, 0, 0);
     }
