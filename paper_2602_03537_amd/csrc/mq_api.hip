@@ -88,9 +88,10 @@ LayerDesc make_desc(const mq_layer &l, int64_t M, uint64_t cost_start, int cnt_o
         d.rs = l.r;
         d.cost = tile_cost(kC);
     }
-    if (use_wide(M)) {  // scheduled in super-tiles of four row blocks; the matrix-core time of a tile grows with the chunks
+    if (use_mfma(M) && !use_wide(M)) d.cost = mfma_tile_cost(l.r);
+    if (use_wide(M)) {  // scheduled in super-tiles of four row blocks
         d.RB = (d.RB + 3) / 4;
-        d.cost = tile_cost(l.r) + 60 * wide_chunks_per_pass(M);
+        d.cost = wide_tile_cost(l.r, wide_chunks_per_pass(M));
     }
     d.cnt_off = cnt_off;
     d.M = (int32_t)M;

@@ -92,6 +92,30 @@ inline int mfma_per_tile(int r) {
 // for r = 2, 3, 4, 6, 8), so equal shares of a mixed stack are equal work as far as a static model can tell.
 inline int tile_cost(int r) { return 10 * (4 * r + 2); }
 
+// Narrow MFMA path (kValuMaxM < M <= kNarrowMaxM): a tile's time there is set by instruction issue more than by its
+// bytes, so the measured per-tile times of uniform stacks are the costs (M = 8, 12 Llama-3-70B blocks: 1.11, 1.24,
+// 1.24, 1.61, 1.87 ms for r = 2, 3, 4, 6, 8).  With the byte-proportional costs a 2-bit share ran 1.6 times as long as
+// an 8-bit share of a mixed stack.
+inline int mfma_tile_cost(int r) {
+    switch (r) {
+        case 2: return 111;
+        case 3: return 124;
+        case 4: return 124;
+        case 6: return 161;
+        default: return 187;
+    }
+}
+
+// Wide MFMA path: cost of a super-tile (256 rows x one group) per pass with C chunks of 32 columns, again the measured
+// times of uniform stacks (12 Llama-3-70B blocks at M = 32, 64, 96, 128; units of 10 us).  The matrix-core work grows
+// with C, the unpacking with r; bytes matter least.
+inline int wide_tile_cost(int r, int C) {
+    static const int t[4][5] = {{146, 160, 164, 191, 213}, {194, 204, 212, 247, 272},
+                                {239, 252, 262, 306, 323}, {293, 308, 318, 358, 377}};
+    const int ri = r == 2 ? 0 : r == 3 ? 1 : r == 4 ? 2 : r == 6 ? 3 : 4;
+    return t[(C < 1 ? 1 : C > 4 ? 4 : C) - 1][ri];
+}
+
 inline int64_t pad_rows(int64_t N) { return (N + kRowBlock - 1) / kRowBlock * kRowBlock; }
 
 // launchers (mq_pack.hip / mq_linear.hip); each returns the hipError of the launch
