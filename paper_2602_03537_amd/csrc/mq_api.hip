@@ -82,11 +82,11 @@ LayerDesc make_desc(const mq_layer &l, int64_t M, uint64_t cost_start, int cnt_o
     d.G = (int32_t)(l.K / kGroup);
     d.RB = (int32_t)(pad_rows(l.N) / kRowBlock);
     d.r = l.r;
-    d.cost = tile_cost(l.r);
+    d.cost = use_mfma(M) ? tile_cost(l.r) : valu_tile_cost(l.r, (int)M);
     if (l.from_parent) {  // the tiles are those of the 8-bit parent; Eq. 1 to l.r bits happens in registers
         d.r = kC;
         d.rs = l.r;
-        d.cost = tile_cost(kC);
+        d.cost = valu_tile_cost(kC, (int)M);
     }
     if (use_mfma(M) && !use_wide(M)) d.cost = mfma_tile_cost(l.r);
     if (use_wide(M)) {  // scheduled in super-tiles of four row blocks

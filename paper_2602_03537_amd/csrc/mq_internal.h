@@ -91,6 +91,15 @@ inline int mfma_per_tile(int r) {
 // (4r + 2 lines).  Measured times of uniform stacks per tile are within 2 % of this (102 : 139 : 180 : 258 : 340
 // for r = 2, 3, 4, 6, 8), so equal shares of a mixed stack are equal work as far as a static model can tell.
 inline int tile_cost(int r) { return 10 * (4 * r + 2); }
+// Vector-ALU path at M = 2, 3, 4: with M accumulators per lane the kernel is bound by the vector ALUs at the narrow
+// widths, so a tile's time is much flatter than its bytes; the costs are the measured times of uniform stacks
+// (12 Llama-3-70B blocks, units of 10 us).  M = 1 keeps the byte-proportional cost above.
+inline int valu_tile_cost(int r, int M) {
+    static const int t[3][5] = {{89, 96, 98, 138, 176}, {109, 118, 117, 148, 178}, {134, 143, 138, 177, 187}};
+    if (M <= 1) return tile_cost(r);
+    const int ri = r == 2 ? 0 : r == 3 ? 1 : r == 4 ? 2 : r == 6 ? 3 : 4;
+    return t[(M > 4 ? 4 : M) - 2][ri];
+}
 
 // Narrow MFMA path (kValuMaxM < M <= kNarrowMaxM): a tile's time there is set by instruction issue more than by its
 // bytes, so the measured per-tile times of uniform stacks are the costs (M = 8, 12 Llama-3-70B blocks: 1.11, 1.24,
