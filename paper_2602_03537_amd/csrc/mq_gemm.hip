@@ -158,7 +158,9 @@ template <int R> struct GemmCtx {
 #pragma unroll
         for (int i = 0; i < NXL; ++i) xb[i] = __builtin_amdgcn_raw_buffer_load_b128(xt, off + i * 1024, 0, 0);
     }
+    // (lanes that copy a batch column beyond M have nothing to store: nobody reads those bytes)
     __device__ __forceinline__ void store_x(const u32x4 (&xb)[NXL], int stage) const {
+        if (c * kChunkCols + (lane & 15) >= L.M) return;
         u32x4 *dst = reinterpret_cast<u32x4 *>(lds + stage * kStageBytes) + lane;
 #pragma unroll
         for (int i = 0; i < NXL; ++i) dst[i * 64] = xb[i];
@@ -252,7 +254,10 @@ __device__ __forceinline__ void run_gemm_units(const LayerDesc &L, const StackPa
     using Ctx = GemmCtx<R>;
     constexpr int D = GemmDepth<R>::value, NB = D + 1;
     const uint32_t xt_bytes = (uint32_t)L.CB * L.G * MF::NMF * 256u;
-    const Ctx cx{L, lane_map(lane), lane, c,
+    LaneMap lmap = lane_map(lane);
+    // a lane whose output column lies beyond M supplies zeros as B: it reads the 16 zero bytes instead of its stage
+    lmap.b_live = lmap.b_live && c * kChunkCols + lmap.col < L.M;
+    const Ctx cx{L, lmap, lane, c,
                  __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(L.xt), 0, (int)xt_bytes, 0x00020000), lds_wave,
                  lds_zero};
     const LaneMap &lm = cx.lm;
