@@ -294,7 +294,7 @@ def bench_mixed_stack(args, mq, synth, torch, np, dev):
                      ms, f"{'Llama-3-70B' if big else 'Llama-2-7B'}-shaped stack, {n_blocks} blocks ({len(layers)} linears), "
                      f"M={M}, per-layer r from {{2,3,4,6,8}} by seed, parameter-weighted mean {mean:.3f} bits",
                      {"M": M, "mean_bits": round(mean, 4), "algorithmic_GB_per_step": round(nbytes / 1e9, 3)})
-    kernel = ("mq::stack_kernel<%d, 1, false>" % M if M <= 4 else "mq::gemm_stack_kernel" if M <= 16
+    kernel = ("mq::stack_kernel<%d, 1, false>" % M if M <= 3 else "mq::gemm_stack_kernel" if M <= 16
               else "mq::wide_stack_kernel")
     ach = nbytes / float(np.mean(us)) / 1e3
     out["stack_us_median"] = round(float(np.median(us)), 1)

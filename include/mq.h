@@ -261,7 +261,11 @@ typedef struct {
     int32_t reserved;    /* 0 */
 } mq_layer;
 
-/* Bytes of plan workspace for a stack of these layers (host arithmetic; 0 on
+/* Kernels by batch: as mq_linear, except that a stack of packed layers already runs on the matrix
+ * cores at M = 4 (scales_t / zeros_t 8-byte aligned from M = 4 on for a stack); stacks computed
+ * from the parent stay on the vector ALUs (M <= 4).
+ *
+ * Bytes of plan workspace for a stack of these layers (host arithmetic; 0 on
  * invalid arguments).  layers: host. */
 size_t mq_stack_workspace_bytes(const mq_layer *layers, int n_layers, int64_t M);
 

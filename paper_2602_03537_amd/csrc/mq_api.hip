@@ -27,6 +27,11 @@ mq_status check_shape(int64_t N, int64_t K, int group) {
 
 size_t counter_bytes(int64_t row_blocks) { return align_up((size_t)row_blocks * 4, kCounterBytesAlign); }
 bool use_mfma(int64_t M) { return M > kValuMaxM; }
+// A stack of packed layers at M = kValuMaxM runs on the matrix cores: measured on uniform stacks, four rows on the
+// vector ALUs take longer than five on the matrix cores at every width (1.34 against 1.02 ms at r = 2, 12 Llama-3-70B
+// blocks).  Single calls keep the vector-ALU kernels (their low-latency shape wins on one layer), and so do stacks
+// computed from the parent.  The "path batch" stands in for M wherever sizes and kernels are chosen.
+int64_t stack_path_m(int64_t M, bool from_parent) { return !from_parent && M == kValuMaxM ? M + 1 : M; }
 // column blocks the schedule sees: 1 (vector ALUs), 16-column chunks (narrow MFMA), passes (wide MFMA)
 int64_t chunks(int64_t M) {
     return use_wide(M) ? wide_passes(M) : use_mfma(M) ? (M + kChunkCols - 1) / kChunkCols : 1;
@@ -67,7 +72,8 @@ mq_status layer_status(const mq_layer &l, int64_t M) {
 }
 
 // xt / xsum: where the MFMA path keeps this layer's prepared activations (nullptr on the ALU path)
-LayerDesc make_desc(const mq_layer &l, int64_t M, uint64_t cost_start, int cnt_off, int job_start, void *xt,
+// Mp: the path batch (== M except for stacks at M = kValuMaxM, see stack_path_m)
+LayerDesc make_desc(const mq_layer &l, int64_t M, int64_t Mp, uint64_t cost_start, int cnt_off, int job_start, void *xt,
                     void *xsum) {
     LayerDesc d{};
     d.Wp = static_cast<const uint4 *>(l.packed_W);
@@ -82,20 +88,20 @@ LayerDesc make_desc(const mq_layer &l, int64_t M, uint64_t cost_start, int cnt_o
     d.G = (int32_t)(l.K / kGroup);
     d.RB = (int32_t)(pad_rows(l.N) / kRowBlock);
     d.r = l.r;
-    d.cost = use_mfma(M) ? tile_cost(l.r) : valu_tile_cost(l.r, (int)M);
+    d.cost = use_mfma(Mp) ? tile_cost(l.r) : valu_tile_cost(l.r, (int)M);
     if (l.from_parent) {  // the tiles are those of the 8-bit parent; Eq. 1 to l.r bits happens in registers
         d.r = kC;
         d.rs = l.r;
         d.cost = valu_tile_cost(kC, (int)M);
     }
-    if (use_mfma(M) && !use_wide(M)) d.cost = mfma_tile_cost(l.r);
-    if (use_wide(M)) {  // scheduled in super-tiles of four row blocks
+    if (use_mfma(Mp) && !use_wide(Mp)) d.cost = mfma_tile_cost(l.r);
+    if (use_wide(Mp)) {  // scheduled in super-tiles of four row blocks
         d.RB = (d.RB + 3) / 4;
-        d.cost = wide_tile_cost(l.r, wide_chunks_per_pass(M));
+        d.cost = wide_tile_cost(l.r, wide_chunks_per_pass(Mp));
     }
     d.cnt_off = cnt_off;
     d.M = (int32_t)M;
-    d.CB = (int32_t)chunks(M);
+    d.CB = (int32_t)chunks(Mp);
     d.job_start = job_start;
     d.cost_start = cost_start;
     return d;
@@ -107,9 +113,9 @@ struct PlanHeader {
     uint64_t cost_total;
     int32_t n_layers, M, max_cost, n_jobs;
     uint64_t table_off, cnt_off, part_off, total_bytes;
-    int32_t from_parent, reserved;
+    int32_t from_parent, path_M;
 };
-constexpr uint64_t kPlanMagic = 0x4d51504c414e3034ull;  // "MQPLAN04"
+constexpr uint64_t kPlanMagic = 0x4d51504c414e3035ull;  // "MQPLAN05"
 
 // Host-side copies of the plan headers, keyed by device address, so that running
 // a stack needs no read-back.  mq_stack_plan overwrites the entry of its address.
@@ -150,7 +156,7 @@ mq_status run_single(const mq_layer &l, int64_t M, void *ws, size_t ws_bytes, mq
     StackParams p{};
     p.table = nullptr;
     p.n_layers = 1;
-    p.single = make_desc(l, M, 0, 0, 0, use_mfma(M) ? act : nullptr, use_mfma(M) ? act + xt_bytes(M, l.K, l.r) : nullptr);
+    p.single = make_desc(l, M, M, 0, 0, 0, use_mfma(M) ? act : nullptr, use_mfma(M) ? act + xt_bytes(M, l.K, l.r) : nullptr);
     p.cost_total = (uint64_t)p.single.CB * p.single.RB * p.single.G * p.single.cost;
     p.cnt = reinterpret_cast<int32_t *>(base);
     p.part = reinterpret_cast<float *>(base + cnt_b);
@@ -390,15 +396,17 @@ size_t mq_stack_workspace_bytes(const mq_layer *layers, int n_layers, int64_t M)
     if (!layers || n_layers < 1 || n_layers > (1 << 20) || M < 1 || M > MQ_MAX_M) return 0;
     for (int i = 0; i < n_layers; ++i)
         if (!valid_pack_r(layers[i].r) || check_shape(layers[i].N, layers[i].K, layers[i].group) != MQ_OK) return 0;
-    return plan_layout(layers, n_layers, M).total;
+    return plan_layout(layers, n_layers, stack_path_m(M, layers[0].from_parent != 0)).total;
 }
 
 mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *plan, size_t plan_bytes,
                         mq_stream stream) {
     if (!layers || !plan) return MQ_ERR_NULL;
     if (n_layers < 1 || n_layers > (1 << 20)) return MQ_ERR_BAD_SHAPE;
+    if (M < 1 || M > MQ_MAX_M) return MQ_ERR_BAD_SHAPE;
+    const int64_t Mp = stack_path_m(M, layers[0].from_parent != 0);
     for (int i = 0; i < n_layers; ++i) {
-        if (mq_status st = layer_status(layers[i], M)) return st;
+        if (mq_status st = layer_status(layers[i], Mp)) return st;
         if (layers[i].from_parent != layers[0].from_parent) return MQ_ERR_UNSUPPORTED;  // one kernel variant per launch
     }
     if (!aligned(plan, 256)) return MQ_ERR_ALIGN;
@@ -406,7 +414,7 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
     if (need == 0) return MQ_ERR_BAD_SHAPE;
     if (plan_bytes < need) return MQ_ERR_BUF_TOO_SMALL;
 
-    const PlanLayout pl = plan_layout(layers, n_layers, M);
+    const PlanLayout pl = plan_layout(layers, n_layers, Mp);
     char *base_dev = static_cast<char *>(plan);
     int64_t counters = 0, jobs = 0;
     uint64_t cost = 0;
@@ -414,13 +422,13 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
     size_t act = pl.act_off;
     std::vector<LayerDesc> table((size_t)n_layers);
     for (int i = 0; i < n_layers; ++i) {
-        const size_t xb = xt_bytes(M, layers[i].K, layers[i].r), sb = xsum_bytes(M, layers[i].K);
-        table[i] = make_desc(layers[i], M, cost, (int)counters, (int)jobs, xb ? base_dev + act : nullptr,
+        const size_t xb = xt_bytes(Mp, layers[i].K, layers[i].r), sb = xsum_bytes(Mp, layers[i].K);
+        table[i] = make_desc(layers[i], M, Mp, cost, (int)counters, (int)jobs, xb ? base_dev + act : nullptr,
                              xb ? base_dev + act + xb : nullptr);
         act += xb + sb;
         cost += (uint64_t)table[i].CB * table[i].RB * table[i].G * table[i].cost;
-        counters += counters_of(M, layers[i].N);
-        jobs += (int64_t)(use_wide(M) ? wide_chunks_padded(M) : table[i].CB) * table[i].G;
+        counters += counters_of(Mp, layers[i].N);
+        jobs += (int64_t)(use_wide(Mp) ? wide_chunks_padded(Mp) : table[i].CB) * table[i].G;
         if (table[i].cost > max_cost) max_cost = table[i].cost;
     }
     if (counters > INT32_MAX || jobs > INT32_MAX) return MQ_ERR_BAD_SHAPE;
@@ -436,6 +444,7 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
     h.part_off = pl.part_off;
     h.total_bytes = pl.total;
     h.from_parent = layers[0].from_parent;
+    h.path_M = (int32_t)Mp;
 
     hipStream_t s = (hipStream_t)stream;
     char *base = static_cast<char *>(plan);
@@ -477,11 +486,11 @@ mq_status mq_linear_stack(void *plan, mq_stream stream) {
     p.cnt = reinterpret_cast<int32_t *>(base + h.cnt_off);
     p.part = reinterpret_cast<float *>(base + h.part_off);
     p.M = h.M;
-    p.slot_floats = slot_floats(h.M);
+    p.slot_floats = slot_floats(h.path_M);
     p.n_jobs = h.n_jobs;
-    const hipError_t e = use_wide(h.M)   ? launch_stack_wide(p, h.max_cost, (hipStream_t)stream)
-                         : use_mfma(h.M) ? launch_stack_mfma(p, h.max_cost, (hipStream_t)stream)
-                                         : launch_stack(p, h.max_cost, h.from_parent != 0, (hipStream_t)stream);
+    const hipError_t e = use_wide(h.path_M)   ? launch_stack_wide(p, h.max_cost, (hipStream_t)stream)
+                         : use_mfma(h.path_M) ? launch_stack_mfma(p, h.max_cost, (hipStream_t)stream)
+                                              : launch_stack(p, h.max_cost, h.from_parent != 0, (hipStream_t)stream);
     return e == hipSuccess ? MQ_OK : MQ_ERR_HIP;
 }
 

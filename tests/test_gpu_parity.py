@@ -435,7 +435,7 @@ def _stack(shapes_r, M=1, seed=0):  # noqa: E302
     return host, layers
 
 
-@pytest.mark.parametrize("M", [1, 2])
+@pytest.mark.parametrize("M", [1, 2, 3, 4])
 def test_stack_mixed_widths_matches_oracle(M):
     shapes_r = [(256, 512, 2), (64, 128, 8), (200, 1280, 3), (512, 256, 6), (130, 384, 4), (1024, 1024, 3),
                 (63, 128, 2), (320, 640, 8)]
