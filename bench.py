@@ -32,7 +32,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of mq::stack_kernel<1, 1, false> on the default workload (mean over the five widths),
 # from the two rocprofv3 --pmc runs summarised in profiles/stack_kernel_llama2_7b_m1_hbm_traffic.txt
 # (FETCH_SIZE scaled by 1.9987, WRITE_SIZE by 1.0, both calibrated on a 45 MB copy in the same run).
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 3936921406
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 3937038032
 WIDTHS = (2, 3, 4, 6, 8)
 
 

@@ -88,7 +88,7 @@ LayerDesc make_desc(const mq_layer &l, int64_t M, int64_t Mp, uint64_t cost_star
     d.G = (int32_t)(l.K / kGroup);
     d.RB = (int32_t)(pad_rows(l.N) / kRowBlock);
     d.r = l.r;
-    d.cost = use_mfma(Mp) ? tile_cost(l.r) : valu_tile_cost(l.r, (int)M);
+    d.cost = valu_tile_cost(l.r, (int)M);  // replaced below on the MFMA paths
     if (l.from_parent) {  // the tiles are those of the 8-bit parent; Eq. 1 to l.r bits happens in registers
         d.r = kC;
         d.rs = l.r;

@@ -87,18 +87,16 @@ inline int mfma_per_tile(int r) {
     }
 }
 
-// Schedule cost of a tile, in tenths of a 256-byte line: weights + scales, zeros and activations
-// (4r + 2 lines).  Measured times of uniform stacks per tile are within 2 % of this (102 : 139 : 180 : 258 : 340
-// for r = 2, 3, 4, 6, 8), so equal shares of a mixed stack are equal work as far as a static model can tell.
-inline int tile_cost(int r) { return 10 * (4 * r + 2); }
-// Vector-ALU path at M = 2, 3, 4: with M accumulators per lane the kernel is bound by the vector ALUs at the narrow
-// widths, so a tile's time is much flatter than its bytes; the costs are the measured times of uniform stacks
-// (12 Llama-3-70B blocks, units of 10 us).  M = 1 keeps the byte-proportional cost above.
+// Schedule cost of a tile on the vector-ALU path: measured times of uniform stacks (12 Llama-3-70B blocks, units of
+// 10 us) per batch M = 1..4.  At M = 1 the kernel is HBM-bound and the cost close to a tile's bytes (4r + 2 lines of
+// 256 bytes: 100 : 140 : 180 : 260 : 340), but the narrow widths run a little below the HBM rate of the wide ones, and
+// mixed stacks are 1.6-1.8 % faster with the measured ratios than with the byte-proportional ones.  From M = 2 on the M
+// accumulators per lane make the narrow widths ALU-bound and the cost much flatter than the bytes.
 inline int valu_tile_cost(int r, int M) {
-    static const int t[3][5] = {{89, 96, 98, 138, 176}, {109, 118, 117, 148, 178}, {134, 143, 138, 177, 187}};
-    if (M <= 1) return tile_cost(r);
+    static const int t[4][5] = {{100, 122, 155, 222, 290}, {89, 96, 98, 138, 176}, {109, 118, 117, 148, 178},
+                                {134, 143, 138, 177, 187}};
     const int ri = r == 2 ? 0 : r == 3 ? 1 : r == 4 ? 2 : r == 6 ? 3 : 4;
-    return t[(M > 4 ? 4 : M) - 2][ri];
+    return t[(M < 1 ? 1 : M > 4 ? 4 : M) - 1][ri];
 }
 
 // Narrow MFMA path (kValuMaxM < M <= kNarrowMaxM): a tile's time there is set by instruction issue more than by its
