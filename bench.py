@@ -32,7 +32,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of mq::stack_kernel<1, 1, false> on the default workload (mean over the five widths),
 # from the two rocprofv3 --pmc runs summarised in profiles/stack_kernel_llama2_7b_m1_hbm_traffic.txt
 # (FETCH_SIZE scaled by 1.9987, WRITE_SIZE by 1.0, both calibrated on a 45 MB copy in the same run).
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 3937038032
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 3936919163
 WIDTHS = (2, 3, 4, 6, 8)
 
 
@@ -47,13 +47,15 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--layers", type=int, default=32, help="decoder blocks in the stack")
-    ap.add_argument("--workload", default="every-r", choices=["every-r", "mixed-7b", "mixed-70b", "mlp-70b", "parent-7b", "parent-70b", "quant-7b", "gptq-7b"],
+    ap.add_argument("--workload", default="every-r", choices=["every-r", "mixed-7b", "mixed-70b", "mlp-70b", "parent-7b", "parent-70b", "quant-7b", "gptq-7b",
+                             "decode-7b"],
                     help="every-r: Llama-2-7B linears at each r (default, the headline); mixed-7b / mixed-70b: one "
                          "mixed-width stack (mean 3.5 / 4 bits); mlp-70b: batched regime on the Llama-3-70B MLP shapes; "
                          "parent-7b / parent-70b: run-time re-slicing of a resident 8-bit parent (mq_reslice, "
                          "mq_slice_pack) and the stack computed straight from the parent; quant-7b: Algorithm 1 (cross-bit-width "
                          "choice of the parent code) on the Llama-2-7B layer shapes; gptq-7b: the MatGPTQ column loop "
-                         "(Algorithm 2) on those shapes")
+                         "(Algorithm 2) on those shapes; decode-7b: shared-input fusions of a decoder block (q/k/v and gate/up "
+                         "as one launch each) against one launch per linear")
     ap.add_argument("--batch", type=int, default=1, help="M for the mixed-* workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-single", action="store_true", help="skip the per-call mq_linear table")
@@ -81,6 +83,8 @@ def main() -> int:
         return bench_quant(args, mq, synth, torch, np, dev)
     if args.workload == "gptq-7b":
         return bench_gptq(args, mq, synth, torch, np, dev)
+    if args.workload == "decode-7b":
+        return bench_decode_fusions(args, mq, synth, torch, np, dev)
     block = synth.LLAMA2_7B_BLOCK
     M = 1
 
@@ -478,6 +482,90 @@ def bench_quant(args, mq, synth, torch, np, dev):
                "sample": f"numpy oracle (oracle/mq_quant_oracle.py, binary32) on {rows} rows of a 4096-column layer, "
                          f"R = {{3,4,8}}, repeated for {ct:.1f} s", "seconds": round(ct, 2)}
     out["cpu_baseline"] = cpu
+    print(json.dumps(out))
+    return 0
+
+
+def bench_decode_fusions(args, mq, synth, torch, np, dev):
+    """Decode-shaped fusions: the linears of a decoder block that share their input (q/k/v; gate/up) as ONE
+    mq_linear_stack launch each, against one mq_linear launch per linear.  Llama-2-7B shapes, per-layer widths by
+    seed (mean 3.5 bits), every block its own weights (cold), replayed from a HIP graph."""
+    M = args.batch
+    block = synth.LLAMA2_7B_BLOCK
+    n_blocks = args.layers
+    shapes = synth.stack_shapes(block, n_blocks)
+    widths, mean = synth.draw_bitwidths([N * K for (_, _, N, K) in shapes], 3.5, seed=0)
+    proto = {}
+    blocks, nbytes = [], 0.0
+    it = iter(widths)
+    for b in range(n_blocks):
+        lays = {}
+        xh = torch.randn((M, 4096), device=dev, dtype=torch.float32).to(torch.float16)       # hidden state
+        xa = torch.randn((M, 4096), device=dev, dtype=torch.float32).to(torch.float16)       # attention output
+        xm = torch.randn((M, 11008), device=dev, dtype=torch.float32).to(torch.float16)      # MLP activation
+        for (name, N, K) in block:
+            r = int(next(it))
+            if (N, K, r) not in proto:
+                L = synth.make_layer_device(N, K, M, seed=6000 + len(proto), device=dev, want_x=False)
+                proto[(N, K, r)] = mq.prepare_layer(L["parent"], L["scales"], L["zeros"], r)
+            p = proto[(N, K, r)]
+            x = xm if K == 11008 else xa if name.startswith("o") else xh
+            lays[name] = dict(packed_W=p["packed_W"].clone(), scales_t=p["scales_t"].clone(), zeros_t=p["zeros_t"].clone(),
+                              N=N, K=K, r=r, x=x, y=torch.empty((M, N), dtype=torch.float16, device=dev))
+            nbytes += algo_bytes(N, K, r, M)
+        blocks.append(lays)
+    names = [n for (n, _, _) in block]
+    qkv, gu = names[0:3], names[4:6]
+    single = [n for n in names if n not in qkv + gu]
+    ws = mq.new_workspace(M, 11008, 11008, 8)
+    for lays in blocks:
+        lays["_qkv"] = mq.mq_stack_plan([lays[n] for n in qkv], M, device=dev)
+        lays["_gu"] = mq.mq_stack_plan([lays[n] for n in gu], M, device=dev)
+
+    def per_linear():
+        for lays in blocks:
+            for n in names:
+                L = lays[n]
+                mq.mq_linear(L["x"], L["packed_W"], L["scales_t"], L["zeros_t"], L["N"], L["K"], L["r"], 128, ws, y=L["y"])
+
+    def fused():
+        for lays in blocks:
+            mq.mq_linear_stack(lays["_qkv"])
+            L = lays[single[0]]
+            mq.mq_linear(L["x"], L["packed_W"], L["scales_t"], L["zeros_t"], L["N"], L["K"], L["r"], 128, ws, y=L["y"])
+            mq.mq_linear_stack(lays["_gu"])
+            L = lays[single[1]]
+            mq.mq_linear(L["x"], L["packed_W"], L["scales_t"], L["zeros_t"], L["N"], L["K"], L["r"], 128, ws, y=L["y"])
+
+    res = {}
+    for label, fn in (("one_launch_per_linear", per_linear), ("fused_qkv_and_gate_up", fused)):
+        fn()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        t = e0.elapsed_time(e1) * 1e-3 / args.steps
+        res[label] = {"us_per_block": round(t / n_blocks * 1e6, 2), "GBps": round(nbytes / t / 1e9, 1),
+                      "launches_per_block": 7 if label.startswith("one") else 4}
+        del g
+    t_f = res["fused_qkv_and_gate_up"]["us_per_block"] * n_blocks * 1e-6
+    out = _base_line("decoder-block linears with shared-input fusions, effective HBM GB/s", nbytes / t_f / 1e9, "GB/s", args,
+                     t_f * 1e3, f"Llama-2-7B decoder blocks x{n_blocks}, M={M}, per-layer r by seed (mean {mean:.3f} bits): "
+                     "q/k/v and gate/up as one mq_linear_stack launch each, o and down as mq_linear", {"M": M})
+    out["table"] = res
+    out["roofline"] = {"bound": "hbm", "kernel": "mq::stack_kernel<%d, 1, false> + mq::linear_rb_kernel" % M,
+                       "achieved": res["fused_qkv_and_gate_up"]["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                       "frac": round(res["fused_qkv_and_gate_up"]["GBps"] / HBM_PEAK_GBPS, 4), "avg_launch_us": None,
+                       "algorithmic_bytes_per_launch": None, "traffic": None}
+    out["cpu_baseline"] = None
     print(json.dumps(out))
     return 0
 

@@ -31,7 +31,17 @@ bool use_mfma(int64_t M) { return M > kValuMaxM; }
 // vector ALUs take longer than five on the matrix cores at every width (1.34 against 1.02 ms at r = 2, 12 Llama-3-70B
 // blocks).  Single calls keep the vector-ALU kernels (their low-latency shape wins on one layer), and so do stacks
 // computed from the parent.  The "path batch" stands in for M wherever sizes and kernels are chosen.
-int64_t stack_path_m(int64_t M, bool from_parent) { return !from_parent && M == kValuMaxM ? M + 1 : M; }
+// A small stack (the few linears of a decoder block that share their input) keeps the vector-ALU kernels in their
+// low-latency shape, as a single call does.
+int64_t stack_path_m(int64_t M, bool from_parent, bool small) {
+    return !from_parent && !small && M == kValuMaxM ? M + 1 : M;
+}
+bool small_stack(const mq_layer *layers, int n_layers, int64_t M) {
+    if (M > kValuMaxM || n_layers > 16) return false;
+    int64_t tiles = 0;
+    for (int i = 0; i < n_layers; ++i) tiles += pad_rows(layers[i].N) / kRowBlock * (layers[i].K / kGroup);
+    return tiles <= 12288;
+}
 // column blocks the schedule sees: 1 (vector ALUs), 16-column chunks (narrow MFMA), passes (wide MFMA)
 int64_t chunks(int64_t M) {
     return use_wide(M) ? wide_passes(M) : use_mfma(M) ? (M + kChunkCols - 1) / kChunkCols : 1;
@@ -114,8 +124,9 @@ struct PlanHeader {
     int32_t n_layers, M, max_cost, n_jobs;
     uint64_t table_off, cnt_off, part_off, total_bytes;
     int32_t from_parent, path_M;
+    int32_t ll_blocks, ll_waves;  // low-latency launch shape of a small stack, or 0
 };
-constexpr uint64_t kPlanMagic = 0x4d51504c414e3035ull;  // "MQPLAN05"
+constexpr uint64_t kPlanMagic = 0x4d51504c414e3036ull;  // "MQPLAN06"
 
 // Host-side copies of the plan headers, keyed by device address, so that running
 // a stack needs no read-back.  mq_stack_plan overwrites the entry of its address.
@@ -396,7 +407,7 @@ size_t mq_stack_workspace_bytes(const mq_layer *layers, int n_layers, int64_t M)
     if (!layers || n_layers < 1 || n_layers > (1 << 20) || M < 1 || M > MQ_MAX_M) return 0;
     for (int i = 0; i < n_layers; ++i)
         if (!valid_pack_r(layers[i].r) || check_shape(layers[i].N, layers[i].K, layers[i].group) != MQ_OK) return 0;
-    return plan_layout(layers, n_layers, stack_path_m(M, layers[0].from_parent != 0)).total;
+    return plan_layout(layers, n_layers, stack_path_m(M, layers[0].from_parent != 0, small_stack(layers, n_layers, M))).total;
 }
 
 mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *plan, size_t plan_bytes,
@@ -404,7 +415,7 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
     if (!layers || !plan) return MQ_ERR_NULL;
     if (n_layers < 1 || n_layers > (1 << 20)) return MQ_ERR_BAD_SHAPE;
     if (M < 1 || M > MQ_MAX_M) return MQ_ERR_BAD_SHAPE;
-    const int64_t Mp = stack_path_m(M, layers[0].from_parent != 0);
+    const int64_t Mp = stack_path_m(M, layers[0].from_parent != 0, small_stack(layers, n_layers, M));
     for (int i = 0; i < n_layers; ++i) {
         if (mq_status st = layer_status(layers[i], Mp)) return st;
         if (layers[i].from_parent != layers[0].from_parent) return MQ_ERR_UNSUPPORTED;  // one kernel variant per launch
@@ -445,6 +456,13 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
     h.total_bytes = pl.total;
     h.from_parent = layers[0].from_parent;
     h.path_M = (int32_t)Mp;
+    {
+        int nb = 0, nw = 0;
+        if (!use_mfma(Mp) && linear_rb_stack_shape(table.data(), n_layers, partial_bytes(Mp), &nb, &nw)) {
+            h.ll_blocks = nb;
+            h.ll_waves = nw;
+        }
+    }
 
     hipStream_t s = (hipStream_t)stream;
     char *base = static_cast<char *>(plan);
@@ -490,6 +508,8 @@ mq_status mq_linear_stack(void *plan, mq_stream stream) {
     p.n_jobs = h.n_jobs;
     const hipError_t e = use_wide(h.path_M)   ? launch_stack_wide(p, h.max_cost, (hipStream_t)stream)
                          : use_mfma(h.path_M) ? launch_stack_mfma(p, h.max_cost, (hipStream_t)stream)
+                         : h.ll_blocks        ? launch_linear_rb_stack(p, h.ll_blocks, h.ll_waves, h.from_parent != 0,
+                                                                       (hipStream_t)stream)
                                               : launch_stack(p, h.max_cost, h.from_parent != 0, (hipStream_t)stream);
     return e == hipSuccess ? MQ_OK : MQ_ERR_HIP;
 }

@@ -152,6 +152,10 @@ hipError_t launch_stack(StackParams p, int max_cost, bool from_parent, hipStream
 // Single layer, M <= kValuMaxM: one workgroup per (row block, K slice); see mq_linear.hip.
 bool linear_rb_fits(const LayerDesc &L, size_t part_bytes);
 hipError_t launch_linear_rb(const LayerDesc &L, float *part, int32_t *cnt, hipStream_t s);
+// The same shape for a small stack (M <= kValuMaxM): all layers' workgroups in one launch.  `table` is the host copy
+// of the descriptors; false = the stack is too big for it.
+bool linear_rb_stack_shape(const LayerDesc *table, int n_layers, size_t part_bytes, int *blocks, int *waves);
+hipError_t launch_linear_rb_stack(const StackParams &p, int blocks, int waves, bool from_parent, hipStream_t s);
 // MFMA path (M > kValuMaxM): activation prep kernel + persistent MFMA kernel.
 hipError_t launch_stack_mfma(StackParams p, int max_cost, hipStream_t s);
 // Wide MFMA path (M > kNarrowMaxM): activation prep kernel + persistent kernel, one workgroup per share.

@@ -224,14 +224,15 @@ template <int M, int XP, bool SL = false> __global__ __launch_bounds__(256) void
 // through LDS in wave order, and -- only if K is cut into KS > 1 slices -- hand over to the
 // last-arriving slice through KS slots (same deterministic protocol as the stack kernel, with
 // KS <= 8 contributors instead of up to G).
-template <int R, int M, int XP, bool SL = false>
-__global__ __launch_bounds__(1024) void linear_rb_kernel(const LayerDesc L, const int KS, float *part, int32_t *cnt) {
-    __shared__ float red[16][M][64];
-    __shared__ __attribute__((aligned(16))) uint32_t xlds_all[XP == kXLds ? 16 * M * 64 : 4];
+// Body shared by the single-layer kernel and the small-stack kernel below.  blk = index of this workgroup among the
+// layer's RB * KS workgroups, slot0 = index of the layer's first partial-sum slot, cnt = the layer's row-block counters.
+template <int R, int M, int XP, bool SL>
+__device__ __forceinline__ void linear_rb_body(const LayerDesc &L, const int KS, const int blk, const int slot0,
+                                               float *part, int32_t *cnt, float (*red)[M][64], uint32_t *xlds_all) {
     uint32_t *xlds = xlds_all + (XP == kXLds ? (threadIdx.x >> 6) * M * 64 : 0);
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6, W = blockDim.x >> 6;
-    const int rb = blockIdx.x / KS, ks = blockIdx.x - rb * KS;
+    const int rb = blk / KS, ks = blk - rb * KS;
     const int g_lo = (int)((int64_t)ks * L.G / KS), g_hi = (int)((int64_t)(ks + 1) * L.G / KS);
     float yacc[M];
 #pragma unroll
@@ -261,7 +262,7 @@ __global__ __launch_bounds__(1024) void linear_rb_kernel(const LayerDesc L, cons
     }
     const int row = rb * kRowBlock + lane;
     if (KS > 1) {
-        float MQ_GLOBAL *mine = gl(part + ((size_t)blockIdx.x * M) * 64 + lane);
+        float MQ_GLOBAL *mine = gl(part + ((size_t)(slot0 + blk) * M) * 64 + lane);
 #pragma unroll
         for (int m = 0; m < M; ++m) __hip_atomic_store(mine + m * 64, tot[m], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         // the write-through stores must have been acknowledged before the counter moves
@@ -272,7 +273,7 @@ __global__ __launch_bounds__(1024) void linear_rb_kernel(const LayerDesc L, cons
         old = __builtin_amdgcn_readfirstlane(old);
         if (old != KS - 1) return;
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-        const float MQ_GLOBAL *src = gl(part + ((size_t)rb * KS * M) * 64 + lane);
+        const float MQ_GLOBAL *src = gl(part + ((size_t)(slot0 + rb * KS) * M) * 64 + lane);
         float v[8][M];
 #pragma unroll
         for (int i = 0; i < 8; ++i)
@@ -294,10 +295,17 @@ __global__ __launch_bounds__(1024) void linear_rb_kernel(const LayerDesc L, cons
         if (row < L.N) gl(L.y)[(size_t)m * L.N + row] = (_Float16)tot[m];
 }
 
+template <int R, int M, int XP, bool SL = false>
+__global__ __launch_bounds__(1024) void linear_rb_kernel(const LayerDesc L, const int KS, float *part, int32_t *cnt) {
+    __shared__ float red[16][M][64];
+    __shared__ __attribute__((aligned(16))) uint32_t xlds_all[XP == kXLds ? 16 * M * 64 : 4];
+    linear_rb_body<R, M, XP, SL>(L, KS, (int)blockIdx.x, 0, part, cnt, red, xlds_all);
+}
+
 // Launch shape, from sweeps on Llama-2-7B / Llama-3-70B shapes (cold weights): enough K slices
 // that (a) there are >= 256 workgroups when there are few row blocks and (b) no wave owns more
 // than about two tiles; at most 8 slices, each at least 4 groups long.
-static int pick_k_slices(const LayerDesc &L) {
+__host__ __device__ static inline int pick_k_slices(const LayerDesc &L) {
     const int cover = L.RB >= 128 ? 1 : (256 + L.RB - 1) / L.RB;
     const int depth = (L.G + 31) / 32;
     int ks = cover > depth ? cover : depth;
@@ -339,6 +347,79 @@ hipError_t launch_linear_rb(const LayerDesc &L, float *part, int32_t *cnt, hipSt
         case 2: return launch_linear_rb_m<2>(L, part, cnt, s);
         case 3: return launch_linear_rb_m<3>(L, part, cnt, s);
         case 4: return launch_linear_rb_m<4>(L, part, cnt, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+// The same shape for a SMALL stack (the linears of a decoder block that share their input, say): the workgroups of all
+// layers in one launch; a workgroup finds its layer by walking the table (a handful of entries).
+template <int M, int XP, bool SL>
+__global__ __launch_bounds__(1024) void linear_rb_stack_kernel(const StackParams p) {
+    __shared__ float red[16][M][64];
+    __shared__ __attribute__((aligned(16))) uint32_t xlds_all[XP == kXLds ? 16 * M * 64 : 4];
+    int blk = (int)blockIdx.x, slot0 = 0, li = 0;
+    LayerDesc L = load_desc(p.table);
+    int KS = pick_k_slices(L);
+    while (blk >= L.RB * KS && li + 1 < p.n_layers) {  // the grid holds exactly sum(RB * KS) workgroups
+        blk -= L.RB * KS;
+        slot0 += L.RB * KS;
+        L = load_desc(p.table + ++li);
+        KS = pick_k_slices(L);
+    }
+    int32_t *cnt = p.cnt + L.cnt_off;
+    if constexpr (SL) {
+        linear_rb_body<8, M, XP, true>(L, KS, blk, slot0, p.part, cnt, red, xlds_all);
+    } else {
+        switch (L.r) {
+            case 2: linear_rb_body<2, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all); break;
+            case 3: linear_rb_body<3, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all); break;
+            case 4: linear_rb_body<4, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all); break;
+            case 6: linear_rb_body<6, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all); break;
+            default: linear_rb_body<8, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all); break;
+        }
+    }
+}
+
+static int rb_waves(const LayerDesc &L) {
+    const int KS = pick_k_slices(L);
+    const int per_block = (L.G + KS - 1) / KS;
+    return (per_block >= 24 || (KS == 1 && per_block >= 12)) ? 16 : per_block >= 6 ? 8 : 4;
+}
+
+// A stack is "small" when all its layers together still fit the low-latency shape (same bound as for one layer).
+// Returns the launch shape: workgroups = sum of RB * KS, waves per workgroup = the most any layer wants.
+bool linear_rb_stack_shape(const LayerDesc *table, int n_layers, size_t part_bytes, int *blocks, int *waves) {
+    if (n_layers > 16 || table[0].M > kValuMaxM) return false;
+    int64_t tiles = 0, slots = 0;
+    int nb = 0, W = 4;
+    for (int i = 0; i < n_layers; ++i) {
+        tiles += (int64_t)table[i].RB * table[i].G;
+        slots += (int64_t)table[i].RB * 8;
+        nb += table[i].RB * pick_k_slices(table[i]);
+        const int w = rb_waves(table[i]);
+        if (w > W) W = w;
+    }
+    if (tiles > 12288 || (size_t)slots * (size_t)table[0].M * 64 * sizeof(float) > part_bytes) return false;
+    *blocks = nb;
+    *waves = W;
+    return true;
+}
+
+template <int M> static hipError_t launch_linear_rb_stack_m(const StackParams &p, int blocks, int waves, bool from_parent,
+                                                            hipStream_t s) {
+    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
+    if (from_parent)
+        hipLaunchKernelGGL((linear_rb_stack_kernel<M, kXLds, true>), dim3((unsigned)blocks), dim3(64 * waves), 0, s, p);
+    else
+        hipLaunchKernelGGL((linear_rb_stack_kernel<M, kXLds, false>), dim3((unsigned)blocks), dim3(64 * waves), 0, s, p);
+    return hipGetLastError();
+}
+hipError_t launch_linear_rb_stack(const StackParams &p, int blocks, int waves, bool from_parent, hipStream_t s) {
+    switch (p.M) {
+        case 1: return launch_linear_rb_stack_m<1>(p, blocks, waves, from_parent, s);
+        case 2: return launch_linear_rb_stack_m<2>(p, blocks, waves, from_parent, s);
+        case 3: return launch_linear_rb_stack_m<3>(p, blocks, waves, from_parent, s);
+        case 4: return launch_linear_rb_stack_m<4>(p, blocks, waves, from_parent, s);
     }
     return hipErrorInvalidValue;
 }

@@ -944,3 +944,23 @@ def test_reslice_many_layers_in_few_launches_bit_exact():
         mq.mq_reslice_many(bad)
     with pytest.raises(mq.MqError):
         mq.mq_reslice_many([dict(jobs[0], out=jobs[0]["packed_parent"][:jobs[0]["out"].numel()])])   # in place
+
+
+@pytest.mark.parametrize("M", [1, 4, 8])
+def test_stack_shared_input_fusions_qkv_and_gate_up(M):
+    # decode-shaped fusions: the linears that read the same activations (q/k/v; gate/up) as one launch each
+    rng = np.random.default_rng([98, M])
+    x = synth.make_x(M, 512, [98, M])
+    xd = dev(x)
+    for shapes_r in ([(512, 512, 4), (128, 512, 2), (128, 512, 8)], [(1376, 512, 3), (1376, 512, 6)]):
+        host, layers = [], []
+        for i, (N, K, r) in enumerate(shapes_r):
+            L = synth.make_layer(N, K, M=M, seed=[98, M, i, N])
+            lay = mq.prepare_layer(dev(L["parent"]), dev(L["scales"]), dev(L["zeros"]), r)
+            lay.update(x=xd, y=torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV))    # one x for all
+            layers.append(lay)
+            host.append(dict(L, x=x, r=r))
+        mq.mq_linear_stack(mq.mq_stack_plan(layers, M))
+        torch.cuda.synchronize()
+        for i, (lay, ref) in enumerate(zip(layers, oracle.linear_stack(host, C, 128))):
+            check_y(lay["y"], ref, f"shared input M={M} layer {i}")
