@@ -263,7 +263,10 @@ typedef struct {
 
 /* Kernels by batch: as mq_linear, except that a stack of packed layers already runs on the matrix
  * cores at M = 4 (scales_t / zeros_t 8-byte aligned from M = 4 on for a stack); stacks computed
- * from the parent stay on the vector ALUs (M <= 4).
+ * from the parent stay on the vector ALUs (M <= 4).  A small stack (at most 16 layers and 12288
+ * tiles of 64 rows x 128 columns in all, M <= 4: the q/k/v or gate/up linears of a decoder block,
+ * which may share one x) is launched for latency, one workgroup per (layer, row block, K slice);
+ * larger ones as one persistent stream-K launch.
  *
  * Bytes of plan workspace for a stack of these layers (host arithmetic; 0 on
  * invalid arguments).  layers: host. */
