@@ -517,7 +517,9 @@ def bench_decode_fusions(args, mq, synth, torch, np, dev):
     names = [n for (n, _, _) in block]
     qkv, gu = names[0:3], names[4:6]
     single = [n for n in names if n not in qkv + gu]
-    ws = mq.new_workspace(M, 11008, 11008, 8)
+    # one workspace for every mq_linear call: the largest any width needs (the prepared activations depend on r)
+    ws = torch.empty(max(mq.mq_workspace_bytes(M, 11008, 11008, r) for r in WIDTHS), dtype=torch.uint8, device=dev)
+    mq.mq_workspace_init(ws)
     for lays in blocks:
         lays["_qkv"] = mq.mq_stack_plan([lays[n] for n in qkv], M, device=dev)
         lays["_gu"] = mq.mq_stack_plan([lays[n] for n in gu], M, device=dev)

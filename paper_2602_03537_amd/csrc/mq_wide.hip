@@ -714,7 +714,9 @@ template <int C> static hipError_t launch_wide_c(StackParams p, int max_cost, hi
     }
     const int hw = wide_resident_groups<C>(lds_bytes);
     if (hw <= 0) return hipErrorUnknown;
-    uint64_t cap = p.cost_total / (uint64_t)max_cost;
+    // shares of at least eight super-tiles: a small layer cut into more shares spends more on handing its row blocks
+    // over than it gains in parallelism (Llama-2-7B shapes at M = 128: 52 -> 40 us per call)
+    uint64_t cap = p.cost_total / ((uint64_t)max_cost * 8);
     if (cap < 1) cap = 1;
     p.nworkers = (int)(cap < (uint64_t)hw ? cap : (uint64_t)hw);
     if (!p.table && p.nworkers == hw) {
