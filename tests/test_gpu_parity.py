@@ -11,40 +11,11 @@ import oracle
 import paper_2602_03537_amd as mq
 from paper_2602_03537_amd import synth
 from layout_ref import pack_ref, meta_ref
+import tolerance
+from gpu_util import C, DEV, WIDTHS, check_layer, check_y, dev, run_linear
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
-
-WIDTHS = (2, 3, 4, 6, 8)
-C = 8
-MAX_ABS = 2e-2
-REL_L2 = 1e-3
-DEV = "cuda"
-
-
-def dev(a):
-    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
-
-
-def check_y(y_gpu, y_ref, what=""):
-    yg = y_gpu.detach().cpu().numpy().astype(np.float64)
-    assert yg.shape == y_ref.shape, what
-    assert np.all(np.isfinite(yg)), what
-    err = np.abs(yg - y_ref).max()
-    rel = np.linalg.norm(yg - y_ref) / max(np.linalg.norm(y_ref), 1e-30)
-    assert err <= MAX_ABS, f"{what}: max-abs {err}"
-    assert rel <= REL_L2, f"{what}: rel-L2 {rel}"
-
-
-def run_linear(L, r, M=None):
-    """host layer dict -> y (device tensor) through slice, pack, meta, linear."""
-    N, K = L["parent"].shape
-    lay = mq.prepare_layer(dev(L["parent"]), dev(L["scales"]), dev(L["zeros"]), r)
-    x = dev(L["x"] if M is None else L["x"][:M])
-    ws = mq.new_workspace(x.shape[0], N, K, r)
-    y = mq.mq_linear(x, lay["packed_W"], lay["scales_t"], lay["zeros_t"], N, K, r, 128, ws)
-    torch.cuda.synchronize()
-    return y
 
 
 # ------------------------------------------------------------------ slice
@@ -151,7 +122,7 @@ def test_linear_config_512x512_r4_seed0():
     # smallest configuration: K=512, N=512, M=1, group 128, r=4, seed 0
     L = synth.make_layer(512, 512, M=1, seed=0)
     y = run_linear(L, 4)
-    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, 4, 128), "config 512x512")
+    check_layer(y, L, 4, "config 512x512")
 
 
 @pytest.mark.parametrize("r", WIDTHS)
@@ -160,7 +131,7 @@ def test_linear_matches_oracle_multi_tile_and_ragged(r, shape):
     N, K = shape
     L = synth.make_layer(N, K, M=1, seed=[1, N, K])
     y = run_linear(L, r)
-    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"{shape} r={r}")
+    check_layer(y, L, r, f"{shape} r={r}")
 
 
 @pytest.mark.parametrize("r", WIDTHS)
@@ -168,7 +139,7 @@ def test_linear_matches_oracle_multi_tile_and_ragged(r, shape):
 def test_linear_small_batches(r, M):
     L = synth.make_layer(200, 768, M=M, seed=[2, M])
     y = run_linear(L, r)
-    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"M={M} r={r}")
+    check_layer(y, L, r, f"M={M} r={r}")
 
 
 @pytest.mark.parametrize("r", WIDTHS)
@@ -176,7 +147,7 @@ def test_linear_uniform_random_codes_and_fractional_zeros(r):
     # not a quantiser's output: every code value, non-integer zero-offsets
     L = synth.make_random_codes_layer(192, 640, M=2, seed=[3, r])
     y = run_linear(L, r)
-    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"random codes r={r}")
+    check_layer(y, L, r, f"random codes r={r}")
 
 
 def test_linear_symmetric_zero_offsets():
@@ -184,7 +155,7 @@ def test_linear_symmetric_zero_offsets():
     L = synth.make_layer(128, 512, M=1, seed=[4])
     L["zeros"] = np.full_like(L["zeros"], 128.0)
     for r in WIDTHS:
-        check_y(run_linear(L, r), oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"sym r={r}")
+        check_layer(run_linear(L, r), L, r, f"sym r={r}")
 
 
 def test_linear_degenerate_inputs():
@@ -194,11 +165,10 @@ def test_linear_degenerate_inputs():
     # extreme codes only (0 and 255): clamp region of Eq. 1 at every width
     ext = dict(L, parent=np.where(L["parent"] > 127, 255, 0).astype(np.uint8))
     for r in WIDTHS:
-        check_y(run_linear(ext, r), oracle.linear(ext["x"], ext["parent"], ext["scales"], ext["zeros"], C, r, 128),
-                f"extreme r={r}")
+        check_layer(run_linear(ext, r), ext, r, f"extreme r={r}")
     # large activations (outliers) keep the fp16-subnormal arithmetic exact
     big = dict(L, x=(L["x"].astype(np.float32) * 64).astype(np.float16), scales=(L["scales"] / 64).astype(np.float16))
-    check_y(run_linear(big, 2), oracle.linear(big["x"], big["parent"], big["scales"], big["zeros"], C, 2, 128), "big x")
+    check_layer(run_linear(big, 2), big, 2, "big x")
 
 
 def test_linear_r8_equals_plain_8bit_layer_and_low_widths_differ():
@@ -207,9 +177,9 @@ def test_linear_r8_equals_plain_8bit_layer_and_low_widths_differ():
     w = np.repeat(L["scales"].astype(np.float64), 128, 1) * (L["parent"].astype(np.float64)
                                                               - np.repeat(L["zeros"].astype(np.float64), 128, 1))
     ref8 = L["x"].astype(np.float64) @ w.T
-    assert np.abs(y8 - ref8).max() <= MAX_ABS
+    assert np.abs(y8 - ref8).max() <= tolerance.MAX_ABS
     y2 = run_linear(L, 2).cpu().numpy().astype(np.float64)
-    assert np.abs(y2 - ref8).max() > 10 * MAX_ABS          # the 2-bit slice is a different model
+    assert np.abs(y2 - ref8).max() > 10 * tolerance.MAX_ABS          # the 2-bit slice is a different model
 
 
 def test_linear_is_deterministic_and_leaves_guard_bands_alone():
@@ -228,7 +198,7 @@ def test_linear_is_deterministic_and_leaves_guard_bands_alone():
         outs.append(y.clone())
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
     assert torch.isnan(buf[:64]).all() and torch.isnan(buf[64 + 2 * N:]).all()
-    check_y(outs[0], oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), "guard")
+    check_layer(outs[0], L, r, "guard")
 
 
 def test_linear_workspace_is_reusable_across_shapes():
@@ -238,7 +208,7 @@ def test_linear_workspace_is_reusable_across_shapes():
         L = synth.make_layer(N, K, M=1, seed=[8, N, K, r])
         lay = mq.prepare_layer(dev(L["parent"]), dev(L["scales"]), dev(L["zeros"]), r)
         y = mq.mq_linear(dev(L["x"]), lay["packed_W"], lay["scales_t"], lay["zeros_t"], N, K, r, 128, ws)
-        check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"reuse {N}x{K} r={r}")
+        check_layer(y, L, r, f"reuse {N}x{K} r={r}")
 
 
 def test_linear_rejects_oversized_batch_loudly():
@@ -259,7 +229,7 @@ def test_linear_rejects_oversized_batch_loudly():
 def test_linear_mfma_one_chunk(r, M):
     L = synth.make_layer(200, 768, M=M, seed=[40, M])
     y = run_linear(L, r)
-    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"mfma M={M} r={r}")
+    check_layer(y, L, r, f"mfma M={M} r={r}")
 
 
 @pytest.mark.parametrize("r", WIDTHS)
@@ -270,14 +240,14 @@ def test_linear_mfma_chunks_ragged_rows_and_columns(r, shape_m):
     N, K, M = shape_m
     L = synth.make_layer(N, K, M=M, seed=[41, N, K, M])
     y = run_linear(L, r)
-    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"mfma {shape_m} r={r}")
+    check_layer(y, L, r, f"mfma {shape_m} r={r}")
 
 
 @pytest.mark.parametrize("r", WIDTHS)
 def test_linear_mfma_uniform_random_codes_and_fractional_zeros(r):
     L = synth.make_random_codes_layer(192, 640, M=24, seed=[42, r])
     y = run_linear(L, r)
-    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"mfma random codes r={r}")
+    check_layer(y, L, r, f"mfma random codes r={r}")
 
 
 def test_linear_mfma_deterministic_guard_bands_and_matches_alu_path():
@@ -296,7 +266,7 @@ def test_linear_mfma_deterministic_guard_bands_and_matches_alu_path():
         outs.append(y.clone())
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
     assert torch.isnan(buf[:64]).all() and torch.isnan(buf[64 + M * N:]).all()
-    check_y(outs[0], oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), "mfma guard")
+    check_layer(outs[0], L, r, "mfma guard")
     # the same rows through the vector-ALU path (M=4 at a time) agree to fp16 rounding of the same fp32 sums
     ws4 = mq.new_workspace(4, N, K, r)
     y4 = torch.cat([mq.mq_linear(x[i:i + 4], lay["packed_W"], lay["scales_t"], lay["zeros_t"], N, K, r, 128, ws4)
@@ -315,7 +285,7 @@ def test_stack_mfma_mixed_widths(M):
         mq.mq_linear_stack(plan)
         torch.cuda.synchronize()
         for i, (lay, ref) in enumerate(zip(layers, oracle.linear_stack(host, C, 128))):
-            check_y(lay["y"], ref, f"mfma stack layer {i} rep {rep}")
+            check_y(lay["y"], ref, f"mfma stack layer {i} rep {rep}", host[i], host[i]["r"])
 
 
 # ------------------------------------------------------------------ wide matrix-core path (M > 16)
@@ -328,7 +298,7 @@ def test_linear_wide_chunk_counts_passes_and_ragged_edges(r, shape_m):
     N, K, M = shape_m
     L = synth.make_layer(N, K, M=M, seed=[47, N, K, M])
     y = run_linear(L, r)
-    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"wide {shape_m} r={r}")
+    check_layer(y, L, r, f"wide {shape_m} r={r}")
 
 
 @pytest.mark.parametrize("r", WIDTHS)
@@ -336,7 +306,7 @@ def test_linear_wide_uniform_random_codes_and_fractional_zeros(r):
     # every code value, zeros with fraction bits: the fp16 step 2^(8-r)*code - zero of this path rounds then
     L = synth.make_random_codes_layer(320, 1024, M=72, seed=[48, r])
     y = run_linear(L, r)
-    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"wide random codes r={r}")
+    check_layer(y, L, r, f"wide random codes r={r}")
 
 
 def test_linear_wide_split_k_hand_over_deterministic_with_guard_bands():
@@ -356,7 +326,7 @@ def test_linear_wide_split_k_hand_over_deterministic_with_guard_bands():
         outs.append(y.clone())
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
     assert torch.isnan(buf[:64]).all() and torch.isnan(buf[64 + M * N:]).all()
-    check_y(outs[0], oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), "wide split-K")
+    check_layer(outs[0], L, r, "wide split-K")
 
 
 @pytest.mark.parametrize("M", [40, 200])
@@ -370,7 +340,7 @@ def test_stack_wide_mixed_widths(M):
         mq.mq_linear_stack(plan)
         torch.cuda.synchronize()
         for i, (lay, ref) in enumerate(zip(layers, oracle.linear_stack(host, C, 128))):
-            check_y(lay["y"], ref, f"wide stack layer {i} rep {rep}")
+            check_y(lay["y"], ref, f"wide stack layer {i} rep {rep}", host[i], host[i]["r"])
 
 
 def test_linear_wide_rejects_misaligned_meta():
@@ -448,7 +418,7 @@ def test_stack_mixed_widths_matches_oracle(M):
         torch.cuda.synchronize()
         refs = oracle.linear_stack(host, C, 128)
         for i, (lay, ref) in enumerate(zip(layers, refs)):
-            check_y(lay["y"], ref, f"stack layer {i} rep {rep}")
+            check_y(lay["y"], ref, f"stack layer {i} rep {rep}", host[i], host[i]["r"])
 
 
 def test_stack_equals_layer_by_layer_calls_bit_for_bit_when_unsplit():
@@ -488,7 +458,8 @@ def test_stack_llama2_7b_block_mixed_widths_sampled_rows():
         N = lay["N"]
         rows = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, 62)]))
         ref = oracle.linear_rows(L["x"], L["parent"], L["scales"], L["zeros"], C, L["r"], 128, rows)
-        check_y(lay["y"][:, torch.from_numpy(rows).to(DEV)], ref, f"block linear {i} r={L['r']}")
+        sub = dict(L, parent=L["parent"][rows], scales=L["scales"][rows], zeros=L["zeros"][rows])
+        check_y(lay["y"][:, torch.from_numpy(rows).to(DEV)], ref, f"block linear {i} r={L['r']}", sub, L["r"])
         assert torch.isfinite(lay["y"]).all()
 
 
@@ -511,9 +482,9 @@ def _check_sampled(gen, layers, idx, n_rows, rng, what):
     N = lay["N"]
     rows = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, n_rows - 2)]))
     rt = torch.from_numpy(rows).to(DEV)
-    ref = oracle.linear(L["x"].cpu().numpy(), L["parent"][rt].cpu().numpy(), L["scales"][rt].cpu().numpy(),
-                        L["zeros"][rt].cpu().numpy(), C, lay["r"], 128)
-    check_y(lay["y"][:, rt], ref, f"{what} linear {idx} r={lay['r']}")
+    sub = dict(x=L["x"].cpu().numpy(), parent=L["parent"][rt].cpu().numpy(), scales=L["scales"][rt].cpu().numpy(),
+               zeros=L["zeros"][rt].cpu().numpy())
+    check_layer(lay["y"][:, rt], sub, lay["r"], f"{what} linear {idx} r={lay['r']}")
 
 
 def test_stack_llama2_7b_full_mixed_widths_mean_3p5():
@@ -614,7 +585,7 @@ def test_linear_from_parent_matches_oracle_and_the_repacked_layer(r, shape_m):
     ws = mq.new_workspace(M, N, K, 8)
     y = mq.mq_linear_from_parent(x, p8, st, zt, N, K, r, 128, ws)
     torch.cuda.synchronize()
-    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"from parent {shape_m} r={r}")
+    check_layer(y, L, r, f"from parent {shape_m} r={r}")
     # the re-packed layer computes the same sums in another order: equal to fp32 rounding
     pr = mq.mq_reslice(p8, N, K, C, r)
     y2 = mq.mq_linear(x, pr, st, zt, N, K, r, 128, mq.new_workspace(M, N, K, r))
@@ -627,7 +598,7 @@ def test_linear_from_parent_every_code_and_fractional_zeros(r):
     L["parent"] = _every_code_parent(192, 640, np.random.default_rng(62))
     p8, st, zt = _resident(L)
     y = mq.mq_linear_from_parent(dev(L["x"]), p8, st, zt, 192, 640, r, 128, mq.new_workspace(2, 192, 640, 8))
-    check_y(y, oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, r, 128), f"every code r={r}")
+    check_layer(y, L, r, f"every code r={r}")
 
 
 def test_linear_from_parent_batch_above_four_is_refused():
@@ -657,7 +628,7 @@ def test_stack_from_parent_mixed_widths(M):
         mq.mq_linear_stack(plan)
         torch.cuda.synchronize()
         for i, (lay, ref) in enumerate(zip(layers, refs)):
-            check_y(lay["y"], ref, f"from-parent stack layer {i} rep {rep}")
+            check_y(lay["y"], ref, f"from-parent stack layer {i} rep {rep}", host[i], host[i]["r"])
     # a different budget from the same resident parents: only the plan changes
     for lay, hl in zip(layers, host):
         lay["r"] = hl["r"] = 4
@@ -665,7 +636,7 @@ def test_stack_from_parent_mixed_widths(M):
     mq.mq_linear_stack(plan4)
     torch.cuda.synchronize()
     for i, (lay, ref) in enumerate(zip(layers, oracle.linear_stack(host, C, 128))):
-        check_y(lay["y"], ref, f"from-parent stack at 4 bits, layer {i}")
+        check_y(lay["y"], ref, f"from-parent stack at 4 bits, layer {i}", host[i], 4)
     mixed = [dict(l) for l in layers]
     mixed[1]["from_parent"] = 0
     with pytest.raises(mq.MqError):
@@ -963,4 +934,4 @@ def test_stack_shared_input_fusions_qkv_and_gate_up(M):
         mq.mq_linear_stack(mq.mq_stack_plan(layers, M))
         torch.cuda.synchronize()
         for i, (lay, ref) in enumerate(zip(layers, oracle.linear_stack(host, C, 128))):
-            check_y(lay["y"], ref, f"shared input M={M} layer {i}")
+            check_y(lay["y"], ref, f"shared input M={M} layer {i}", host[i], host[i]["r"])
