@@ -9,12 +9,22 @@
  *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers owned by the caller unless the
- *     argument is marked "host".  The library never allocates, frees or
- *     synchronises; every call enqueues work on `stream` (a hipStream_t passed
- *     as void*, NULL = the default stream) and returns.
+ *     argument is marked "host".  The library never allocates or frees device
+ *     memory, never copies between host and device, never synchronises and
+ *     keeps no state of its own between calls: every call enqueues kernels on
+ *     `stream` (a hipStream_t passed as void*, NULL = the default stream) and
+ *     returns.  Host arrays (layer tables, job lists, lambda) are consumed
+ *     before the call returns.  Every call may be recorded into a HIP graph.
  *   - Arguments are validated on the host BEFORE anything is enqueued; a call
- *     that returns anything but MQ_OK has enqueued nothing.  No exceptions, no
- *     abort.  Launch failures reported by the HIP runtime map to MQ_ERR_HIP.
+ *     that returns anything but MQ_OK because of its arguments has enqueued
+ *     nothing.  No exceptions, no abort.  A launch the HIP runtime refuses maps
+ *     to MQ_ERR_HIP (for the calls that enqueue several launches, the earlier
+ *     ones stay enqueued).  The runtime's sticky "last error" is neither read
+ *     nor cleared: an error the caller's own earlier work left pending is still
+ *     there for the caller afterwards.
+ *   - Launch shapes follow the device the calling thread has current (compute
+ *     units, occupancy), queried once per process; sizes returned by the
+ *     *_bytes functions do not depend on the device.
  *   - Matrices are row-major.  W is [N, K] (torch.nn.Linear convention:
  *     N output features, K input features), x is [M, K], y is [M, N].
  *   - fp16 values are IEEE binary16 (uint16_t storage on the C side).
@@ -79,8 +89,10 @@ mq_status mq_workspace_init(void *ws, size_t ws_bytes, mq_stream stream);
  * rounding half up (Section 3.1 "Slicing": the next lower bit alone decides),
  * r == c is the identity.  Elementwise over n codes.
  *   parent : device, n bytes, c-bit codes (values >= 2^c are masked to c bits)
- *   S_out  : device, n bytes, c-bit codes on the 2^(c-r) grid; may alias parent
- * Errors: BAD_R (r or c out of 1 <= r <= c <= 8), BAD_SHAPE (n < 0), NULL.
+ *   S_out  : device, n bytes, c-bit codes on the 2^(c-r) grid; either S_out == parent
+ *            (in place) or the two do not overlap
+ * Errors: BAD_R (r or c out of 1 <= r <= c <= 8), BAD_SHAPE (n < 0), NULL,
+ * UNSUPPORTED (partial overlap).
  * n == 0 is a no-op that returns MQ_OK even for NULL pointers. */
 mq_status mq_slice_codes(const uint8_t *parent, int64_t n, int c, int r, uint8_t *S_out,
                          mq_stream stream);
@@ -226,6 +238,19 @@ mq_status mq_linear(const mq_half *x, int64_t M, const void *packed_W, const mq_
                     const mq_half *zeros_t, int64_t N, int64_t K, int r, int group, mq_half *y,
                     void *ws, size_t ws_bytes, mq_stream stream);
 
+/* The call shape of the paper's kernel interface (Section 4: activations, packed weights, scales,
+ * zero-offsets in, y out) for callers that keep the quantiser's own [N, K/group] arrays: scales and
+ * zeros are re-tiled into `ws` by one small extra launch (reads and writes 4 * N * K/group bytes)
+ * and mq_linear runs on the result.  A hot loop tiles once with mq_pack_meta and calls mq_linear.
+ *   scales, zeros : device, fp16 [N, K/group] row-major (NOT tiled)
+ *   ws            : device, 256-byte aligned, ws_bytes >= mq_linear_plain_workspace_bytes(M,N,K,r),
+ *                   initialised once with mq_workspace_init
+ * Other arguments, results and errors as mq_linear. */
+size_t mq_linear_plain_workspace_bytes(int64_t M, int64_t N, int64_t K, int r);
+mq_status mq_linear_plain(const mq_half *x, int64_t M, const void *packed_W, const mq_half *scales,
+                          const mq_half *zeros, int64_t N, int64_t K, int r, int group, mq_half *y,
+                          void *ws, size_t ws_bytes, mq_stream stream);
+
 /* The same layer computed straight from the resident 8-bit parent: Eq. 1 is
  * applied to the codes in registers, so any r is served without a packed copy of
  * its own (8 bits per weight are streamed whatever r is).  Same arithmetic as
@@ -272,16 +297,31 @@ typedef struct {
  * invalid arguments).  layers: host. */
 size_t mq_stack_workspace_bytes(const mq_layer *layers, int n_layers, int64_t M);
 
-/* Validate the layers, build the device-side schedule inside `plan` (one
- * host-to-device copy enqueued on `stream`; the host array may be reused as
- * soon as the call returns) and zero its counters.  Done once per stack, like
- * packing.  plan: device, 256-byte aligned, plan_bytes >= mq_stack_workspace_bytes. */
-mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *plan,
-                        size_t plan_bytes, mq_stream stream);
+/* What mq_linear_stack needs to know about a planned stack.  HOST memory owned by the caller,
+ * filled by mq_stack_plan, opaque.  It names the device workspace it was built in: it is valid for
+ * as long as that workspace and the layers' buffers are, may be copied freely, and must be filled
+ * again if the workspace is reused for anything else. */
+typedef struct {
+    uint64_t opaque[16];
+} mq_plan;
 
-/* Run every layer of a planned stack: one launch, asynchronous on `stream`.
- * `plan` must not be used by two calls that may run concurrently. */
-mq_status mq_linear_stack(void *plan, mq_stream stream);
+/* Validate the layers and build the schedule of the stack: the descriptor table is written into
+ * `plan_ws` (through kernel arguments, ceil(n_layers / 32) small launches on `stream`: `layers` may
+ * be reused as soon as the call returns) and its counters are zeroed; `plan` receives the header.
+ * Done once per stack, like packing.  Nothing is copied, read back or waited for.
+ *   layers  : host, n_layers entries
+ *   plan_ws : device, 256-byte aligned, plan_bytes >= mq_stack_workspace_bytes(layers, n_layers, M)
+ *   plan    : host, out
+ * Errors: NULL, BAD_SHAPE, BAD_R, BAD_GROUP, ALIGN, BUF_TOO_SMALL, UNSUPPORTED, HIP; `plan` is
+ * written only on MQ_OK. */
+mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *plan_ws,
+                        size_t plan_bytes, mq_plan *plan, mq_stream stream);
+
+/* Run every layer of a planned stack: one launch (two on the matrix-core paths), asynchronous on
+ * `stream`, after the work mq_stack_plan enqueued (same stream, or ordered by the caller).
+ * A plan must not be used by two calls that may run concurrently.
+ * Errors: NULL; BAD_SHAPE if `plan` was not filled by mq_stack_plan (or was overwritten); HIP. */
+mq_status mq_linear_stack(const mq_plan *plan, mq_stream stream);
 
 #ifdef __cplusplus
 }

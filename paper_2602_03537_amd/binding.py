@@ -14,7 +14,8 @@ __all__ = [
     "mq_workspace_init", "mq_slice_codes", "mq_pack", "mq_unpack", "mq_pack_meta", "mq_linear",
     "mq_slice_pack", "mq_reslice", "mq_reslice_many", "MqResliceJob", "mq_linear_from_parent", "mq_quant_matgptq",
     "mq_matgptq_workspace_bytes", "mq_matgptq_quantize",
-    "mq_stack_workspace_bytes", "mq_stack_plan", "mq_linear_stack", "MqLayer",
+    "mq_stack_workspace_bytes", "mq_stack_plan", "mq_linear_stack", "MqLayer", "MqPlan", "StackPlan",
+    "mq_linear_plain", "mq_linear_plain_workspace_bytes",
     "new_workspace", "prepare_layer",
 ]
 
@@ -45,6 +46,20 @@ class MqLayer(ctypes.Structure):
         ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("r", ctypes.c_int32), ("group", ctypes.c_int32),
         ("from_parent", ctypes.c_int32), ("reserved", ctypes.c_int32),
     ]
+
+
+class MqPlan(ctypes.Structure):
+    """mq_plan of include/mq.h: the host-side header of a planned stack (opaque)."""
+    _fields_ = [("opaque", ctypes.c_uint64 * 16)]
+
+
+class StackPlan:
+    """A planned stack as Python holds it: the host header and the device workspace it names (kept alive here)."""
+    __slots__ = ("handle", "ws")
+
+    def __init__(self, handle: MqPlan, ws):
+        self.handle = handle
+        self.ws = ws
 
 
 class MqResliceJob(ctypes.Structure):
@@ -94,8 +109,10 @@ def lib():
         "mq_matgptq_workspace_bytes": (sz, [i64, i32]),
         "mq_matgptq_quantize": (i32, [vp, i64, i64, i64, vp, i64, vp, vp, i32, i32, vp, i32, vp, i64, vp, sz, vp]),
         "mq_stack_workspace_bytes": (sz, [vp, i32, i64]),
-        "mq_stack_plan": (i32, [vp, i32, i64, vp, sz, vp]),
+        "mq_stack_plan": (i32, [vp, i32, i64, vp, sz, vp, vp]),
         "mq_linear_stack": (i32, [vp, vp]),
+        "mq_linear_plain_workspace_bytes": (sz, [i64, i64, i64, i32]),
+        "mq_linear_plain": (i32, [vp, i64, vp, vp, vp, i64, i64, i32, i32, vp, vp, sz, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -201,6 +218,21 @@ def mq_linear(x, packed_W, scales_t, zeros_t, N: int, K: int, r: int, group: int
         y = torch.empty((M, N), dtype=torch.float16, device=x.device)
     _check(lib().mq_linear(_ptr(x), M, _ptr(packed_W), _ptr(scales_t), _ptr(zeros_t), N, K, r, group, _ptr(y),
                            _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "mq_linear")
+    return y
+
+
+def mq_linear_plain_workspace_bytes(M: int, N: int, K: int, r: int) -> int:
+    return lib().mq_linear_plain_workspace_bytes(M, N, K, r)
+
+
+def mq_linear_plain(x, packed_W, scales, zeros, N: int, K: int, r: int, group: int, ws, y=None, stream=None):
+    """mq_linear on the quantiser's own [N, K/group] scales and zero-offsets (re-tiled into ws by the call)."""
+    import torch
+    M = x.shape[0]
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _check(lib().mq_linear_plain(_ptr(x), M, _ptr(packed_W), _ptr(scales), _ptr(zeros), N, K, r, group, _ptr(y),
+                                 _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "mq_linear_plain")
     return y
 
 
@@ -322,21 +354,24 @@ def mq_stack_workspace_bytes(layers: Sequence[dict], M: int) -> int:
     return lib().mq_stack_workspace_bytes(ctypes.cast(arr, ctypes.c_void_p), len(layers), M)
 
 
-def mq_stack_plan(layers: Sequence[dict], M: int, device="cuda", stream=None):
-    """layers: dicts with packed_W, scales_t, zeros_t, x, y (tensors), N, K, r.  Returns the plan tensor."""
+def mq_stack_plan(layers: Sequence[dict], M: int, device="cuda", stream=None, ws=None) -> StackPlan:
+    """layers: dicts with packed_W, scales_t, zeros_t, x, y (tensors), N, K, r.  Returns a StackPlan (host header +
+    the device workspace, allocated here with torch unless `ws` is given)."""
     import torch
     arr = _layer_array(layers)
     nbytes = lib().mq_stack_workspace_bytes(ctypes.cast(arr, ctypes.c_void_p), len(layers), M)
     if nbytes == 0:
         raise MqError(3, "mq_stack_workspace_bytes")
-    plan = torch.empty(nbytes, dtype=torch.uint8, device=device)
-    _check(lib().mq_stack_plan(ctypes.cast(arr, ctypes.c_void_p), len(layers), M, _ptr(plan), nbytes,
-                               _stream(stream)), "mq_stack_plan")
-    return plan
+    if ws is None:
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    handle = MqPlan()
+    _check(lib().mq_stack_plan(ctypes.cast(arr, ctypes.c_void_p), len(layers), M, _ptr(ws),
+                               ws.numel() * ws.element_size(), ctypes.byref(handle), _stream(stream)), "mq_stack_plan")
+    return StackPlan(handle, ws)
 
 
-def mq_linear_stack(plan, stream=None) -> None:
-    _check(lib().mq_linear_stack(_ptr(plan), _stream(stream)), "mq_linear_stack")
+def mq_linear_stack(plan: StackPlan, stream=None) -> None:
+    _check(lib().mq_linear_stack(ctypes.byref(plan.handle), _stream(stream)), "mq_linear_stack")
 
 
 # ----------------------------------------------------------------- convenience

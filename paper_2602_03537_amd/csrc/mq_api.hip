@@ -2,8 +2,7 @@
 // workspace arithmetic and dispatch to the kernel launchers.
 #include <climits>
 #include <cmath>
-#include <mutex>
-#include <unordered_map>
+#include <cstring>
 #include <vector>
 
 #include "mq_internal.h"
@@ -117,21 +116,31 @@ LayerDesc make_desc(const mq_layer &l, int64_t M, int64_t Mp, uint64_t cost_star
     return d;
 }
 
-// Plan workspace: [header 256 B][LayerDesc table][counters][partial sums][prepared activations per layer]
+// Plan workspace (device): [256 B unused][LayerDesc table][counters][partial sums][prepared activations per layer].
+// What a launch needs to know about it lives on the HOST, in the caller's mq_plan: running a stack reads nothing
+// back from the device and the library keeps no record of plans of its own.
 struct PlanHeader {
     uint64_t magic;
+    uint64_t check;  // fold of every other field: an mq_plan that was never filled, or was overwritten, is refused
+    void *ws;        // the device workspace the plan was built in
     uint64_t cost_total;
     int32_t n_layers, M, max_cost, n_jobs;
     uint64_t table_off, cnt_off, part_off, total_bytes;
     int32_t from_parent, path_M;
     int32_t ll_blocks, ll_waves;  // low-latency launch shape of a small stack, or 0
 };
-constexpr uint64_t kPlanMagic = 0x4d51504c414e3036ull;  // "MQPLAN06"
+static_assert(sizeof(PlanHeader) <= sizeof(mq_plan), "the header must fit the caller's handle");
+constexpr uint64_t kPlanMagic = 0x4d51504c414e3037ull;  // "MQPLAN07"
 
-// Host-side copies of the plan headers, keyed by device address, so that running
-// a stack needs no read-back.  mq_stack_plan overwrites the entry of its address.
-std::mutex g_plan_mutex;
-std::unordered_map<void *, PlanHeader> g_plans;
+uint64_t plan_check(const PlanHeader &h) {
+    PlanHeader t = h;
+    t.check = 0;
+    uint64_t w[sizeof(PlanHeader) / 8 + 1] = {};
+    std::memcpy(w, &t, sizeof(t));
+    uint64_t acc = 0x9e3779b97f4a7c15ull;
+    for (uint64_t v : w) acc = (acc ^ v) * 0x100000001b3ull + (acc >> 29);
+    return acc;
+}
 
 struct PlanLayout {
     size_t table_off, cnt_off, cnt_bytes, part_off, act_off, total;
@@ -239,6 +248,7 @@ mq_status mq_slice_codes(const uint8_t *parent, int64_t n, int c, int r, uint8_t
     if (n < 0) return MQ_ERR_BAD_SHAPE;
     if (n == 0) return MQ_OK;  // nothing to do; pointers of an empty array may be NULL
     if (!parent || !S_out) return MQ_ERR_NULL;
+    if (S_out != parent && S_out < parent + n && parent < S_out + n) return MQ_ERR_UNSUPPORTED;  // partial overlap
     return launch_slice(parent, n, c, r, S_out, (hipStream_t)stream) == hipSuccess ? MQ_OK : MQ_ERR_HIP;
 }
 
@@ -410,9 +420,9 @@ size_t mq_stack_workspace_bytes(const mq_layer *layers, int n_layers, int64_t M)
     return plan_layout(layers, n_layers, stack_path_m(M, layers[0].from_parent != 0, small_stack(layers, n_layers, M))).total;
 }
 
-mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *plan, size_t plan_bytes,
-                        mq_stream stream) {
-    if (!layers || !plan) return MQ_ERR_NULL;
+mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *plan_ws, size_t plan_bytes,
+                        mq_plan *plan, mq_stream stream) {
+    if (!layers || !plan_ws || !plan) return MQ_ERR_NULL;
     if (n_layers < 1 || n_layers > (1 << 20)) return MQ_ERR_BAD_SHAPE;
     if (M < 1 || M > MQ_MAX_M) return MQ_ERR_BAD_SHAPE;
     const int64_t Mp = stack_path_m(M, layers[0].from_parent != 0, small_stack(layers, n_layers, M));
@@ -420,13 +430,13 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
         if (mq_status st = layer_status(layers[i], Mp)) return st;
         if (layers[i].from_parent != layers[0].from_parent) return MQ_ERR_UNSUPPORTED;  // one kernel variant per launch
     }
-    if (!aligned(plan, 256)) return MQ_ERR_ALIGN;
+    if (!aligned(plan_ws, 256)) return MQ_ERR_ALIGN;
     const size_t need = mq_stack_workspace_bytes(layers, n_layers, M);
     if (need == 0) return MQ_ERR_BAD_SHAPE;
     if (plan_bytes < need) return MQ_ERR_BUF_TOO_SMALL;
 
     const PlanLayout pl = plan_layout(layers, n_layers, Mp);
-    char *base_dev = static_cast<char *>(plan);
+    char *base_dev = static_cast<char *>(plan_ws);
     int64_t counters = 0, jobs = 0;
     uint64_t cost = 0;
     int max_cost = 0;
@@ -445,6 +455,7 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
     if (counters > INT32_MAX || jobs > INT32_MAX) return MQ_ERR_BAD_SHAPE;
     PlanHeader h{};
     h.magic = kPlanMagic;
+    h.ws = plan_ws;
     h.cost_total = cost;
     h.n_layers = n_layers;
     h.M = (int32_t)M;
@@ -463,40 +474,25 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
             h.ll_waves = nw;
         }
     }
+    h.check = plan_check(h);
 
+    // The descriptor table travels to the device inside kernel arguments (copied when the launch is enqueued), so the
+    // host arrays may go away as soon as this returns and nothing is waited for.
     hipStream_t s = (hipStream_t)stream;
-    char *base = static_cast<char *>(plan);
-    // set-up call: the copies are waited for, so the host arrays may go away
-    if (hipMemcpyAsync(base, &h, sizeof(h), hipMemcpyHostToDevice, s) != hipSuccess) return MQ_ERR_HIP;
-    if (hipMemcpyAsync(base + pl.table_off, table.data(), table.size() * sizeof(LayerDesc), hipMemcpyHostToDevice,
-                       s) != hipSuccess)
+    if (launch_write_table(table.data(), n_layers, reinterpret_cast<LayerDesc *>(base_dev + pl.table_off), s) != hipSuccess)
         return MQ_ERR_HIP;
-    if (launch_fill_zero(base + pl.cnt_off, pl.cnt_bytes, s) != hipSuccess) return MQ_ERR_HIP;
-    if (hipStreamSynchronize(s) != hipSuccess) return MQ_ERR_HIP;
-    {
-        std::lock_guard<std::mutex> lock(g_plan_mutex);
-        g_plans[plan] = h;
-    }
+    if (launch_fill_zero(base_dev + pl.cnt_off, pl.cnt_bytes, s) != hipSuccess) return MQ_ERR_HIP;
+    std::memset(plan, 0, sizeof(*plan));
+    std::memcpy(plan, &h, sizeof(h));
     return MQ_OK;
 }
 
-mq_status mq_linear_stack(void *plan, mq_stream stream) {
+mq_status mq_linear_stack(const mq_plan *plan, mq_stream stream) {
     if (!plan) return MQ_ERR_NULL;
-    if (!aligned(plan, 256)) return MQ_ERR_ALIGN;
     PlanHeader h{};
-    bool known = false;
-    {
-        std::lock_guard<std::mutex> lock(g_plan_mutex);
-        auto it = g_plans.find(plan);
-        if (it != g_plans.end()) { h = it->second; known = true; }
-    }
-    if (!known) {  // planned by another process image: read the header back once
-        if (hipMemcpy(&h, plan, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return MQ_ERR_HIP;
-        if (h.magic != kPlanMagic) return MQ_ERR_BAD_SHAPE;
-        std::lock_guard<std::mutex> lock(g_plan_mutex);
-        g_plans[plan] = h;
-    }
-    char *base = static_cast<char *>(plan);
+    std::memcpy(&h, plan, sizeof(h));
+    if (h.magic != kPlanMagic || h.check != plan_check(h) || !h.ws) return MQ_ERR_BAD_SHAPE;  // not a filled plan
+    char *base = static_cast<char *>(h.ws);
     StackParams p{};
     p.table = reinterpret_cast<const LayerDesc *>(base + h.table_off);
     p.n_layers = h.n_layers;
@@ -512,6 +508,31 @@ mq_status mq_linear_stack(void *plan, mq_stream stream) {
                                                                        (hipStream_t)stream)
                                               : launch_stack(p, h.max_cost, h.from_parent != 0, (hipStream_t)stream);
     return e == hipSuccess ? MQ_OK : MQ_ERR_HIP;
+}
+
+size_t mq_linear_plain_workspace_bytes(int64_t M, int64_t N, int64_t K, int r) {
+    const size_t ws = mq_workspace_bytes(M, N, K, r), meta = mq_meta_bytes(N, K, kGroup);
+    if (ws == 0 || meta == 0) return 0;
+    return align_up(ws, 256) + 2 * align_up(meta, 256);
+}
+
+mq_status mq_linear_plain(const mq_half *x, int64_t M, const void *packed_W, const mq_half *scales, const mq_half *zeros,
+                          int64_t N, int64_t K, int r, int group, mq_half *y, void *ws, size_t ws_bytes,
+                          mq_stream stream) {
+    if (!scales || !zeros || !ws) return MQ_ERR_NULL;
+    if (!valid_pack_r(r)) return MQ_ERR_BAD_R;
+    if (M < 1 || M > MQ_MAX_M) return MQ_ERR_BAD_SHAPE;
+    if (mq_status st = check_shape(N, K, group)) return st;
+    if (!aligned(ws, 256) || !aligned(scales, 2) || !aligned(zeros, 2)) return MQ_ERR_ALIGN;
+    if (ws_bytes < mq_linear_plain_workspace_bytes(M, N, K, r)) return MQ_ERR_BUF_TOO_SMALL;
+    const size_t inner = align_up(mq_workspace_bytes(M, N, K, r), 256), meta = align_up(mq_meta_bytes(N, K, group), 256);
+    char *base = static_cast<char *>(ws);
+    mq_half *st = reinterpret_cast<mq_half *>(base + inner), *zt = reinterpret_cast<mq_half *>(base + inner + meta);
+    // validate the linear call before anything is enqueued (a failing call enqueues nothing)
+    const mq_layer l{packed_W, st, zt, x, y, N, K, r, group, 0, 0};
+    if (mq_status s = layer_status(l, M)) return s;
+    if (mq_status s = mq_pack_meta(scales, zeros, N, K, group, st, zt, mq_meta_bytes(N, K, group), stream)) return s;
+    return run_single(l, M, ws, inner, stream);
 }
 
 }  // extern "C"

@@ -389,12 +389,9 @@ hipError_t launch_stack_mfma(StackParams p, int max_cost, hipStream_t s) {
     if (cap < 1) cap = 1;
     p.nwaves = (int)(cap < (uint64_t)hw ? cap : (uint64_t)hw);
     p.nworkers = p.nwaves;
-    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
-    hipLaunchKernelGGL(xprep_kernel, dim3((unsigned)((p.n_jobs + 3) / 4)), dim3(256), 0, s, p);
-    hipError_t e = hipGetLastError();
+    const hipError_t e = launch(xprep_kernel, dim3((unsigned)((p.n_jobs + 3) / 4)), dim3(256), 0, s, p);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(gemm_stack_kernel, dim3((unsigned)((p.nwaves + 3) / 4)), dim3(256), 0, s, p);
-    return hipGetLastError();
+    return launch(gemm_stack_kernel, dim3((unsigned)((p.nwaves + 3) / 4)), dim3(256), 0, s, p);
 }
 
 }  // namespace mq

@@ -211,12 +211,12 @@ __global__ __launch_bounds__(64) void gptq_trailing_kernel(float *__restrict__ W
 }
 
 template <uint32_t MASK, int LPR>
-static void launch_gptq_block(const float *W, int64_t ldw, int64_t N, int64_t i0, int B, const float *U, int64_t ldu,
+static hipError_t launch_gptq_block(const float *W, int64_t ldw, int64_t N, int64_t i0, int B, const float *U, int64_t ldu,
                               const _Float16 *scales, const _Float16 *zeros, int64_t G, const QuantLambda &lam,
                               float n_widths, uint8_t *Q, int64_t ldq, float *E, hipStream_t s) {
     constexpr int RPW = 64 / LPR;
-    hipLaunchKernelGGL((gptq_block_kernel<MASK, LPR>), dim3((unsigned)((N + RPW - 1) / RPW)), dim3(64), 0, s, W, ldw, N, i0,
-                       B, U, ldu, scales, zeros, G, lam, n_widths, Q, ldq, E);
+    return launch((gptq_block_kernel<MASK, LPR>), dim3((unsigned)((N + RPW - 1) / RPW)), dim3(64), 0, s, W, ldw, N, i0, B, U,
+                  ldu, scales, zeros, G, lam, n_widths, Q, ldq, E);
 }
 
 // Lanes per row: the column steps are a dependent chain, so the chip is filled by spreading each
@@ -235,29 +235,29 @@ static hipError_t launch_gptq_mask(float *W, int64_t ldw, int64_t N, int64_t K, 
     // B, K and the block starts are multiples of 16, so only the strides and base addresses decide
     const bool vec4 = ldw % 4 == 0 && ldu % 4 == 0 && (reinterpret_cast<uintptr_t>(W) & 15) == 0 &&
                       (reinterpret_cast<uintptr_t>(U) & 15) == 0;
-    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
     for (int64_t i0 = 0; i0 < K; i0 += B) {
+        hipError_t e;
         if (lpr == 4)
-            launch_gptq_block<MASK, 4>(W, ldw, N, i0, B, U, ldu, scales, zeros, G, lam, n_widths, Q, ldq, E, s);
+            e = launch_gptq_block<MASK, 4>(W, ldw, N, i0, B, U, ldu, scales, zeros, G, lam, n_widths, Q, ldq, E, s);
         else if (lpr == 16)
-            launch_gptq_block<MASK, 16>(W, ldw, N, i0, B, U, ldu, scales, zeros, G, lam, n_widths, Q, ldq, E, s);
+            e = launch_gptq_block<MASK, 16>(W, ldw, N, i0, B, U, ldu, scales, zeros, G, lam, n_widths, Q, ldq, E, s);
         else
-            launch_gptq_block<MASK, 64>(W, ldw, N, i0, B, U, ldu, scales, zeros, G, lam, n_widths, Q, ldq, E, s);
+            e = launch_gptq_block<MASK, 64>(W, ldw, N, i0, B, U, ldu, scales, zeros, G, lam, n_widths, Q, ldq, E, s);
+        if (e != hipSuccess) return e;
         const int64_t c0 = i0 + B, ncols = K - c0;
         if (ncols > 0) {
             const int64_t rblocks = (N + kTrailRows - 1) / kTrailRows;
             if (vec4) {
                 const int64_t kblocks = (ncols + 255) / 256;
-                hipLaunchKernelGGL(gptq_trailing_kernel<true>, dim3((unsigned)(kblocks * rblocks)), dim3(64), 0, s, W, ldw, N,
-                                   c0, ncols, E, B, U, ldu, i0, kblocks);
+                e = launch(gptq_trailing_kernel<true>, dim3((unsigned)(kblocks * rblocks)), dim3(64), 0, s, W, ldw, N, c0,
+                           ncols, E, B, U, ldu, i0, kblocks);
             } else {
                 const int64_t kblocks = (ncols + 63) / 64;
-                hipLaunchKernelGGL(gptq_trailing_kernel<false>, dim3((unsigned)(kblocks * rblocks)), dim3(64), 0, s, W, ldw, N,
-                                   c0, ncols, E, B, U, ldu, i0, kblocks);
+                e = launch(gptq_trailing_kernel<false>, dim3((unsigned)(kblocks * rblocks)), dim3(64), 0, s, W, ldw, N, c0,
+                           ncols, E, B, U, ldu, i0, kblocks);
             }
+            if (e != hipSuccess) return e;
         }
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
     }
     return hipSuccess;
 }

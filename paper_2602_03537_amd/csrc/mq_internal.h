@@ -3,13 +3,19 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <type_traits>
+#include <utility>
+
 #include "../../include/mq.h"
 #include "mq_layout.h"
 
 namespace mq {
 
-// Upper bound on resident wavefronts of a persistent launch (256 CUs x 32);
-// sizes the partial-sum slots of a workspace independently of the device.
+// Caps on the wavefronts / workgroups of a persistent launch.  They size the partial-sum slots of a workspace, which
+// must be plain host arithmetic (callable without a device); every launcher asks the device for its compute units
+// and the kernel's occupancy and launches min(what is resident there, the cap), so a smaller or larger part stays
+// correct and only loses the slots it cannot use.  (8192 = 256 compute units x 32 waves, the MI355X.)
 constexpr int kMaxWaves = 8192;
 constexpr int kMaxWavesMfma = 4096;  // the MFMA kernel runs at most 2 waves per SIMD
 // Vector-ALU stack kernel: each wave serves several interleaved shares of the schedule, so that
@@ -123,6 +129,21 @@ inline int wide_tile_cost(int r, int C) {
     return t[(C < 1 ? 1 : C > 4 ? 4 : C) - 1][ri];
 }
 
+// Enqueue a kernel and return the status of THIS launch.  The runtime's sticky "last error" is neither read nor
+// cleared, so an error the caller's own earlier work left pending stays where the caller will find it.
+template <class... KArgs, size_t... I>
+inline hipError_t launch_impl(void (*kernel)(KArgs...), dim3 grid, dim3 block, unsigned lds_bytes, hipStream_t s,
+                              std::tuple<std::decay_t<KArgs>...> &vals, std::index_sequence<I...>) {
+    void *ptrs[sizeof...(KArgs) ? sizeof...(KArgs) : 1] = {static_cast<void *>(&std::get<I>(vals))...};
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, lds_bytes, s);
+}
+template <class... KArgs, class... Args>
+inline hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, unsigned lds_bytes, hipStream_t s, Args &&...args) {
+    static_assert(sizeof...(KArgs) == sizeof...(Args), "argument count differs from the kernel's");
+    std::tuple<std::decay_t<KArgs>...> vals{static_cast<std::decay_t<KArgs>>(std::forward<Args>(args))...};
+    return launch_impl(kernel, grid, block, lds_bytes, s, vals, std::index_sequence_for<KArgs...>{});
+}
+
 inline int64_t pad_rows(int64_t N) { return (N + kRowBlock - 1) / kRowBlock * kRowBlock; }
 
 // launchers (mq_pack.hip / mq_linear.hip); each returns the hipError of the launch
@@ -138,6 +159,8 @@ hipError_t launch_reslice_many(const uint4 *const *src, uint4 *const *dst, const
 hipError_t launch_pack_meta(const _Float16 *sc, const _Float16 *zr, int64_t N, int64_t G, _Float16 *st,
                             _Float16 *zt, hipStream_t s);
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
+// table: host, n descriptors -> dst: device.  ceil(n / 32) small launches; the host array is free again on return.
+hipError_t launch_write_table(const LayerDesc *table, int n, LayerDesc *dst, hipStream_t s);
 // Algorithm 1 (mq_quant.hip).  lambda: host, kC floats (width r at [r-1]); vec4: four columns per lane (alignment checked by the caller)
 // Algorithm 2 column loop (mq_gptq.hip): 2 * K / B launches on s.  E: device, N * B floats of scratch.
 hipError_t launch_gptq(float *W, int64_t ldw, int64_t N, int64_t K, const float *U, int64_t ldu, const _Float16 *scales,

@@ -319,10 +319,8 @@ static hipError_t launch_linear_rb_rm(const LayerDesc &L, float *part, int32_t *
     const int KS = pick_k_slices(L);
     const int per_block = (L.G + KS - 1) / KS;
     const int W = (per_block >= 24 || (KS == 1 && per_block >= 12)) ? 16 : per_block >= 6 ? 8 : 4;
-    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
-    hipLaunchKernelGGL((linear_rb_kernel<R, M, kXLds, SL>), dim3((unsigned)(L.RB * KS)), dim3(64 * W), 0, s, L, KS, part,
+    return launch((linear_rb_kernel<R, M, kXLds, SL>), dim3((unsigned)(L.RB * KS)), dim3(64 * W), 0, s, L, KS, part,
                        cnt);
-    return hipGetLastError();
 }
 template <int M> static hipError_t launch_linear_rb_m(const LayerDesc &L, float *part, int32_t *cnt, hipStream_t s) {
     if (L.rs) return launch_linear_rb_rm<8, M, true>(L, part, cnt, s);
@@ -407,12 +405,9 @@ bool linear_rb_stack_shape(const LayerDesc *table, int n_layers, size_t part_byt
 
 template <int M> static hipError_t launch_linear_rb_stack_m(const StackParams &p, int blocks, int waves, bool from_parent,
                                                             hipStream_t s) {
-    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
     if (from_parent)
-        hipLaunchKernelGGL((linear_rb_stack_kernel<M, kXLds, true>), dim3((unsigned)blocks), dim3(64 * waves), 0, s, p);
-    else
-        hipLaunchKernelGGL((linear_rb_stack_kernel<M, kXLds, false>), dim3((unsigned)blocks), dim3(64 * waves), 0, s, p);
-    return hipGetLastError();
+        return launch((linear_rb_stack_kernel<M, kXLds, true>), dim3((unsigned)blocks), dim3(64 * waves), 0, s, p);
+    return launch((linear_rb_stack_kernel<M, kXLds, false>), dim3((unsigned)blocks), dim3(64 * waves), 0, s, p);
 }
 hipError_t launch_linear_rb_stack(const StackParams &p, int blocks, int waves, bool from_parent, hipStream_t s) {
     switch (p.M) {
@@ -465,9 +460,7 @@ template <int M, int XP, bool SL> static hipError_t launch_stack_mx(StackParams 
     if (spw < 1) spw = 1;
     p.nworkers = (int)(spw * (uint64_t)p.nwaves);
     const unsigned nblocks = (unsigned)((p.nwaves + 3) / 4);
-    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
-    hipLaunchKernelGGL((stack_kernel<M, XP, SL>), dim3(nblocks), dim3(256), 0, s, p);
-    return hipGetLastError();
+    return launch((stack_kernel<M, XP, SL>), dim3(nblocks), dim3(256), 0, s, p);
 }
 template <int M> static hipError_t launch_stack_m(StackParams p, int max_cost, bool from_parent, hipStream_t s) {
     // kXLds: measured 1-3 % (stack) to 20 % (single calls) faster than kXScalar

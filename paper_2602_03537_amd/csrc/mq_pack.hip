@@ -17,8 +17,9 @@ __device__ __forceinline__ uint32_t slice_byte(uint32_t q, int cmask, int sh, in
     return t << sh;
 }
 
-__global__ __launch_bounds__(256) void slice_kernel(const uint8_t *__restrict__ in, uint8_t *__restrict__ out,
-                                                    int64_t n, int cmask, int sh, int half, int tmax, int vec) {
+// in == out (in place) is allowed: every element is read and then written by the same lane.
+__global__ __launch_bounds__(256) void slice_kernel(const uint8_t *in, uint8_t *out, int64_t n, int cmask, int sh, int half,
+                                                    int tmax, int vec) {
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     int64_t nvec = vec ? n / 16 : 0;
@@ -45,10 +46,8 @@ hipError_t launch_slice(const uint8_t *parent, int64_t n, int c, int r, uint8_t 
     int64_t work = vec ? (n + 15) / 16 : n;
     int64_t blocks = (work + 255) / 256;
     if (blocks > 256 * 64) blocks = 256 * 64;
-    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
-    hipLaunchKernelGGL(slice_kernel, dim3((unsigned)blocks), dim3(256), 0, s, parent, out, n, (1 << c) - 1, sh, half,
-                       (1 << r) - 1, vec);
-    return hipGetLastError();
+    return launch(slice_kernel, dim3((unsigned)blocks), dim3(256), 0, s, parent, out, n, (1 << c) - 1, sh, half,
+                  (1 << r) - 1, vec);
 }
 
 // ------------------------------------------------------------------ pack
@@ -246,18 +245,14 @@ static hipError_t launch_pack_r(const uint8_t *S, int64_t N, int64_t K, uint4 *p
     const int64_t ntiles = pad_rows(N) / kRowBlock * G;
     const int64_t blocks = (ntiles * 64 + 255) / 256;
     if (blocks > (int64_t)0x7fffffff) return hipErrorInvalidValue;  // beyond one grid dimension
-    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
-    hipLaunchKernelGGL((pack_kernel<R, SL>), dim3((unsigned)blocks), dim3(256), 0, s, S, packed, (int)N, K, G, ntiles);
-    return hipGetLastError();
+    return launch((pack_kernel<R, SL>), dim3((unsigned)blocks), dim3(256), 0, s, S, packed, (int)N, K, G, ntiles);
 }
 template <int R>
 static hipError_t launch_reslice_r(const uint4 *parent8, int64_t N, int64_t K, uint4 *packed, hipStream_t s) {
     const int64_t ntiles = pad_rows(N) / kRowBlock * (K / kGroup);
     const int64_t blocks = (ntiles * 64 + 255) / 256;
     if (blocks > (int64_t)0x7fffffff) return hipErrorInvalidValue;  // beyond one grid dimension
-    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
-    hipLaunchKernelGGL(reslice_kernel<R>, dim3((unsigned)blocks), dim3(256), 0, s, parent8, packed, ntiles);
-    return hipGetLastError();
+    return launch(reslice_kernel<R>, dim3((unsigned)blocks), dim3(256), 0, s, parent8, packed, ntiles);
 }
 template <int R>
 static hipError_t launch_unpack_r(const uint4 *packed, int64_t N, int64_t K, uint8_t *S, hipStream_t s) {
@@ -265,9 +260,7 @@ static hipError_t launch_unpack_r(const uint4 *packed, int64_t N, int64_t K, uin
     const int64_t ntiles = pad_rows(N) / kRowBlock * G;
     const int64_t blocks = (ntiles * 64 + 255) / 256;
     if (blocks > (int64_t)0x7fffffff) return hipErrorInvalidValue;  // beyond one grid dimension
-    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
-    hipLaunchKernelGGL(unpack_kernel<R>, dim3((unsigned)blocks), dim3(256), 0, s, packed, S, (int)N, K, G, ntiles);
-    return hipGetLastError();
+    return launch(unpack_kernel<R>, dim3((unsigned)blocks), dim3(256), 0, s, packed, S, (int)N, K, G, ntiles);
 }
 
 hipError_t launch_pack(const uint8_t *S, int64_t N, int64_t K, int r, uint4 *packed, hipStream_t s) {
@@ -292,7 +285,6 @@ hipError_t launch_slice_pack(const uint8_t *parent, int64_t N, int64_t K, int r,
 }
 hipError_t launch_reslice_many(const uint4 *const *src, uint4 *const *dst, const int64_t *N, const int64_t *K,
                                const int *r, int n, hipStream_t s) {
-    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
     for (int j0 = 0; j0 < n; j0 += kResliceBatch) {
         ResliceJobs jobs{};
         int64_t tiles = 0;
@@ -306,8 +298,7 @@ hipError_t launch_reslice_many(const uint4 *const *src, uint4 *const *dst, const
         }
         const int64_t blocks = (tiles * 64 + 255) / 256;
         if (blocks > (int64_t)0x7fffffff) return hipErrorInvalidValue;  // beyond one grid dimension
-        hipLaunchKernelGGL(reslice_many_kernel, dim3((unsigned)blocks), dim3(256), 0, s, jobs);
-        const hipError_t e = hipGetLastError();
+        const hipError_t e = launch(reslice_many_kernel, dim3((unsigned)blocks), dim3(256), 0, s, jobs);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -352,10 +343,8 @@ __global__ __launch_bounds__(256) void pack_meta_kernel(const _Float16 *__restri
 hipError_t launch_pack_meta(const _Float16 *sc, const _Float16 *zr, int64_t N, int64_t G, _Float16 *st, _Float16 *zt,
                             hipStream_t s) {
     const int64_t total = pad_rows(N) * G;
-    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
-    hipLaunchKernelGGL(pack_meta_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, sc, zr, st, zt, N, G,
+    return launch(pack_meta_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, sc, zr, st, zt, N, G,
                        total);
-    return hipGetLastError();
 }
 
 __global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t *p, size_t n) {
@@ -365,9 +354,33 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t *p, size_t n) {
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s) {
     const size_t n = bytes / 4;
     if (!n) return hipSuccess;
-    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
-    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (uint32_t *)p, n);
-    return hipGetLastError();
+    return launch(fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (uint32_t *)p, n);
+}
+
+// ------------------------------------------------------------------ descriptor table of a stack plan
+// The table reaches the device inside kernel arguments, kDescPerLaunch descriptors per launch: the runtime copies
+// arguments when a launch is enqueued, so no host buffer has to outlive the call and nothing is waited for.
+constexpr int kDescPerLaunch = 32;
+constexpr int kDescDwords = sizeof(LayerDesc) / 4;
+struct DescChunk {
+    uint32_t w[kDescPerLaunch * kDescDwords];
+};
+static_assert(sizeof(DescChunk) + 16 <= 4096, "kernel arguments are limited to 4 KiB");
+
+__global__ __launch_bounds__(256) void write_table_kernel(const DescChunk chunk, uint32_t *dst, int ndw) {
+    for (int i = (int)threadIdx.x; i < ndw; i += 256) dst[i] = chunk.w[i];
+}
+
+hipError_t launch_write_table(const LayerDesc *table, int n, LayerDesc *dst, hipStream_t s) {
+    for (int i0 = 0; i0 < n; i0 += kDescPerLaunch) {
+        const int cnt = n - i0 < kDescPerLaunch ? n - i0 : kDescPerLaunch;
+        DescChunk c{};
+        __builtin_memcpy(c.w, table + i0, (size_t)cnt * sizeof(LayerDesc));
+        const hipError_t e = launch(write_table_kernel, dim3(1), dim3(256), 0, s, c,
+                                    reinterpret_cast<uint32_t *>(dst + i0), cnt * kDescDwords);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace mq

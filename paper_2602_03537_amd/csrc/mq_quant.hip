@@ -44,14 +44,11 @@ static hipError_t launch_quant_mask(const float *W, int64_t ldw, int64_t N, int6
     const int64_t threads = vec4 ? N * (ncols / 4) : N * ncols;
     const int64_t blocks = (threads + 255) / 256;
     if (blocks > (int64_t)0x7fffffff) return hipErrorInvalidValue;  // beyond one grid dimension
-    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
     if (vec4)
-        hipLaunchKernelGGL((quant_kernel<MASK, 4>), dim3((unsigned)blocks), dim3(256), 0, s, W, ldw, N, ncols, col0, scales,
-                           zeros, G, lam, Q, ldq);
-    else
-        hipLaunchKernelGGL((quant_kernel<MASK, 1>), dim3((unsigned)blocks), dim3(256), 0, s, W, ldw, N, ncols, col0, scales,
-                           zeros, G, lam, Q, ldq);
-    return hipGetLastError();
+        return launch((quant_kernel<MASK, 4>), dim3((unsigned)blocks), dim3(256), 0, s, W, ldw, N, ncols, col0, scales, zeros,
+                      G, lam, Q, ldq);
+    return launch((quant_kernel<MASK, 1>), dim3((unsigned)blocks), dim3(256), 0, s, W, ldw, N, ncols, col0, scales, zeros, G,
+                  lam, Q, ldq);
 }
 
 hipError_t launch_quant(const float *W, int64_t ldw, int64_t N, int64_t ncols, int64_t col0, const _Float16 *scales,

@@ -736,12 +736,9 @@ template <int C> static hipError_t launch_wide_c(StackParams p, int max_cost, hi
     }
     p.nwaves = p.nworkers * 4;
     p.slot_floats = 4 * C * 32 * 64;
-    (void)hipGetLastError();  // drop stale errors of earlier, unrelated calls
-    hipLaunchKernelGGL(xprep_wide_kernel, dim3((unsigned)p.n_jobs), dim3(256), 0, s, p);
-    hipError_t e = hipGetLastError();
+    const hipError_t e = launch(xprep_wide_kernel, dim3((unsigned)p.n_jobs), dim3(256), 0, s, p);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(wide_stack_kernel<C>, dim3((unsigned)p.nworkers), dim3(256), lds_bytes, s, p);
-    return hipGetLastError();
+    return launch(wide_stack_kernel<C>, dim3((unsigned)p.nworkers), dim3(256), (unsigned)lds_bytes, s, p);
 }
 
 hipError_t launch_stack_wide(StackParams p, int max_cost, hipStream_t s) {

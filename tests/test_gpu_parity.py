@@ -935,3 +935,91 @@ def test_stack_shared_input_fusions_qkv_and_gate_up(M):
         torch.cuda.synchronize()
         for i, (lay, ref) in enumerate(zip(layers, oracle.linear_stack(host, C, 128))):
             check_y(lay["y"], ref, f"shared input M={M} layer {i}", host[i], host[i]["r"])
+
+
+# ------------------------------------------------------------------ boundary conventions
+@pytest.mark.parametrize("shape_m_r", [(512, 512, 1, 4), (200, 1280, 3, 3), (130, 384, 8, 6), (320, 640, 40, 2), (1, 256, 1, 8)])
+def test_linear_plain_on_row_major_scales_and_zeros(shape_m_r):
+    # the call shape of the paper's kernel interface: the quantiser's own [N, K/128] arrays go straight in
+    N, K, M, r = shape_m_r
+    L = synth.make_layer(N, K, M=M, seed=[99, N, K, M])
+    packed = mq.mq_slice_pack(dev(L["parent"]), C, r)
+    ws = torch.empty(mq.mq_linear_plain_workspace_bytes(M, N, K, r), dtype=torch.uint8, device=DEV)
+    mq.mq_workspace_init(ws)
+    for _ in range(2):                                           # the workspace is reusable
+        y = mq.mq_linear_plain(dev(L["x"]), packed, dev(L["scales"]), dev(L["zeros"]), N, K, r, 128, ws)
+        torch.cuda.synchronize()
+        check_layer(y, L, r, f"plain {shape_m_r}")
+    st, zt = mq.mq_pack_meta(dev(L["scales"]), dev(L["zeros"]), K)
+    y2 = mq.mq_linear(dev(L["x"]), packed, st, zt, N, K, r, 128, mq.new_workspace(M, N, K, r))
+    assert torch.equal(y, y2)                                    # the same kernels on the same tiles
+
+
+def test_stack_replanned_in_the_same_workspace_and_host_arrays_reused_at_once():
+    # the plan header lives with the caller: planning again into the same device workspace simply replaces it, and
+    # the host layer table may be overwritten as soon as mq_stack_plan has returned (nothing is waited for)
+    hostA, layersA = _stack([(256, 512, 2), (200, 1280, 3), (64, 128, 8), (1024, 1024, 3)], M=2, seed=101)
+    hostB, layersB = _stack([(130, 384, 4), (512, 256, 6)], M=2, seed=102)
+    planA = mq.mq_stack_plan(layersA, 2)
+    mq.mq_linear_stack(planA)
+    torch.cuda.synchronize()
+    for i, (lay, L) in enumerate(zip(layersA, hostA)):
+        check_layer(lay["y"], L, L["r"], f"first plan layer {i}")
+    planB = mq.mq_stack_plan(layersB, 2, ws=planA.ws)            # same address, another stack
+    mq.mq_linear_stack(planB)
+    torch.cuda.synchronize()
+    for i, (lay, L) in enumerate(zip(layersB, hostB)):
+        check_layer(lay["y"], L, L["r"], f"second plan layer {i}")
+    # many stacks planned back to back from ONE host array that is rewritten between the calls
+    import ctypes
+    n = 40
+    arr = (mq.MqLayer * n)()
+    handles, wss, ys = [], [], []
+    base = layersA[1]
+    for rep in range(3):
+        for i in range(n):
+            y = torch.full((2, base["N"]), float("nan"), dtype=torch.float16, device=DEV)
+            ys.append(y)
+            arr[i] = mq.MqLayer(base["packed_W"].data_ptr(), base["scales_t"].data_ptr(), base["zeros_t"].data_ptr(),
+                                base["x"].data_ptr(), y.data_ptr(), base["N"], base["K"], base["r"], 128, 0, 0)
+        nbytes = mq.lib().mq_stack_workspace_bytes(ctypes.cast(arr, ctypes.c_void_p), n, 2)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+        h = mq.MqPlan()
+        st = mq.lib().mq_stack_plan(ctypes.cast(arr, ctypes.c_void_p), n, 2, ws.data_ptr(), nbytes, ctypes.byref(h),
+                                    ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        assert st == 0
+        ctypes.memset(arr, 0xFF, ctypes.sizeof(arr))             # the table is gone before anything has run
+        handles.append(h)
+        wss.append(ws)
+    for h in handles:
+        assert mq.lib().mq_linear_stack(ctypes.byref(h), ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)) == 0
+    torch.cuda.synchronize()
+    for y in ys:
+        assert torch.equal(y, ys[0])
+    check_layer(ys[0], hostA[1], hostA[1]["r"], "stack of 40 from a rewritten host table")
+
+
+def test_stack_plan_and_run_inside_a_hip_graph():
+    # neither call copies, synchronises or allocates: both can be recorded, and every replay gives the eager bits
+    host, layers = _stack([(256, 512, 2), (200, 1280, 3), (64, 128, 8), (512, 256, 6)], M=1, seed=103)
+    eager = mq.mq_stack_plan(layers, 1)
+    mq.mq_linear_stack(eager)
+    torch.cuda.synchronize()
+    want = [lay["y"].clone() for lay in layers]
+    ws = torch.empty_like(eager.ws)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            plan = mq.mq_stack_plan(layers, 1, ws=ws, stream=side)
+            mq.mq_linear_stack(plan, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for lay in layers:
+            lay["y"].fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for i, (lay, w) in enumerate(zip(layers, want)):
+            assert torch.equal(lay["y"], w), (rep, i)

@@ -258,24 +258,84 @@ def test_workspace_and_stack_validation():
     assert need > 0
     assert L.mq_stack_workspace_bytes(p, 0, 1) == 0
     assert L.mq_stack_workspace_bytes(None, 2, 1) == 0
-    assert L.mq_stack_plan(None, 2, 1, FAKE, need, None) == _st("MQ_ERR_NULL")
-    assert L.mq_stack_plan(p, 2, 1, None, need, None) == _st("MQ_ERR_NULL")
-    assert L.mq_stack_plan(p, 0, 1, FAKE, need, None) == _st("MQ_ERR_BAD_SHAPE")
-    assert L.mq_stack_plan(p, 2, 1, FAKE + 32, need, None) == _st("MQ_ERR_ALIGN")
-    assert L.mq_stack_plan(p, 2, 1, FAKE, need - 1, None) == _st("MQ_ERR_BUF_TOO_SMALL")
+    h = mq.MqPlan()
+    hp = ctypes.byref(h)
+    assert L.mq_stack_plan(None, 2, 1, FAKE, need, hp, None) == _st("MQ_ERR_NULL")
+    assert L.mq_stack_plan(p, 2, 1, None, need, hp, None) == _st("MQ_ERR_NULL")
+    assert L.mq_stack_plan(p, 2, 1, FAKE, need, None, None) == _st("MQ_ERR_NULL")
+    assert L.mq_stack_plan(p, 0, 1, FAKE, need, hp, None) == _st("MQ_ERR_BAD_SHAPE")
+    assert L.mq_stack_plan(p, 2, 1, FAKE + 32, need, hp, None) == _st("MQ_ERR_ALIGN")
+    assert L.mq_stack_plan(p, 2, 1, FAKE, need - 1, hp, None) == _st("MQ_ERR_BUF_TOO_SMALL")
     lay[1].r = 5
-    assert L.mq_stack_plan(p, 2, 1, FAKE, need, None) == _st("MQ_ERR_BAD_R")
+    assert L.mq_stack_plan(p, 2, 1, FAKE, need, hp, None) == _st("MQ_ERR_BAD_R")
     lay[1].r = 3
     lay[1].x = None
-    assert L.mq_stack_plan(p, 2, 1, FAKE, need, None) == _st("MQ_ERR_NULL")
+    assert L.mq_stack_plan(p, 2, 1, FAKE, need, hp, None) == _st("MQ_ERR_NULL")
     assert L.mq_linear_stack(None, None) == _st("MQ_ERR_NULL")
     lay[1].x = FAKE
     lay[1].from_parent = 1                        # layers of one stack must agree
-    assert L.mq_stack_plan(p, 2, 1, FAKE, need, None) == _st("MQ_ERR_UNSUPPORTED")
+    assert L.mq_stack_plan(p, 2, 1, FAKE, need, hp, None) == _st("MQ_ERR_UNSUPPORTED")
     lay[0].from_parent = 1
-    assert L.mq_stack_plan(p, 2, 8, FAKE, 1 << 40, None) == _st("MQ_ERR_UNSUPPORTED")   # batch above the ALU path
+    assert L.mq_stack_plan(p, 2, 8, FAKE, 1 << 40, hp, None) == _st("MQ_ERR_UNSUPPORTED")   # batch above the ALU path
     lay[0].from_parent = lay[1].from_parent = 2
-    assert L.mq_stack_plan(p, 2, 1, FAKE, need, None) == _st("MQ_ERR_UNSUPPORTED")
+    assert L.mq_stack_plan(p, 2, 1, FAKE, need, hp, None) == _st("MQ_ERR_UNSUPPORTED")
+    assert bytes(h) == bytes(ctypes.sizeof(h))    # a refused plan leaves the caller's header untouched
+
+
+def test_stack_run_refuses_a_header_that_no_plan_filled():
+    # mq_linear_stack takes everything it knows from the caller's host header and checks it before any launch:
+    # zeroes, garbage and a copy with one field changed are "not a plan", not a launch on whatever the bytes say
+    L = mq.lib()
+    h = mq.MqPlan()
+    assert L.mq_linear_stack(ctypes.byref(h), None) == _st("MQ_ERR_BAD_SHAPE")
+    rng = np.random.default_rng(0)
+    for _ in range(20):
+        for i in range(16):
+            h.opaque[i] = int(rng.integers(0, 1 << 63))
+        assert L.mq_linear_stack(ctypes.byref(h), None) == _st("MQ_ERR_BAD_SHAPE")
+    h.opaque[0] = 0x4d51504c414e3037              # the right magic alone is not enough
+    assert L.mq_linear_stack(ctypes.byref(h), None) == _st("MQ_ERR_BAD_SHAPE")
+
+
+def test_header_states_the_conventions_the_library_keeps():
+    text = " ".join(open(HEADER).read().replace("*", " ").split())
+    for phrase in ("never allocates or frees", "never synchronises", "keeps no state of its own",
+                   "neither read nor cleared"):
+        assert phrase in text, phrase
+    # and the sources hold none of the calls that would break them
+    csrc = os.path.join(ROOT, "paper_2602_03537_amd", "csrc")
+    banned = ("hipMalloc", "hipFree", "hipMemcpy", "hipMemset", "hipStreamSynchronize", "hipDeviceSynchronize",
+              "hipGetLastError", "hipEventSynchronize", "unordered_map", "std::map")
+    for name in sorted(os.listdir(csrc)):
+        if not name.endswith((".hip", ".h")):
+            continue
+        src = open(os.path.join(csrc, name)).read()
+        code = re.sub(r"//[^\n]*|/\*.*?\*/", "", src, flags=re.S)
+        for b in banned:
+            assert b not in code, (name, b)
+
+
+def test_slice_rejects_partial_overlap():
+    L = mq.lib()
+    assert L.mq_slice_codes(FAKE, 100, 8, 4, FAKE + 50, None) == _st("MQ_ERR_UNSUPPORTED")
+    assert L.mq_slice_codes(FAKE + 50, 100, 8, 4, FAKE, None) == _st("MQ_ERR_UNSUPPORTED")
+
+
+def test_linear_plain_validation():
+    L = mq.lib()
+    need = L.mq_linear_plain_workspace_bytes(1, 64, 128, 4)
+    assert need >= L.mq_workspace_bytes(1, 64, 128, 4) + 2 * L.mq_meta_bytes(64, 128, 128)
+    assert L.mq_linear_plain_workspace_bytes(1, 64, 100, 4) == 0 and L.mq_linear_plain_workspace_bytes(1, 64, 128, 5) == 0
+
+    def call(x=FAKE, M=1, W=FAKE, s=FAKE, z=FAKE, N=64, K=128, r=4, group=128, y=FAKE, ws=FAKE, wsb=None):
+        return L.mq_linear_plain(x, M, W, s, z, N, K, r, group, y, ws, need if wsb is None else wsb, None)
+    assert call(s=None) == _st("MQ_ERR_NULL") and call(z=None) == _st("MQ_ERR_NULL") and call(ws=None) == _st("MQ_ERR_NULL")
+    assert call(x=None) == _st("MQ_ERR_NULL") and call(W=None) == _st("MQ_ERR_NULL") and call(y=None) == _st("MQ_ERR_NULL")
+    assert call(r=5) == _st("MQ_ERR_BAD_R")
+    assert call(M=0) == _st("MQ_ERR_BAD_SHAPE") and call(M=257) == _st("MQ_ERR_BAD_SHAPE")
+    assert call(K=192) == _st("MQ_ERR_BAD_GROUP") and call(group=64) == _st("MQ_ERR_BAD_GROUP")
+    assert call(ws=FAKE + 64) == _st("MQ_ERR_ALIGN") and call(W=FAKE + 8) == _st("MQ_ERR_ALIGN")
+    assert call(wsb=need - 1) == _st("MQ_ERR_BUF_TOO_SMALL")
 
 
 # ------------------------------------------------------------ input recipe
