@@ -11,7 +11,8 @@
  *   - All data pointers are DEVICE pointers owned by the caller unless the
  *     argument is marked "host".  The library never allocates or frees device
  *     memory, never copies between host and device, never synchronises and
- *     keeps no state of its own between calls: every call enqueues kernels on
+ *     keeps no state of its own between calls (mq_linear_noalloc's static
+ *     scratch array aside): every call enqueues kernels on
  *     `stream` (a hipStream_t passed as void*, NULL = the default stream) and
  *     returns.  Host arrays (layer tables, job lists, lambda) are consumed
  *     before the call returns.  Every call may be recorded into a HIP graph.
@@ -61,6 +62,9 @@ typedef uint16_t mq_half; /* IEEE binary16 bits */
 #define MQ_ROW_BLOCK 64
 #define MQ_GROUP 128
 #define MQ_MAX_M 256
+/* Bytes of device memory mq_linear_noalloc works in: a static array inside the library's code
+ * object, held by every GPU the library runs on until the process ends. */
+#define MQ_NOALLOC_SCRATCH_BYTES (8u << 20)
 
 const char *mq_status_str(int status);
 int mq_version(void);
@@ -237,6 +241,25 @@ mq_status mq_matgptq_quantize(float *W, int64_t ldw, int64_t N, int64_t K, const
 mq_status mq_linear(const mq_half *x, int64_t M, const void *packed_W, const mq_half *scales_t,
                     const mq_half *zeros_t, int64_t N, int64_t K, int r, int group, mq_half *y,
                     void *ws, size_t ws_bytes, mq_stream stream);
+
+/* mq_linear for callers that cannot allocate and have no workspace to hand over: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and results
+ * as mq_linear (to rounding: the split-K shares may be cut differently), but the counters, the
+ * split-K partial sums and, for M > 4, the prepared activations live in a static device array of
+ * MQ_NOALLOC_SCRATCH_BYTES inside the library instead of a caller's `ws`.  The call allocates
+ * nothing, frees nothing and initialises what it needs itself (one small fill kernel ahead of the
+ * layer's launches, all on `stream`).
+ *   1 <= M <= 16; larger batches return MQ_ERR_UNSUPPORTED (their partial sums alone exceed the array).
+ *   Shapes whose counters + prepared activations + at least 256 partial-sum slot pairs do not fit
+ *   the array return MQ_ERR_BUF_TOO_SMALL (every Llama-2-7B and Llama-3-70B linear fits at M <= 16).
+ * Every call on a GPU uses that GPU's one array: two calls that may overlap in time on the same
+ * GPU (different streams, or graphs replayed concurrently) race; calls on one stream do not.  The
+ * device current to the calling thread must be the stream's device.  The first call on a device
+ * looks the array's address up (a host-side query): make it outside stream capture.
+ * Other arguments, results and errors as mq_linear. */
+mq_status mq_linear_noalloc(const mq_half *x, int64_t M, const void *packed_W, const mq_half *scales_t,
+                            const mq_half *zeros_t, int64_t N, int64_t K, int r, int group, mq_half *y,
+                            mq_stream stream);
 
 /* The call shape of the paper's kernel interface (Section 4: activations, packed weights, scales,
  * zero-offsets in, y out) for callers that keep the quantiser's own [N, K/group] arrays: scales and

@@ -15,13 +15,14 @@ __all__ = [
     "mq_slice_pack", "mq_reslice", "mq_reslice_many", "MqResliceJob", "mq_linear_from_parent", "mq_quant_matgptq",
     "mq_matgptq_workspace_bytes", "mq_matgptq_quantize",
     "mq_stack_workspace_bytes", "mq_stack_plan", "mq_linear_stack", "MqLayer", "MqPlan", "StackPlan",
-    "mq_linear_plain", "mq_linear_plain_workspace_bytes",
+    "mq_linear_plain", "mq_linear_plain_workspace_bytes", "mq_linear_noalloc", "MQ_NOALLOC_SCRATCH_BYTES",
     "new_workspace", "prepare_layer",
 ]
 
 MQ_ROW_BLOCK = 64
 MQ_GROUP = 128
 MQ_MAX_M = 256
+MQ_NOALLOC_SCRATCH_BYTES = 8 << 20
 STATUS = {
     0: "MQ_OK", 1: "MQ_ERR_NULL", 2: "MQ_ERR_BAD_R", 3: "MQ_ERR_BAD_SHAPE", 4: "MQ_ERR_BAD_GROUP",
     5: "MQ_ERR_ALIGN", 6: "MQ_ERR_BUF_TOO_SMALL", 7: "MQ_ERR_HIP", 8: "MQ_ERR_UNSUPPORTED",
@@ -111,6 +112,7 @@ def lib():
         "mq_stack_workspace_bytes": (sz, [vp, i32, i64]),
         "mq_stack_plan": (i32, [vp, i32, i64, vp, sz, vp, vp]),
         "mq_linear_stack": (i32, [vp, vp]),
+        "mq_linear_noalloc": (i32, [vp, i64, vp, vp, vp, i64, i64, i32, i32, vp, vp]),
         "mq_linear_plain_workspace_bytes": (sz, [i64, i64, i64, i32]),
         "mq_linear_plain": (i32, [vp, i64, vp, vp, vp, i64, i64, i32, i32, vp, vp, sz, vp]),
     }
@@ -218,6 +220,14 @@ def mq_linear(x, packed_W, scales_t, zeros_t, N: int, K: int, r: int, group: int
         y = torch.empty((M, N), dtype=torch.float16, device=x.device)
     _check(lib().mq_linear(_ptr(x), M, _ptr(packed_W), _ptr(scales_t), _ptr(zeros_t), N, K, r, group, _ptr(y),
                            _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "mq_linear")
+    return y
+
+
+def mq_linear_noalloc(x, packed_W, scales_t, zeros_t, N: int, K: int, r: int, group: int, y, stream=None):
+    """mq_linear without a workspace: the library's static scratch array serves.  y must be given (this wrapper
+    allocates nothing either)."""
+    _check(lib().mq_linear_noalloc(_ptr(x), x.shape[0], _ptr(packed_W), _ptr(scales_t), _ptr(zeros_t), N, K, r, group,
+                                   _ptr(y), _stream(stream)), "mq_linear_noalloc")
     return y
 
 

@@ -3,6 +3,7 @@
 #include <climits>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "mq_internal.h"
@@ -132,6 +133,29 @@ struct PlanHeader {
 static_assert(sizeof(PlanHeader) <= sizeof(mq_plan), "the header must fit the caller's handle");
 constexpr uint64_t kPlanMagic = 0x4d51504c414e3037ull;  // "MQPLAN07"
 
+// ---- scratch of mq_linear_noalloc: device memory that exists without anybody allocating it.
+// The array's name is only a host-side stand-in; its device address is looked up once per device (each device
+// holds its own copy at its own address) and only that pointer is ever handed to a kernel.
+constexpr size_t kScratchBytes = MQ_NOALLOC_SCRATCH_BYTES;
+constexpr size_t kNoallocMinWorkers = 256;  // fewer schedule shares than this would leave most of the chip idle
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+mq_status scratch_of_current_device(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MQ_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MQ_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return MQ_OK;
+}
+
 uint64_t plan_check(const PlanHeader &h) {
     PlanHeader t = h;
     t.check = 0;
@@ -163,17 +187,22 @@ PlanLayout plan_layout(const mq_layer *layers, int n_layers, int64_t M) {
 }
 
 // One layer on its own workspace: [counters][partial sums][prepared activations]
-mq_status run_single(const mq_layer &l, int64_t M, void *ws, size_t ws_bytes, mq_stream stream) {
+// worker_cap: 0 = the workspace has mq_workspace_bytes; else it holds partial-sum slots for that many schedule
+// shares only ([counters][worker_cap slots pairs][prepared activations], checked by the caller) and the launch keeps
+// to them.  M <= kNarrowMaxM when capped.
+mq_status run_single(const mq_layer &l, int64_t M, void *ws, size_t ws_bytes, mq_stream stream, int worker_cap = 0) {
     if (!ws) return MQ_ERR_NULL;
     if (mq_status st = layer_status(l, M)) return st;
     if (!aligned(ws, 256)) return MQ_ERR_ALIGN;
     const int r_ws = l.from_parent ? kC : l.r;
-    if (ws_bytes < mq_workspace_bytes(M, l.N, l.K, r_ws)) return MQ_ERR_BUF_TOO_SMALL;
+    if (!worker_cap && ws_bytes < mq_workspace_bytes(M, l.N, l.K, r_ws)) return MQ_ERR_BUF_TOO_SMALL;
 
     char *base = static_cast<char *>(ws);
     const size_t cnt_b = counter_bytes(counters_of(M, l.N));
-    char *act = base + cnt_b + partial_bytes(M);
+    const size_t part_b = worker_cap ? (size_t)worker_cap * 2 * (size_t)slot_floats(M) * sizeof(float) : partial_bytes(M);
+    char *act = base + cnt_b + part_b;
     StackParams p{};
+    p.worker_cap = worker_cap;
     p.table = nullptr;
     p.n_layers = 1;
     p.single = make_desc(l, M, M, 0, 0, 0, use_mfma(M) ? act : nullptr, use_mfma(M) ? act + xt_bytes(M, l.K, l.r) : nullptr);
@@ -188,7 +217,7 @@ mq_status run_single(const mq_layer &l, int64_t M, void *ws, size_t ws_bytes, mq
         e = launch_stack_wide(p, p.single.cost, (hipStream_t)stream);
     else if (use_mfma(M))
         e = launch_stack_mfma(p, p.single.cost, (hipStream_t)stream);
-    else if (linear_rb_fits(p.single, partial_bytes(M)))
+    else if (linear_rb_fits(p.single, part_b))
         e = launch_linear_rb(p.single, p.part, p.cnt, (hipStream_t)stream);
     else
         e = launch_stack(p, p.single.cost, l.from_parent != 0, (hipStream_t)stream);
@@ -508,6 +537,26 @@ mq_status mq_linear_stack(const mq_plan *plan, mq_stream stream) {
                                                                        (hipStream_t)stream)
                                               : launch_stack(p, h.max_cost, h.from_parent != 0, (hipStream_t)stream);
     return e == hipSuccess ? MQ_OK : MQ_ERR_HIP;
+}
+
+mq_status mq_linear_noalloc(const mq_half *x, int64_t M, const void *packed_W, const mq_half *scales_t,
+                            const mq_half *zeros_t, int64_t N, int64_t K, int r, int group, mq_half *y, mq_stream stream) {
+    const mq_layer l{packed_W, scales_t, zeros_t, x, y, N, K, r, group, 0, 0};
+    if (mq_status st = layer_status(l, M)) return st;
+    if (M > kNarrowMaxM) return MQ_ERR_UNSUPPORTED;  // the wide path's slots alone exceed the scratch array
+    // [counters][slot pairs for `cap` schedule shares][prepared activations] must fit the array
+    const size_t cnt_b = counter_bytes(counters_of(M, N));
+    const size_t act_b = xt_bytes(M, K, r) + xsum_bytes(M, K);
+    const size_t pair_b = 2 * (size_t)slot_floats(M) * sizeof(float);
+    if (cnt_b + act_b + kNoallocMinWorkers * pair_b > kScratchBytes) return MQ_ERR_BUF_TOO_SMALL;
+    size_t cap = (kScratchBytes - cnt_b - act_b) / pair_b;
+    const size_t most = use_mfma(M) ? (size_t)kMaxWavesMfma : (size_t)max_workers_valu(M);
+    if (cap > most) cap = most;
+    void *ws = nullptr;
+    if (mq_status st = scratch_of_current_device(&ws)) return st;
+    // the array keeps the last call's contents, laid out for that call's shape: this call's counters start at zero
+    if (launch_fill_zero(ws, cnt_b, (hipStream_t)stream) != hipSuccess) return MQ_ERR_HIP;
+    return run_single(l, M, ws, kScratchBytes, stream, (int)cap);
 }
 
 size_t mq_linear_plain_workspace_bytes(int64_t M, int64_t N, int64_t K, int r) {

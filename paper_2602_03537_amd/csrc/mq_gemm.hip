@@ -380,8 +380,9 @@ static int gemm_resident_waves() {
 }
 
 hipError_t launch_stack_mfma(StackParams p, int max_cost, hipStream_t s) {
-    const int hw = gemm_resident_waves();
+    int hw = gemm_resident_waves();
     if (hw <= 0) return hipErrorUnknown;
+    if (p.worker_cap && hw > p.worker_cap) hw = p.worker_cap;
     // shares of at least four tiles: with one tile per wave a small layer (a 4096 x 4096 one has 2048 tiles) hands
     // every row block over between as many waves as it has groups, which costs more than the parallelism gains
     // (measured on the Llama-2-7B shapes at M = 8: 26 -> 19 us per call)

@@ -79,6 +79,7 @@ struct StackParams {
     int32_t M;
     int32_t slot_floats;     // floats per partial-sum slot (64*M, or 64*16 on the MFMA path)
     int32_t n_jobs;          // prep kernel jobs (MFMA path)
+    int32_t worker_cap;      // 0, or: `part` holds slots for this many schedule shares only (a small workspace)
     LayerDesc single;
 };
 

@@ -440,7 +440,9 @@ template <int M, int XP, bool SL> static bool residency(int &cus, int &blocks) {
 template <int M, int XP, bool SL> static hipError_t launch_stack_mx(StackParams p, int max_cost, hipStream_t s) {
     int cus = 0, blocks = 0;
     if (!residency<M, XP, SL>(cus, blocks)) return hipErrorUnknown;
-    const int hw = cus * blocks * 4;
+    int hw = cus * blocks * 4;
+    if (p.worker_cap && hw > p.worker_cap) hw = p.worker_cap;
+    const uint64_t max_workers = p.worker_cap ? (uint64_t)p.worker_cap : (uint64_t)max_workers_valu(M);
     // every share must be at least one tile long, so that each share between the first
     // and last contributor of a row block really owns a tile of it
     uint64_t cap = p.cost_total / (uint64_t)max_cost;
@@ -456,7 +458,7 @@ template <int M, int XP, bool SL> static hipError_t launch_stack_mx(StackParams 
     // best with one share per wave, Llama-3-70B stacks gain 15 % from eight).
     uint64_t spw = p.cost_total / ((uint64_t)max_cost * 128 * (uint64_t)p.nwaves);  // whole shares per wave
     if (spw > (uint64_t)kSharesPerWave) spw = kSharesPerWave;
-    while (spw > 1 && spw * (uint64_t)p.nwaves > (uint64_t)max_workers_valu(M)) --spw;
+    while (spw > 1 && spw * (uint64_t)p.nwaves > max_workers) --spw;
     if (spw < 1) spw = 1;
     p.nworkers = (int)(spw * (uint64_t)p.nwaves);
     const unsigned nblocks = (unsigned)((p.nwaves + 3) / 4);
