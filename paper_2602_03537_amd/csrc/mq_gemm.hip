@@ -144,7 +144,7 @@ template <int R> struct GemmCtx {
         const u32x4 MQ_GLOBAL *src = gl(reinterpret_cast<const u32x4 *>(L.Wp) + (size_t)u * (R * 64) + lane);
 #pragma unroll
         for (int i = 0; i < R; ++i) {
-            const u32x4 v = src[i * 64];
+            const u32x4 v = __builtin_nontemporal_load(src + i * 64);  // read once per call: streaming hint
             w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
         }
     }
@@ -299,7 +299,10 @@ __device__ __forceinline__ void run_gemm_units(const LayerDesc &L, const StackPa
             const u32x2 MQ_GLOBAL *sp = gl(reinterpret_cast<const u32x2 *>(L.st + (size_t)u * 64 + lm.rowbase));
             const u32x2 MQ_GLOBAL *zp = gl(reinterpret_cast<const u32x2 *>(L.zt + (size_t)u * 64 + lm.rowbase));
 #pragma unroll
-            for (int q = 0; q < 4; ++q) { s4[q] = sp[2 * q]; z4[q] = zp[2 * q]; }
+            for (int q = 0; q < 4; ++q) {
+                s4[q] = __builtin_nontemporal_load(sp + 2 * q);
+                z4[q] = __builtin_nontemporal_load(zp + 2 * q);
+            }
             const float xg = gl(L.xsum)[(size_t)(c * L.G + g) * kChunkCols + lm.col];
             __builtin_amdgcn_sched_barrier(0);  // keep the loads up here, ahead of the math
             gemm_tile_math<R>(cx, w[j], st, s4, z4, xg, yacc);

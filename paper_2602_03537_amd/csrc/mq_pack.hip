@@ -123,10 +123,12 @@ template <int R> __device__ __forceinline__ uint32_t slice_pair_index(uint32_t v
 template <int R>
 __device__ __forceinline__ void reslice_tile(const uint4 *__restrict__ src, uint4 *__restrict__ dst) {
     using T = Layout<R>;
+    // both sides are touched once: non-temporal (streaming) loads and stores
+    typedef uint32_t v4u __attribute__((ext_vector_type(4)));
     uint32_t q[4 * kC];
 #pragma unroll
     for (int i = 0; i < kC; ++i) {
-        const uint4 v = src[i * 64];
+        const v4u v = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src) + i * 64);
         q[4 * i] = v.x; q[4 * i + 1] = v.y; q[4 * i + 2] = v.z; q[4 * i + 3] = v.w;
     }
     uint32_t dw[4 * R];
@@ -147,7 +149,10 @@ __device__ __forceinline__ void reslice_tile(const uint4 *__restrict__ src, uint
         });
     });
 #pragma unroll
-    for (int i = 0; i < R; ++i) dst[i * 64] = make_uint4(dw[4 * i], dw[4 * i + 1], dw[4 * i + 2], dw[4 * i + 3]);
+    for (int i = 0; i < R; ++i) {
+        const v4u v = {dw[4 * i], dw[4 * i + 1], dw[4 * i + 2], dw[4 * i + 3]};
+        __builtin_nontemporal_store(v, reinterpret_cast<v4u *>(dst) + i * 64);
+    }
 }
 
 template <int R>

@@ -358,33 +358,49 @@ __device__ __forceinline__ void finish_row_block_blocked(const LayerDesc &L, con
 // N consecutive 1 KB lines (16 bytes per lane each): lane addresses src_lane + i * 1024 -> LDS dst_wave + i * 1024.
 // The instruction offset of global_load_lds applies to the global and to the LDS address alike, so four
 // lines share one address register pair and one setting of M0 (the LDS base of the wave's transfer).
-template <int N> __device__ __forceinline__ void dma_lines(const uint8_t *src_lane, MQ_LDS uint8_t *dst_wave) {
+// NT: non-temporal (streaming) transfers for data that is read once per call -- the weights, scales and zeros; the
+// activations are shared by every workgroup and stay ordinary transfers.
+template <int N, bool NT = false>
+__device__ __forceinline__ void dma_lines(const uint8_t *src_lane, MQ_LDS uint8_t *dst_wave) {
     static_assert(N >= 1 && N <= 8, "one or two blocks of up to four lines");
     const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst_wave);
     const uint8_t MQ_GLOBAL *src = gl(src_lane);
     constexpr int N0 = N < 4 ? N : 4;
-    if constexpr (N0 == 1)
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(src) : "memory");
-    else if constexpr (N0 == 2)
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\t"
-                     "global_load_lds_dwordx4 %1, off offset:1024" ::"s"(base), "v"(src) : "memory");
-    else if constexpr (N0 == 3)
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\t"
-                     "global_load_lds_dwordx4 %1, off offset:1024\n\tglobal_load_lds_dwordx4 %1, off offset:2048" ::"s"(base),
-                     "v"(src)
+#define MQ_DMA_LINES(POL)                                                                                              \
+    if constexpr (N0 == 1)                                                                                             \
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" POL ::"s"(base), "v"(src)         \
+                     : "memory");                                                                                      \
+    else if constexpr (N0 == 2)                                                                                        \
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" POL "\n\t"                        \
+                     "global_load_lds_dwordx4 %1, off offset:1024" POL ::"s"(base),                                    \
+                     "v"(src)                                                                                          \
+                     : "memory");                                                                                      \
+    else if constexpr (N0 == 3)                                                                                        \
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" POL "\n\t"                        \
+                     "global_load_lds_dwordx4 %1, off offset:1024" POL "\n\t"                                          \
+                     "global_load_lds_dwordx4 %1, off offset:2048" POL ::"s"(base),                                    \
+                     "v"(src)                                                                                          \
+                     : "memory");                                                                                      \
+    else                                                                                                               \
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" POL "\n\t"                        \
+                     "global_load_lds_dwordx4 %1, off offset:1024" POL "\n\t"                                          \
+                     "global_load_lds_dwordx4 %1, off offset:2048" POL "\n\t"                                          \
+                     "global_load_lds_dwordx4 %1, off offset:3072" POL ::"s"(base),                                    \
+                     "v"(src)                                                                                          \
                      : "memory");
-    else
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\t"
-                     "global_load_lds_dwordx4 %1, off offset:1024\n\tglobal_load_lds_dwordx4 %1, off offset:2048\n\t"
-                     "global_load_lds_dwordx4 %1, off offset:3072" ::"s"(base),
-                     "v"(src)
-                     : "memory");
-    if constexpr (N > 4) dma_lines<N - 4>(src_lane + 4096, dst_wave + 4096);
+    if constexpr (NT) {
+        MQ_DMA_LINES(" nt")
+    } else {
+        MQ_DMA_LINES("")
+    }
+#undef MQ_DMA_LINES
+    if constexpr (N > 4) dma_lines<N - 4, NT>(src_lane + 4096, dst_wave + 4096);
 }
 // block B (four lines each, the last one shorter) of an N-line transfer
-template <int N, int B> __device__ __forceinline__ void dma_block(const uint8_t *src_lane, MQ_LDS uint8_t *dst_wave) {
+template <int N, int B, bool NT = false>
+__device__ __forceinline__ void dma_block(const uint8_t *src_lane, MQ_LDS uint8_t *dst_wave) {
     static_assert(4 * B < N, "no such block");
-    dma_lines<(N - 4 * B < 4 ? N - 4 * B : 4)>(src_lane + 4096 * B, dst_wave + 4096 * B);
+    dma_lines<(N - 4 * B < 4 ? N - 4 * B : 4), NT>(src_lane + 4096 * B, dst_wave + 4096 * B);
 }
 // acc += A * B with the accumulator pinned to the accumulation registers: the C * 32 accumulators of a
 // wave live there for a whole row block and no vector instruction touches them in between (left to
@@ -488,11 +504,11 @@ __device__ __forceinline__ void run_wide_units(const LayerDesc &L, const StackPa
         const size_t tile = (size_t)rb * G + g_pf;
         MQ_LDS uint8_t *dst = ring + slot * kSlot;
         if constexpr (piece < kWBlocks) {
-            dma_block<R, piece>(reinterpret_cast<const uint8_t *>(L.Wp) + tile * (R * 1024) + lane * 16, dst);
+            dma_block<R, piece, true>(reinterpret_cast<const uint8_t *>(L.Wp) + tile * (R * 1024) + lane * 16, dst);
         } else if constexpr (piece == kWBlocks) {
-            if (lane < 8) dma_lines<1>(reinterpret_cast<const uint8_t *>(L.st) + tile * 128 + lane * 16, dst + R * 1024);
+            if (lane < 8) dma_lines<1, true>(reinterpret_cast<const uint8_t *>(L.st) + tile * 128 + lane * 16, dst + R * 1024);
         } else {
-            if (lane < 8) dma_lines<1>(reinterpret_cast<const uint8_t *>(L.zt) + tile * 128 + lane * 16, dst + R * 1024 + 128);
+            if (lane < 8) dma_lines<1, true>(reinterpret_cast<const uint8_t *>(L.zt) + tile * 128 + lane * 16, dst + R * 1024 + 128);
             if (n_pf > 1) {
                 --n_pf;
                 if (++g_pf == G) { g_pf = 0; ++s_pf; }
