@@ -88,6 +88,16 @@ size_t mq_workspace_bytes(int64_t M, int64_t N, int64_t K, int r);
  * ws: device, 256-byte aligned. */
 mq_status mq_workspace_init(void *ws, size_t ws_bytes, mq_stream stream);
 
+/* ---------------------------------------------------------------- measurement aid
+ * What a plain streaming read achieves on this device: every wavefront reads a contiguous share of
+ * `buf` with non-temporal 16-byte loads (the access pattern of the linear kernels' weight stream,
+ * with no arithmetic behind it) and the xor of all 32-bit words read is xor-ed into *out.  Timed by
+ * the caller on a buffer well beyond the last-level cache, it gives the read bandwidth the kernels
+ * are measured against, next to the published HBM peak.
+ *   buf : device, 16-byte aligned, bytes > 0 and a multiple of 16;   out : device, one uint32
+ * Errors: NULL, BAD_SHAPE, ALIGN, HIP. */
+mq_status mq_read_probe(const void *buf, size_t bytes, uint32_t *out, mq_stream stream);
+
 /* ---------------------------------------------------------------- slicing
  * Eq. 1 (Section 2): S = clamp(round(q / 2^(c-r)), 0, 2^r - 1) * 2^(c-r),
  * rounding half up (Section 3.1 "Slicing": the next lower bit alone decides),

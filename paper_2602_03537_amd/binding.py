@@ -15,7 +15,7 @@ __all__ = [
     "mq_slice_pack", "mq_reslice", "mq_reslice_many", "MqResliceJob", "mq_linear_from_parent", "mq_quant_matgptq",
     "mq_matgptq_workspace_bytes", "mq_matgptq_quantize",
     "mq_stack_workspace_bytes", "mq_stack_plan", "mq_linear_stack", "MqLayer", "MqPlan", "StackPlan",
-    "mq_linear_plain", "mq_linear_plain_workspace_bytes", "mq_linear_noalloc", "MQ_NOALLOC_SCRATCH_BYTES",
+    "mq_read_probe", "mq_linear_plain", "mq_linear_plain_workspace_bytes", "mq_linear_noalloc", "MQ_NOALLOC_SCRATCH_BYTES",
     "new_workspace", "prepare_layer",
 ]
 
@@ -112,6 +112,7 @@ def lib():
         "mq_stack_workspace_bytes": (sz, [vp, i32, i64]),
         "mq_stack_plan": (i32, [vp, i32, i64, vp, sz, vp, vp]),
         "mq_linear_stack": (i32, [vp, vp]),
+        "mq_read_probe": (i32, [vp, sz, vp, vp]),
         "mq_linear_noalloc": (i32, [vp, i64, vp, vp, vp, i64, i64, i32, i32, vp, vp]),
         "mq_linear_plain_workspace_bytes": (sz, [i64, i64, i64, i32]),
         "mq_linear_plain": (i32, [vp, i64, vp, vp, vp, i64, i64, i32, i32, vp, vp, sz, vp]),
@@ -221,6 +222,11 @@ def mq_linear(x, packed_W, scales_t, zeros_t, N: int, K: int, r: int, group: int
     _check(lib().mq_linear(_ptr(x), M, _ptr(packed_W), _ptr(scales_t), _ptr(zeros_t), N, K, r, group, _ptr(y),
                            _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "mq_linear")
     return y
+
+
+def mq_read_probe(buf, out, stream=None) -> None:
+    """xor of all 32-bit words of buf (uint8 tensor, a multiple of 16 bytes) is xor-ed into out (one int32/uint32)."""
+    _check(lib().mq_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _ptr(out), _stream(stream)), "mq_read_probe")
 
 
 def mq_linear_noalloc(x, packed_W, scales_t, zeros_t, N: int, K: int, r: int, group: int, y, stream=None):

@@ -59,7 +59,7 @@ size_t partial_bytes(int64_t M) {
 // MFMA paths: re-ordered activations and their group sums for one layer
 size_t xt_bytes(int64_t M, int64_t K, int r) {
     if (use_wide(M)) return align_up((size_t)wide_chunks_padded(M) * (size_t)(K / kGroup) * kWideXtBlockBytes, 256);
-    return use_mfma(M) ? (size_t)chunks(M) * (size_t)(K / kGroup) * (size_t)mfma_per_tile(r) * 256 : 0;
+    return use_mfma(M) ? (size_t)chunks(M) * (size_t)(K / kGroup) * (size_t)(mfma_per_tile(r) + 1) * 256 : 0;
 }
 size_t xsum_bytes(int64_t M, int64_t K) {
     if (use_wide(M)) return 0;  // the sums live inside the activation blocks
@@ -557,6 +557,13 @@ mq_status mq_linear_noalloc(const mq_half *x, int64_t M, const void *packed_W, c
     // the array keeps the last call's contents, laid out for that call's shape: this call's counters start at zero
     if (launch_fill_zero(ws, cnt_b, (hipStream_t)stream) != hipSuccess) return MQ_ERR_HIP;
     return run_single(l, M, ws, kScratchBytes, stream, (int)cap);
+}
+
+mq_status mq_read_probe(const void *buf, size_t bytes, uint32_t *out, mq_stream stream) {
+    if (!buf || !out) return MQ_ERR_NULL;
+    if (bytes == 0 || bytes % 16) return MQ_ERR_BAD_SHAPE;
+    if (!aligned(buf, 16) || !aligned(out, 4)) return MQ_ERR_ALIGN;
+    return launch_read_probe(buf, bytes, out, (hipStream_t)stream) == hipSuccess ? MQ_OK : MQ_ERR_HIP;
 }
 
 size_t mq_linear_plain_workspace_bytes(int64_t M, int64_t N, int64_t K, int r) {

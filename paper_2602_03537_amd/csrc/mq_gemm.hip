@@ -22,9 +22,21 @@
 //
 // A batch of more than 16 rows is served in chunks of 16 columns; a chunk is
 // scheduled like a layer of its own (chunk index slowest).
-// Per tile, group-local sums stay in one 32x32 accumulator per field key; per
-// group  y += scale * (2^(8-r) * D - zero * X_g)  in fp32, exactly as on the
-// vector-ALU path (integer codes stay exact, scales are never rounded to fp16).
+//
+// One accumulator per tile.  A masked field is the fp16 subnormal digit * 2^(p-24) and stands for
+// digit * 2^d of the code (p = position of the field in its half, d = first code bit it carries), so
+// fields with different p - d ("keys") would need accumulators of their own.  Instead the B operand
+// of each MFMA is the activations times 2^(e - (p - d)): every MFMA of a tile then adds
+// code-part * x * 2^(e-24) into the SAME 32x32 accumulator, and no vector instruction touches the
+// accumulator before the group is complete.  e is a block exponent chosen by the prep kernel per
+// (chunk, group, batch column) so that the largest |x| of the group lands in [2^14, 2^15): the scaling
+// is exact for every element within 2^-22 of the group's largest (smaller ones lose low bits worth
+// less than 2^-38 of the largest product: far below the fp32 accumulation itself).
+// The zero-offset rides on the matrix core as well: one more MFMA per tile multiplies the row's zero
+// (A = z * 2^(r-17), exact for every zero >= 2) by -X_g * 2^(e-15) split into three fp16 pieces
+// (relative error 2^-33), so that D = 2^(e+r-32) * sum_k x_k * (S_k - z).  Per group and accumulator
+// element what is left for the vector ALUs is  y += scale * (F * D),  F = 2^(32-r-e)  from the prep
+// kernel: integer codes stay exact and scales are never rounded to fp16, as on the vector-ALU path.
 #include "mq_device.h"
 
 namespace mq {
@@ -45,6 +57,16 @@ template <int R> struct Mfma {
 // One wave per (layer, chunk, group): writes the B operands of the NMF MFMAs of a tile
 // (16 columns x 8 halves each) and the per-column group sums X_g.  Branch-free: columns
 // beyond M read column 0 and are masked to zero, all loads are issued before the stores.
+template <int CTRL> __device__ __forceinline__ float dpp_max(float v) {
+    const int t = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false);
+    return fmaxf(v, __builtin_bit_cast(float, t));
+}
+// (x_lo, x_hi) * scale, a power of two, back to an fp16 pair (exact unless a result is subnormal)
+__device__ __forceinline__ uint32_t scale_pair(uint32_t v, float scale) {
+    const half2_t h = __builtin_bit_cast(half2_t, v);
+    const half2_t o = {(_Float16)((float)h.x * scale), (_Float16)((float)h.y * scale)};
+    return __builtin_bit_cast(uint32_t, o);
+}
 template <int R> __device__ __forceinline__ void xprep_job(const LayerDesc &L, int c, int g, int lane) {
     using T = Layout<R>;
     constexpr int NMF = Mfma<R>::NMF;
@@ -54,25 +76,50 @@ template <int R> __device__ __forceinline__ void xprep_job(const LayerDesc &L, i
     const uint32_t MQ_GLOBAL *xrow =
         gl(reinterpret_cast<const uint32_t *>(L.x + (size_t)(live ? col : 0) * L.K) + (size_t)g * 64);
     uint32_t MQ_GLOBAL *out =
-        gl(reinterpret_cast<uint32_t *>(const_cast<uint4 *>(L.xt)) + ((size_t)(c * L.G + g) * NMF) * 64 + lane);
+        gl(reinterpret_cast<uint32_t *>(const_cast<uint4 *>(L.xt)) + ((size_t)(c * L.G + g) * (NMF + 1)) * 64 + lane);
     uint32_t v[NMF];
     static_for<NMF>([&](auto mf) {
         constexpr int Q = mf / T::NOPS;
         constexpr Op o = T::op(mf % T::NOPS);
         // dword j of the lane's operand = activation pair of unit 4Q+j, field o
-        v[mf] = xrow[(4 * Q + j) * T::PPU + o.pair];
+        v[mf] = xrow[(4 * Q + j) * T::PPU + o.pair] & live;
     });
     uint32_t q[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) q[i] = xrow[j * 16 + i];
-    static_for<NMF>([&](auto mf) { out[mf * 64] = v[mf] & live; });
-    // X_g for column m: lanes 4m..4m+3 each sum a quarter of the group
-    float s = 0.f;
+    for (int i = 0; i < 16; ++i) q[i] = xrow[j * 16 + i] & live;
+    // X_g and the largest |x| of column m: lanes 4m..4m+3 each cover a quarter of the group
+    float s = 0.f, amax = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) s = dot2(q[i] & live, 0x3C003C00u, s);
+    for (int i = 0; i < 16; ++i) {
+        s = dot2(q[i], 0x3C003C00u, s);
+        const half2_t h = __builtin_bit_cast(half2_t, q[i] & 0x7FFF7FFFu);
+        amax = fmaxf(amax, fmaxf((float)h.x, (float)h.y));
+    }
     s = dpp_add<0xB1>(s);
     s = dpp_add<0x4E>(s);
-    if (j == 0) gl(const_cast<float *>(L.xsum))[(size_t)(c * L.G + g) * kChunkCols + m] = s;
+    amax = dpp_max<0xB1>(amax);
+    amax = dpp_max<0x4E>(amax);
+    // block exponent: amax * 2^e in [2^14, 2^15) (amax = 0 or subnormal: as if it were the smallest normal)
+    int ex = (int)((__builtin_bit_cast(uint32_t, amax) >> 23) & 0xFF) - 127;  // floor(log2(amax)) for normal fp32
+    if (ex < -14) ex = -14;
+    if (ex > 15) ex = 15;  // Inf / NaN in, garbage out, but no undefined shifts
+    const int e = 14 - ex;
+    const float base = __builtin_ldexpf(1.f, e);
+    static_for<NMF>([&](auto mf) {
+        constexpr Op o = T::op(mf % T::NOPS);
+        constexpr int key = ctz16(o.mask) - o.d;
+        out[mf * 64] = scale_pair(v[mf], base * __builtin_ldexpf(1.f, -key));
+    });
+    // the zero-offset block: -X_g * 2^(e-15) in three fp16 pieces (hi, mid, lo), then zeros
+    const float xs = -s * base * 0x1p-15f;
+    const _Float16 p0 = (_Float16)xs;
+    const float r1 = xs - (float)p0;
+    const _Float16 p1 = (_Float16)r1;
+    const _Float16 p2 = (_Float16)(r1 - (float)p1);
+    const half2_t d0 = {p0, p1}, d1 = {p2, (_Float16)0.f};
+    out[NMF * 64] = j == 0 ? __builtin_bit_cast(uint32_t, d0) : j == 1 ? __builtin_bit_cast(uint32_t, d1) : 0u;
+    // F = 2^(32 - r - e): what turns the accumulator back into code units times Eq. 1's rescale
+    if (j == 0) gl(const_cast<float *>(L.xsum))[(size_t)(c * L.G + g) * kChunkCols + m] = __builtin_ldexpf(1.f, 32 - R - e);
 }
 
 __global__ __launch_bounds__(256) void xprep_kernel(const StackParams p) {
@@ -119,7 +166,7 @@ __device__ __forceinline__ LaneMap lane_map(int lane) {
 
 // Per-wave LDS: two stages of prepared activations (the B operands of one tile each) so
 // that B is read just in time with ds_read instead of being held in 64..80 registers.
-constexpr int kStageBytes = 5 * 1024;                 // >= NMF * 256 for every width (NMF <= 20)
+constexpr int kStageBytes = 6 * 1024;                 // >= (NMF + 1) * 256 for every width (NMF <= 20)
 constexpr int kWaveLds = 2 * kStageBytes;
 constexpr int kZeroOff = 4 * kWaveLds;                // 16 zero bytes after the four waves' stages
 constexpr int kLdsBytes = kZeroOff + 16;
@@ -132,7 +179,8 @@ __device__ __forceinline__ float half_of(u32x2 v, int e) {
 
 template <int R> struct GemmCtx {
     using MF = Mfma<R>;
-    static constexpr int NXL = (MF::NMF * 256 + 1023) / 1024;  // 1 KiB wave-loads per tile of activations
+    static constexpr int NBLK = MF::NMF + 1;                // operand blocks per tile: the MFMAs' and the zero-offset's
+    static constexpr int NXL = (NBLK * 256 + 1023) / 1024;  // 1 KiB wave-loads per tile of activations
     const LayerDesc &L;
     const LaneMap lm;
     const int lane, c;
@@ -154,7 +202,7 @@ template <int R> struct GemmCtx {
     // activation traffic, which is as large as a 4-bit weight tile, is never requested).
     __device__ __forceinline__ void load_x(u32x4 (&xb)[NXL], int g) const {
         const bool live = c * kChunkCols + (lane & 15) < L.M;
-        const uint32_t off = live ? (uint32_t)(c * L.G + g) * (MF::NMF * 256u) + (uint32_t)lane * 16u : 0x80000000u;
+        const uint32_t off = live ? (uint32_t)(c * L.G + g) * (NBLK * 256u) + (uint32_t)lane * 16u : 0x80000000u;
 #pragma unroll
         for (int i = 0; i < NXL; ++i) xb[i] = __builtin_amdgcn_raw_buffer_load_b128(xt, off + i * 1024, 0, 0);
     }
@@ -167,55 +215,30 @@ template <int R> struct GemmCtx {
     }
 };
 
-// MFMA order of a tile: key by key (so that one 32x32 accumulator is live at a time).
-template <int R> struct MfmaOrder {
-    using T = Layout<R>;
-    static constexpr int NMF = Mfma<R>::NMF;
-    // i-th MFMA in issue order -> index mf = Q * NOPS + oi
-    static constexpr int at(int i) {
-        int n = 0;
-        for (int key = 0; key < T::NKEYS; ++key)
-            for (int mf = 0; mf < NMF; ++mf)
-                if (key_index<R>(mf % T::NOPS) == key) {
-                    if (n == i) return mf;
-                    ++n;
-                }
-        return -1;
-    }
-    static constexpr int key_of(int i) { return key_index<R>(at(i) % T::NOPS); }
-    static constexpr bool last_of_key(int i) { return i + 1 == NMF || key_of(i + 1) != key_of(i); }
-    static constexpr bool first_of_key(int i) { return i == 0 || key_of(i - 1) != key_of(i); }
-};
-
-// One tile: NMF MFMAs, then the per-group scale / zero step.  B comes from LDS stage `stage`,
-// read four MFMAs ahead of its use so that the LDS latency overlaps the previous MFMAs.
+// One tile: NMF MFMAs on the masked fields, one on the zero-offset, then y += scale * (F * D).  B comes from LDS
+// stage `stage`, read four MFMAs ahead of its use so that the LDS latency overlaps the previous MFMAs.
+//   zl : zero-offset of the lane's OWN row (the lane is an A supplier of that row)
+//   s4 : scales of the 16 rows the lane holds accumulator elements of
 template <int R>
 __device__ __forceinline__ void gemm_tile_math(const GemmCtx<R> &cx, const uint32_t (&w)[4 * R], int stage,
-                                               const u32x2 (&s4)[4], const u32x2 (&z4)[4], float xg,
-                                               float (&yacc)[16]) {
+                                               const u32x2 (&s4)[4], _Float16 zl, float F, float (&yacc)[16]) {
     using T = Layout<R>;
     using MF = Mfma<R>;
-    using Ord = MfmaOrder<R>;
     constexpr int kAhead = 4;
-    const u32x4 *bsrc = cx.lm.b_live ? reinterpret_cast<const u32x4 *>(cx.lds + stage * kStageBytes) + cx.lm.col
-                                     : reinterpret_cast<const u32x4 *>(cx.zero);
-    const int bstep = cx.lm.b_live ? 16 : 0;  // u32x4 elements per MFMA block (256 bytes)
-    u32x4 bq[kAhead];                          // ring of B operands in flight
-    static_for<kAhead>([&](auto i) {
-        if constexpr (i < MF::NMF) bq[i] = bsrc[Ord::at(i) * bstep];
-    });
-    // field value = digit * 2^(key-24): back to code units, then Eq. 1's rescale 2^(8-r)
-    float dsum[16];
+    constexpr int NBLK = MF::NMF + 1;
+    // Lanes whose B operand is zero do not read at all (their registers are cleared once per tile): an LDS read
+    // costs its bandwidth per active lane, and B operands are what the LDS pipe is busy with in this kernel.
+    const u32x4 *bsrc = reinterpret_cast<const u32x4 *>(cx.lds + stage * kStageBytes) + cx.lm.col;
+    constexpr int bstep = 16;  // u32x4 elements per operand block (256 bytes)
+    u32x4 bq[kAhead];          // ring of B operands in flight
+    static_for<kAhead>([&](auto i) { bq[i] = u32x4{0u, 0u, 0u, 0u}; });
+    if (cx.lm.b_live) static_for<kAhead>([&](auto i) { bq[i] = bsrc[i * bstep]; });
     float16_t D;
-    static_for<MF::NMF>([&](auto i) {
-        constexpr int mf = Ord::at(i);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) D[v] = 0.f;
+    static_for<MF::NMF>([&](auto mf) {
         constexpr int Q = mf / T::NOPS;
         constexpr Op o = T::op(mf % T::NOPS);
-        constexpr int key = Ord::key_of(i);
-        if constexpr (Ord::first_of_key(i)) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) D[v] = 0.f;
-        }
         uint32_t a[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -224,26 +247,28 @@ __device__ __forceinline__ void gemm_tile_math(const GemmCtx<R> &cx, const uint3
             a[j] = v & ((uint32_t)o.mask * 0x10001u);
         }
         const u32x4 av = {a[0], a[1], a[2], a[3]};
-        const u32x4 bv = bq[i % kAhead];
-        if constexpr (i + kAhead < MF::NMF) bq[i % kAhead] = bsrc[Ord::at(i + kAhead) * bstep];
+        const u32x4 bv = bq[mf % kAhead];
+        if constexpr (mf + kAhead < NBLK) {
+            if (cx.lm.b_live) bq[mf % kAhead] = bsrc[(mf + kAhead) * bstep];
+        }
         D = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, av), __builtin_bit_cast(half8_t, bv), D,
                                                    0, 0, 0);
-        if constexpr (Ord::last_of_key(i)) {
-            const float ck = __builtin_ldexpf(1.f, 24 - T::key(key) + kC - R);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) dsum[v] = key == 0 ? D[v] * ck : fmaf(D[v], ck, dsum[v]);
-        }
     });
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const float s = half_of(s4[v >> 2], v & 3), z = half_of(z4[v >> 2], v & 3);
-        yacc[v] = fmaf(s, fmaf(-z, xg, dsum[v]), yacc[v]);
+    {   // zero-offset: A = (z', z', z', 0, ...) with z' = z * 2^(r-17), B = -X_g * 2^(e-15) in three pieces
+        const _Float16 zs = zl * (_Float16)__builtin_ldexpf(1.f, R - 17);
+        const half2_t zz = {zs, zs}, z0 = {zs, (_Float16)0.f};
+        const u32x4 av = {__builtin_bit_cast(uint32_t, zz), __builtin_bit_cast(uint32_t, z0), 0u, 0u};
+        D = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, av),
+                                                   __builtin_bit_cast(half8_t, bq[MF::NMF % kAhead]), D, 0, 0, 0);
     }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) yacc[v] = fmaf(half_of(s4[v >> 2], v & 3), D[v] * F, yacc[v]);
 }
 
-// Weight tiles a wave keeps in flight ahead of the one it is working on (about 8 KB).
+// Weight tiles a wave keeps in flight ahead of the one it is working on.  The ring has an even number of
+// buffers (depth + 1) so that the two-deep ring of scales / zero / factor below keeps compile-time indices.
 template <int R> struct GemmDepth {
-    static constexpr int value = R <= 3 ? 4 : R == 4 ? 3 : 2;
+    static constexpr int value = R <= 6 ? 3 : 1;
 };
 
 // Tiles [u_begin, u_end) of chunk c of one layer (tile index u = rb*G + g).
@@ -253,7 +278,7 @@ __device__ __forceinline__ void run_gemm_units(const LayerDesc &L, const StackPa
     using MF = Mfma<R>;
     using Ctx = GemmCtx<R>;
     constexpr int D = GemmDepth<R>::value, NB = D + 1;
-    const uint32_t xt_bytes = (uint32_t)L.CB * L.G * MF::NMF * 256u;
+    const uint32_t xt_bytes = (uint32_t)L.CB * L.G * (MF::NMF + 1) * 256u;
     LaneMap lmap = lane_map(lane);
     // a lane whose output column lies beyond M supplies zeros as B: it reads the 16 zero bytes instead of its stage
     lmap.b_live = lmap.b_live && c * kChunkCols + lmap.col < L.M;
@@ -278,9 +303,26 @@ __device__ __forceinline__ void run_gemm_units(const LayerDesc &L, const StackPa
         cx.load_w(dst, u_pf);
         if (u_pf + 1 < u_end) ++u_pf;
     };
+    // Scales, zero-offset and rescale factor of a tile are fetched one tile ahead, BEFORE that iteration's weight
+    // prefetch: loads return in order, so waiting for anything issued after the prefetch would wait for the prefetch
+    // itself (a full trip to HBM per tile).  Every wait of the loop is then for a load at least one tile old.
+    static_assert(NB % 2 == 0, "the two-deep meta ring relies on an even unroll");
+    struct TileMeta {
+        u32x2 s4[4];
+        _Float16 zl;
+        float F;
+    } meta[2];
+    auto load_meta = [&](TileMeta &t, int ut, int gt) {
+        const u32x2 MQ_GLOBAL *sp = gl(reinterpret_cast<const u32x2 *>(L.st + (size_t)ut * 64 + lm.rowbase));
+#pragma unroll
+        for (int q = 0; q < 4; ++q) t.s4[q] = __builtin_nontemporal_load(sp + 2 * q);
+        t.zl = __builtin_nontemporal_load(gl(L.zt) + (size_t)ut * 64 + lane);
+        t.F = gl(L.xsum)[(size_t)(c * L.G + gt) * kChunkCols + lm.col];
+    };
     {
         u32x4 xb[Ctx::NXL];
         cx.load_x(xb, g);
+        load_meta(meta[0], u_begin, g);
         static_for<D>([&](auto j) { prefetch_w(w[j]); });
         cx.store_x(xb, 0);
     }
@@ -293,19 +335,11 @@ __device__ __forceinline__ void run_gemm_units(const LayerDesc &L, const StackPa
             const int g_next = more ? (g + 1 == L.G ? 0 : g + 1) : g;
             u32x4 xb[Ctx::NXL];
             cx.load_x(xb, g_next);              // first: it is awaited first (loads return in order)
-            __builtin_amdgcn_sched_barrier(0);  // ... and must really be issued first
+            load_meta(meta[(j + 1) % 2], more ? u + 1 : u, g_next);
+            __builtin_amdgcn_sched_barrier(0);  // ... and these must really be issued ahead of the prefetch
             prefetch_w(w[(j + D) % NB]);
-            u32x2 s4[4], z4[4];
-            const u32x2 MQ_GLOBAL *sp = gl(reinterpret_cast<const u32x2 *>(L.st + (size_t)u * 64 + lm.rowbase));
-            const u32x2 MQ_GLOBAL *zp = gl(reinterpret_cast<const u32x2 *>(L.zt + (size_t)u * 64 + lm.rowbase));
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                s4[q] = __builtin_nontemporal_load(sp + 2 * q);
-                z4[q] = __builtin_nontemporal_load(zp + 2 * q);
-            }
-            const float xg = gl(L.xsum)[(size_t)(c * L.G + g) * kChunkCols + lm.col];
             __builtin_amdgcn_sched_barrier(0);  // keep the loads up here, ahead of the math
-            gemm_tile_math<R>(cx, w[j], st, s4, z4, xg, yacc);
+            gemm_tile_math<R>(cx, w[j], st, meta[j % 2].s4, meta[j % 2].zl, meta[j % 2].F, yacc);
             cx.store_x(xb, st ^ 1);
             st ^= 1;
             ++g;

@@ -54,8 +54,8 @@ struct LayerDesc {
     const _Float16 *zt;
     const _Float16 *x;
     _Float16 *y;
-    const uint4 *xt;        // MFMA path: activations re-ordered per (chunk, group, MFMA) by the prep kernel
-    const float *xsum;      // MFMA path: per (chunk, group, column) sums of x
+    const uint4 *xt;        // MFMA path: activations re-ordered (narrow path: and scaled) per (chunk, group, MFMA) by the prep kernel
+    const float *xsum;      // narrow MFMA path: per (chunk, group, column) the factor F that rescales a tile's accumulator
     int32_t N, K, G, RB;    // RB = row blocks = ceil(N/64); on the wide path super row blocks = ceil(N/256)
     int32_t r;
     int32_t cost;           // schedule cost of one (row block, group) tile
@@ -160,6 +160,8 @@ hipError_t launch_reslice_many(const uint4 *const *src, uint4 *const *dst, const
 hipError_t launch_pack_meta(const _Float16 *sc, const _Float16 *zr, int64_t N, int64_t G, _Float16 *st,
                             _Float16 *zt, hipStream_t s);
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
+// xor of all 16-byte words of buf is xor-ed into *out (measurement aid); bytes is a multiple of 16
+hipError_t launch_read_probe(const void *buf, size_t bytes, uint32_t *out, hipStream_t s);
 // table: host, n descriptors -> dst: device.  ceil(n / 32) small launches; the host array is free again on return.
 hipError_t launch_write_table(const LayerDesc *table, int n, LayerDesc *dst, hipStream_t s);
 // Algorithm 1 (mq_quant.hip).  lambda: host, kC floats (width r at [r-1]); vec4: four columns per lane (alignment checked by the caller)

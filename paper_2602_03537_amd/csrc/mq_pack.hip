@@ -388,4 +388,43 @@ hipError_t launch_write_table(const LayerDesc *table, int n, LayerDesc *dst, hip
     return hipSuccess;
 }
 
+// ------------------------------------------------------------------ measurement aid: what a plain read achieves
+// Every wave streams a contiguous share of the buffer with eight non-temporal 16-byte loads per lane in flight and
+// folds what it read into one word (so that nothing can be dropped); the rate of this kernel is the read bandwidth
+// the linear kernels are measured against, next to the published peak.
+__global__ __launch_bounds__(256) void read_probe_kernel(const uint4 *buf, size_t n16, uint32_t *out) {
+    typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+    constexpr int U = 8;
+    const int lane = threadIdx.x & 63;
+    const size_t wave = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const size_t nw = ((size_t)gridDim.x * blockDim.x) >> 6;
+    const v4u __attribute__((address_space(1))) *g = (const v4u __attribute__((address_space(1))) *)buf;
+    const size_t chunk = (size_t)U * 64;
+    const size_t per = (n16 / nw + chunk - 1) / chunk * chunk;
+    const size_t lo = wave * per;
+    size_t hi = lo + per;
+    if (hi > n16) hi = n16;
+    v4u acc = {0, 0, 0, 0};
+    size_t base = lo;
+    for (; base + chunk <= hi; base += chunk) {
+        v4u v[U];
+#pragma unroll
+        for (int i = 0; i < U; ++i) v[i] = __builtin_nontemporal_load(g + base + i * 64 + lane);
+#pragma unroll
+        for (int i = 0; i < U; ++i) acc ^= v[i];
+    }
+    for (base += lane; base < hi; base += 64) acc ^= __builtin_nontemporal_load(g + base);
+    uint32_t r = acc.x ^ acc.y ^ acc.z ^ acc.w;
+#pragma unroll
+    for (int off = 32; off; off >>= 1) r ^= __shfl_xor(r, off);
+    if (lane == 0) __hip_atomic_fetch_xor(out, r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+hipError_t launch_read_probe(const void *buf, size_t bytes, uint32_t *out, hipStream_t s) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return hipErrorUnknown;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) return hipErrorUnknown;
+    return launch(read_probe_kernel, dim3((unsigned)(cus * 4)), dim3(256), 0, s, static_cast<const uint4 *>(buf), bytes / 16, out);
+}
+
 }  // namespace mq
