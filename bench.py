@@ -29,11 +29,36 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-# HBM bytes per launch of mq::stack_kernel<1, 1, false> on the default workload (mean over the five widths),
-# from the two rocprofv3 --pmc runs summarised in profiles/stack_kernel_llama2_7b_m1_hbm_traffic.txt
-# (FETCH_SIZE scaled by 1.9987, WRITE_SIZE by 1.0, both calibrated on a 45 MB copy in the same run).
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 3936919163
 WIDTHS = (2, 3, 4, 6, 8)
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "stack_kernel_llama2_7b_m1_hbm_traffic.txt")
+# the sources that define mq::stack_kernel<1, 1, false>: a traffic figure is quoted only while they are the ones profiled
+KERNEL_SOURCES = ("mq_linear.hip", "mq_device.h", "mq_layout.h", "mq_internal.h", "mq_static_for.h")
+
+
+def kernel_sources_sha() -> str:
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2602_03537_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def traffic_from_profile():
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (two machine-readable
+    lines: `traffic_bytes_per_launch = N`, `kernel_sources_sha = H`).  None, with the reason, if the summary is
+    missing or was taken on other kernel sources than the ones in the tree."""
+    try:
+        kv = {}
+        for line in open(TRAFFIC_PROFILE):
+            if " = " in line and line.split(" = ")[0].strip() in ("traffic_bytes_per_launch", "kernel_sources_sha"):
+                k, v = line.split(" = ", 1)
+                kv[k.strip()] = v.strip()
+        if kv.get("kernel_sources_sha") != kernel_sources_sha():
+            return None, "profile summary was taken on other kernel sources"
+        return int(kv["traffic_bytes_per_launch"]), os.path.relpath(TRAFFIC_PROFILE, ROOT)
+    except (OSError, KeyError, ValueError) as e:
+        return None, f"no usable profile summary ({type(e).__name__})"
 
 
 def algo_bytes(N, K, r, M=1, group=128):
@@ -60,6 +85,9 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-single", action="store_true", help="skip the per-call mq_linear table")
     ap.add_argument("--no-loadtime", action="store_true", help="skip the slice/pack throughput leg")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the legs folded into the default line (achievable read, mixed Llama-2-7B stack, a cut of "
+                         "the batched Llama-3-70B MLP regime, decoder-block fusions)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -87,6 +115,9 @@ def main() -> int:
         return bench_decode_fusions(args, mq, synth, torch, np, dev)
     block = synth.LLAMA2_7B_BLOCK
     M = 1
+
+    # ---- what a plain streaming read achieves on this device, measured before anything else is resident
+    read = None if args.no_extras else measure_read_probe(mq, torch, dev)
 
     # ---- inputs: one seeded parent per distinct shape (host recipe), uploaded once
     host = {}
@@ -180,8 +211,10 @@ def main() -> int:
     achieved = bytes_per_launch / avg_launch_us / 1e3
     roofline = {"bound": "hbm", "kernel": "mq::stack_kernel<1, 1, false>", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "avg_launch_us": round(avg_launch_us, 1), "algorithmic_bytes_per_launch": int(bytes_per_launch),
-                "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH if args.layers == 32 else None}
+                "avg_launch_us": round(avg_launch_us, 1), "algorithmic_bytes_per_launch": int(bytes_per_launch)}
+    traffic, traffic_src = traffic_from_profile() if args.layers == 32 else (None, "not the profiled workload")
+    roofline["traffic"] = traffic
+    roofline["traffic_source"] = traffic_src
 
     # ---- per-call table: one mq_linear launch per layer, cold (cycling distinct copies), replayed from a HIP graph
     single = None
@@ -213,8 +246,39 @@ def main() -> int:
                 torch.cuda.synchronize()
                 us = e0.elapsed_time(e1) * 1e3 / (3 * len(same))
                 b = algo_bytes(N, K, r, M)
-                single[f"{N}x{K}:r{r}"] = {"us": round(us, 2), "GBps": round(b / us / 1e3, 1), "copies": len(same)}
                 del g
+                # warm: the same weights again and again (cache-resident up to the last-level cache), graph replay
+                L0 = same[0]
+
+                def run_warm():
+                    for _ in range(32):
+                        mq.mq_linear(L0["x"], L0["packed_W"], L0["scales_t"], L0["zeros_t"], N, K, r, 128, ws, y=y)
+
+                run_warm()
+                torch.cuda.synchronize()
+                gw = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gw):
+                    run_warm()
+                gw.replay()
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(3):
+                    gw.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                us_warm = e0.elapsed_time(e1) * 1e3 / (3 * 32)
+                del gw
+                # isolated: one launch on an idle device, cold weights (another copy each time), events around it
+                iso = []
+                for L1 in same[1:9]:
+                    torch.cuda.synchronize()
+                    e0.record()
+                    mq.mq_linear(L1["x"], L1["packed_W"], L1["scales_t"], L1["zeros_t"], N, K, r, 128, ws, y=y)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    iso.append(e0.elapsed_time(e1) * 1e3)
+                single[f"{N}x{K}:r{r}"] = {"us": round(us, 2), "GBps": round(b / us / 1e3, 1), "copies": len(same),
+                                           "us_warm": round(us_warm, 2), "us_isolated": round(float(np.median(iso)), 2)}
 
     # ---- CPU oracle on the host cores: whole decoder blocks (7 linears at every r) until about 12 s of work
     cpu = None
@@ -236,6 +300,36 @@ def main() -> int:
                          f"= {passes}/{args.layers} of the timed workload; same algorithmic-byte accounting as the GPU value",
                "seconds": round(ct, 2)}
 
+    # ---- legs folded into the default line so that one driver run checks every quoted configuration
+    extras = {}
+    if not args.no_extras:
+        del stacks, prepared, layers
+        torch.cuda.empty_cache()
+        extras["achievable_read"] = read
+        for r in WIDTHS:
+            per_r[str(r)]["frac_of_achievable_read"] = round(per_r[str(r)]["GBps"] / read["GBps"], 4)
+        roofline["frac_of_achievable_read"] = round(achieved / read["GBps"], 4)
+        m = measure_mixed_stack(mq, synth, torch, np, dev, False, synth.LLAMA2_7B_LAYERS, 1, args.steps, args.warmup)
+        gb = m["bytes"] / float(np.median(m["us"])) / 1e3
+        extras["mixed_7b"] = {"workload": f"Llama-2-7B-shaped stack, 32 blocks ({m['n_linears']} linears), M=1, per-layer r by seed, "
+                                          f"mean {m['mean_bits']:.3f} bits, one persistent launch",
+                              "us_median": round(float(np.median(m["us"])), 1), "us_min": round(float(np.min(m["us"])), 1),
+                              "GBps": round(gb, 1), "frac": round(gb / HBM_PEAK_GBPS, 4),
+                              "frac_of_achievable_read": round(gb / read["GBps"], 4),
+                              "algorithmic_GB": round(m["bytes"] / 1e9, 3)}
+        del m
+        torch.cuda.empty_cache()
+        cut = measure_mlp(mq, synth, torch, dev, (("up", 28672, 8192),), (4,), (1, 4, 16, 64, 256), max(2, args.steps // 4))
+        for v in cut.values():
+            v.pop("bytes")
+        extras["mlp_70b_cut"] = {"workload": "Llama-3-70B up-projection 28672x8192, r=4, M in {1,4,16,64,256}, one mq_linear "
+                                             "launch per call, 4 weight copies cycled (cold)", "table": cut}
+        torch.cuda.empty_cache()
+        res, dbytes, dmean = measure_decode_fusions(mq, synth, torch, np, dev, 1, 32, max(5, args.steps // 2))
+        extras["decode_7b"] = {"workload": f"Llama-2-7B decoder blocks x32, M=1, per-layer r by seed (mean {dmean:.3f} bits), "
+                                           "every block its own weights, HIP-graph replay", "table": res,
+                               "frac": round(res["fused_qkv_and_gate_up"]["GBps"] / HBM_PEAK_GBPS, 4)}
+
     out = {
         "metric": "batch-1 sliced GEMV effective HBM GB/s (algorithmic bytes / time) over r in {2,3,4,6,8}",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -252,6 +346,7 @@ def main() -> int:
         "single_call": single,
         "load_time": loadtime or None,
     }
+    out.update(extras)
     print(json.dumps(out))
     return 0
 
@@ -262,13 +357,10 @@ def _base_line(metric, value, unit, args, ms_per_step, workload, extra_cfg):
             "vs_baseline": None, "dtype": "f16", "data": "synthetic", "config": dict({"workload": workload}, **extra_cfg)}
 
 
-def bench_mixed_stack(args, mq, synth, torch, np, dev):
-    """One mixed-width stack (per-layer r drawn by seed), one persistent launch per step."""
-    big = args.workload == "mixed-70b"
+def measure_mixed_stack(mq, synth, torch, np, dev, big, n_blocks, M, steps, warmup):
+    """One mixed-width stack (per-layer r drawn by seed), one persistent launch per step.  Returns a dict of results."""
     block = synth.LLAMA3_70B_BLOCK if big else synth.LLAMA2_7B_BLOCK
-    n_blocks = (synth.LLAMA3_70B_LAYERS if big else synth.LLAMA2_7B_LAYERS) if args.layers == 32 else args.layers
     target = 4.0 if big else 3.5
-    M = args.batch
     shapes = synth.stack_shapes(block, n_blocks)
     widths, mean = synth.draw_bitwidths([N * K for (_, _, N, K) in shapes], target, seed=0)
     layers, nbytes, keep = [], 0.0, []
@@ -281,30 +373,40 @@ def bench_mixed_stack(args, mq, synth, torch, np, dev):
             keep.append(L["parent"])          # the 8-bit parent stays resident, as the configuration states
         nbytes += algo_bytes(N, K, int(r), M)
     plan = mq.mq_stack_plan(layers, M, device=dev)
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         mq.mq_linear_stack(plan)
     torch.cuda.synchronize()
-    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t0 = time.perf_counter()
-    for k in range(args.steps):
+    for k in range(steps):
         evs[k].record()
         mq.mq_linear_stack(plan)
-    evs[args.steps].record()
+    evs[steps].record()
     torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    us = [evs[k].elapsed_time(evs[k + 1]) * 1e3 for k in range(args.steps)]
-    value = nbytes / (ms * 1e-3) / 1e9
-    out = _base_line("mixed-precision stack, decode-step latency and aggregate effective HBM GB/s", value, "GB/s", args,
-                     ms, f"{'Llama-3-70B' if big else 'Llama-2-7B'}-shaped stack, {n_blocks} blocks ({len(layers)} linears), "
-                     f"M={M}, per-layer r from {{2,3,4,6,8}} by seed, parameter-weighted mean {mean:.3f} bits",
-                     {"M": M, "mean_bits": round(mean, 4), "algorithmic_GB_per_step": round(nbytes / 1e9, 3)})
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    us = [evs[k].elapsed_time(evs[k + 1]) * 1e3 for k in range(steps)]
     kernel = ("mq::stack_kernel<%d, 1, false>" % M if M <= 3 else "mq::gemm_stack_kernel" if M <= 16
               else "mq::wide_stack_kernel")
+    return {"ms_wall": ms, "us": us, "bytes": nbytes, "mean_bits": mean, "n_linears": len(layers), "n_blocks": n_blocks,
+            "kernel": kernel}
+
+
+def bench_mixed_stack(args, mq, synth, torch, np, dev):
+    big = args.workload == "mixed-70b"
+    n_blocks = (synth.LLAMA3_70B_LAYERS if big else synth.LLAMA2_7B_LAYERS) if args.layers == 32 else args.layers
+    M = args.batch
+    m = measure_mixed_stack(mq, synth, torch, np, dev, big, n_blocks, M, args.steps, args.warmup)
+    ms, us, nbytes, mean = m["ms_wall"], m["us"], m["bytes"], m["mean_bits"]
+    value = nbytes / (ms * 1e-3) / 1e9
+    out = _base_line("mixed-precision stack, decode-step latency and aggregate effective HBM GB/s", value, "GB/s", args,
+                     ms, f"{'Llama-3-70B' if big else 'Llama-2-7B'}-shaped stack, {n_blocks} blocks ({m['n_linears']} linears), "
+                     f"M={M}, per-layer r from {{2,3,4,6,8}} by seed, parameter-weighted mean {mean:.3f} bits",
+                     {"M": M, "mean_bits": round(mean, 4), "algorithmic_GB_per_step": round(nbytes / 1e9, 3)})
     ach = nbytes / float(np.mean(us)) / 1e3
     out["stack_us_median"] = round(float(np.median(us)), 1)
     out["stack_us_min"] = round(float(np.min(us)), 1)
     out["frac_of_hbm_peak"] = round(value / HBM_PEAK_GBPS, 4)
-    out["roofline"] = {"bound": "hbm", "kernel": kernel, "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+    out["roofline"] = {"bound": "hbm", "kernel": m["kernel"], "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                        "frac": round(ach / HBM_PEAK_GBPS, 4), "avg_launch_us": round(float(np.mean(us)), 1),
                        "algorithmic_bytes_per_launch": int(nbytes), "traffic": None}
     out["cpu_baseline"] = None
@@ -422,6 +524,24 @@ def bench_resident_parent(args, mq, synth, torch, np, dev):
 
 
 FP32_VECTOR_PEAK_TFLOPS = 157.3
+# Vector lanes x clock without the factor two of a fused multiply-add: 256 CUs x 4 SIMDs x 32 lanes per clock x 2.4 GHz.
+# Algorithm 1's arithmetic is defined operation by operation (nothing may be fused), so this is its ceiling.
+VECTOR_LANE_OPS_PEAK_T = 78.6
+# Vector instructions the compiled quant_kernel<140, 4> executes per candidate and weight (R = {3,4,8}), from the
+# SQ_INSTS_VALU counter in profiles/quant_kernel_alg1_llama2_7b_shapes.txt (8117 per wave of 64 lanes x 4 weights x 256
+# candidates); the definition counts 19 per candidate and weight, the kernel skips recomputing terms that cannot change.
+QUANT_PROFILE = os.path.join(ROOT, "profiles", "quant_kernel_alg1_llama2_7b_shapes.txt")
+
+
+def quant_executed_ops_per_weight():
+    """executed vector lane-operations per weight of quant_kernel<140, 4>, read from the committed counter summary"""
+    import re
+    try:
+        m = re.search(r"R = \{3,4,8\}, \d+ weights: SQ_INSTS_VALU [^\n]*?= ([0-9.]+) per candidate and lane \(4 weights\)",
+                      open(QUANT_PROFILE).read())
+        return float(m.group(1)) * 256.0 / 4.0
+    except (OSError, AttributeError, ValueError):
+        return None
 
 
 def bench_quant(args, mq, synth, torch, np, dev):
@@ -461,11 +581,23 @@ def bench_quant(args, mq, synth, torch, np, dev):
                      "c = 8, R = {3,4,8} with lambda = 1 (the paper's setting); other R in `table`", {})
     out["dtype"] = "f32"
     out["table"] = table
-    ach = tot_fl / tot_t / 1e12
-    out["roofline"] = {"bound": "alu", "kernel": "mq::quant_kernel<140, 4>", "achieved": round(ach, 1),
-                       "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / FP32_VECTOR_PEAK_TFLOPS, 4),
-                       "avg_launch_us": round(tot_t / 3 * 1e6, 1),
-                       "algorithmic_flops_per_launch": int(tot_fl / 3), "traffic": None}
+    # roofline: the lane-operations the kernel EXECUTES per second against the unfused vector peak (the brute force as
+    # defined counts 19 operations per candidate and weight; the kernel executes fewer because a width's term is only
+    # recomputed where its slice changes, so the counted-work rate would exceed the peak and say nothing)
+    ops_w = quant_executed_ops_per_weight()
+    counted = tot_fl / tot_t / 1e12
+    if ops_w is not None:
+        ach = ops_w * tot_w / tot_t / 1e12
+        out["roofline"] = {"bound": "alu", "kernel": "mq::quant_kernel<140, 4>", "achieved": round(ach, 1),
+                           "peak": VECTOR_LANE_OPS_PEAK_T, "unit": "T lane-op/s", "frac": round(ach / VECTOR_LANE_OPS_PEAK_T, 4),
+                           "avg_launch_us": round(tot_t / 3 * 1e6, 1),
+                           "executed_lane_ops_per_weight": round(ops_w, 1),
+                           "executed_ops_source": os.path.relpath(QUANT_PROFILE, ROOT),
+                           "counted_brute_force_Tops": round(counted, 1), "traffic": None}
+    else:
+        out["roofline"] = {"bound": "alu", "kernel": "mq::quant_kernel<140, 4>", "achieved": None,
+                           "peak": VECTOR_LANE_OPS_PEAK_T, "unit": "T lane-op/s", "frac": None,
+                           "counted_brute_force_Tops": round(counted, 1), "traffic": None}
     cpu = None
     if not args.no_cpu:
         import oracle
@@ -486,13 +618,11 @@ def bench_quant(args, mq, synth, torch, np, dev):
     return 0
 
 
-def bench_decode_fusions(args, mq, synth, torch, np, dev):
+def measure_decode_fusions(mq, synth, torch, np, dev, M, n_blocks, steps):
     """Decode-shaped fusions: the linears of a decoder block that share their input (q/k/v; gate/up) as ONE
     mq_linear_stack launch each, against one mq_linear launch per linear.  Llama-2-7B shapes, per-layer widths by
     seed (mean 3.5 bits), every block its own weights (cold), replayed from a HIP graph."""
-    M = args.batch
     block = synth.LLAMA2_7B_BLOCK
-    n_blocks = args.layers
     shapes = synth.stack_shapes(block, n_blocks)
     widths, mean = synth.draw_bitwidths([N * K for (_, _, N, K) in shapes], 3.5, seed=0)
     proto = {}
@@ -550,14 +680,20 @@ def bench_decode_fusions(args, mq, synth, torch, np, dev):
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        for _ in range(args.steps):
+        for _ in range(steps):
             g.replay()
         e1.record()
         torch.cuda.synchronize()
-        t = e0.elapsed_time(e1) * 1e-3 / args.steps
+        t = e0.elapsed_time(e1) * 1e-3 / steps
         res[label] = {"us_per_block": round(t / n_blocks * 1e6, 2), "GBps": round(nbytes / t / 1e9, 1),
                       "launches_per_block": 7 if label.startswith("one") else 4}
         del g
+    return res, nbytes, mean
+
+
+def bench_decode_fusions(args, mq, synth, torch, np, dev):
+    M, n_blocks = args.batch, args.layers
+    res, nbytes, mean = measure_decode_fusions(mq, synth, torch, np, dev, M, n_blocks, args.steps)
     t_f = res["fused_qkv_and_gate_up"]["us_per_block"] * n_blocks * 1e-6
     out = _base_line("decoder-block linears with shared-input fusions, effective HBM GB/s", nbytes / t_f / 1e9, "GB/s", args,
                      t_f * 1e3, f"Llama-2-7B decoder blocks x{n_blocks}, M={M}, per-layer r by seed (mean {mean:.3f} bits): "
@@ -626,16 +762,15 @@ def bench_gptq(args, mq, synth, torch, np, dev):
     return 0
 
 
-def bench_mlp_batched(args, mq, synth, torch, np, dev):
-    """Batched regime on the Llama-3-70B MLP shapes: mq_linear per (shape, r, M), cold (cycling copies)."""
+def measure_mlp(mq, synth, torch, dev, shapes, widths, batches, reps):
+    """mq_linear per (shape, r, M) on the Llama-3-70B MLP shapes, cold (four distinct weight copies cycled)."""
     table = {}
-    tot_b, tot_t = 0.0, 0.0
-    for (name, N, K) in (("up", 28672, 8192), ("down", 8192, 28672)):
-        L = synth.make_layer_device(N, K, 256, seed=9000 + N, device=dev)
-        for r in (3, 4, 8):
+    for (name, N, K) in shapes:
+        L = synth.make_layer_device(N, K, max(batches), seed=9000 + N, device=dev)
+        for r in widths:
             lay = mq.prepare_layer(L["parent"], L["scales"], L["zeros"], r)
             copies = [(lay["packed_W"].clone(), lay["scales_t"].clone(), lay["zeros_t"].clone()) for _ in range(4)]
-            for M in (1, 4, 16, 64, 256):
+            for M in batches:
                 x = L["x"][:M].contiguous()
                 ws = mq.new_workspace(M, N, K, r)
                 y = torch.empty((M, N), dtype=torch.float16, device=dev)
@@ -647,19 +782,27 @@ def bench_mlp_batched(args, mq, synth, torch, np, dev):
                 torch.cuda.synchronize()
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
-                for _ in range(max(1, args.steps // 4)):
+                for _ in range(reps):
                     run()
                 e1.record()
                 torch.cuda.synchronize()
-                us = e0.elapsed_time(e1) * 1e3 / (max(1, args.steps // 4) * len(copies))
+                us = e0.elapsed_time(e1) * 1e3 / (reps * len(copies))
                 b, fl = algo_bytes(N, K, r, M), 2.0 * M * N * K
                 table[f"{name}:{N}x{K}:r{r}:M{M}"] = {"us": round(us, 1), "GBps": round(b / us / 1e3, 1),
                                                      "hbm_frac": round(b / us / 1e3 / HBM_PEAK_GBPS, 4),
                                                      "TFLOPs": round(fl / us / 1e6, 1),
-                                                     "mfma_frac": round(fl / us / 1e6 / 2500.0, 4)}
-                tot_b += b
-                tot_t += us
+                                                     "mfma_frac": round(fl / us / 1e6 / 2500.0, 4), "bytes": b}
             del copies
+        del L
+    return table
+
+
+def bench_mlp_batched(args, mq, synth, torch, np, dev):
+    """Batched regime on the Llama-3-70B MLP shapes: mq_linear per (shape, r, M), cold (cycling copies)."""
+    table = measure_mlp(mq, synth, torch, dev, (("up", 28672, 8192), ("down", 8192, 28672)), (3, 4, 8), (1, 4, 16, 64, 256),
+                        max(1, args.steps // 4))
+    tot_b = sum(v.pop("bytes") for v in table.values())
+    tot_t = sum(v["us"] for v in table.values())
     out = _base_line("batched sliced linear, effective HBM GB/s and MFMA utilisation", tot_b / tot_t / 1e3, "GB/s", args,
                      tot_t / 1e3, "Llama-3-70B MLP shapes (28672x8192, 8192x28672), M in {1,4,16,64,256}, r in {3,4,8}, "
                      "one mq_linear launch per call, 4 distinct weight copies cycled", {})
@@ -674,6 +817,30 @@ def bench_mlp_batched(args, mq, synth, torch, np, dev):
     out["cpu_baseline"] = None
     print(json.dumps(out))
     return 0
+
+
+def measure_read_probe(mq, torch, dev, gib=4, reps=10):
+    """What a plain streaming read achieves: mq_read_probe over a buffer far beyond the last-level cache."""
+    buf = torch.empty(gib << 30, dtype=torch.uint8, device=dev)
+    buf.zero_()
+    out = torch.zeros(1, dtype=torch.int32, device=dev)
+    for _ in range(3):
+        mq.mq_read_probe(buf, out)
+    torch.cuda.synchronize()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+    for k in range(reps):
+        evs[k].record()
+        mq.mq_read_probe(buf, out)
+    evs[reps].record()
+    torch.cuda.synchronize()
+    us = sorted(evs[k].elapsed_time(evs[k + 1]) * 1e3 for k in range(reps))
+    med = us[len(us) // 2]
+    nbytes = buf.numel()
+    del buf
+    torch.cuda.empty_cache()
+    return {"GBps": round(nbytes / med / 1e3, 1), "frac_of_8TBps": round(nbytes / med / 1e3 / HBM_PEAK_GBPS, 4),
+            "bytes": nbytes, "us_median": round(med, 1), "us_min": round(us[0], 1),
+            "kernel": "mq::read_probe_kernel (non-temporal 16-byte loads, contiguous share per wave)"}
 
 
 if __name__ == "__main__":

@@ -400,10 +400,9 @@ __global__ __launch_bounds__(256) void read_probe_kernel(const uint4 *buf, size_
     const size_t nw = ((size_t)gridDim.x * blockDim.x) >> 6;
     const v4u __attribute__((address_space(1))) *g = (const v4u __attribute__((address_space(1))) *)buf;
     const size_t chunk = (size_t)U * 64;
-    const size_t per = (n16 / nw + chunk - 1) / chunk * chunk;
-    const size_t lo = wave * per;
-    size_t hi = lo + per;
-    if (hi > n16) hi = n16;
+    const size_t per = ((n16 + nw - 1) / nw + chunk - 1) / chunk * chunk;  // whole chunks, shares cover the buffer
+    const size_t lo = wave * per < n16 ? wave * per : n16;
+    const size_t hi = lo + per < n16 ? lo + per : n16;
     v4u acc = {0, 0, 0, 0};
     size_t base = lo;
     for (; base + chunk <= hi; base += chunk) {

@@ -1023,3 +1023,14 @@ def test_stack_plan_and_run_inside_a_hip_graph():
         torch.cuda.synchronize()
         for i, (lay, w) in enumerate(zip(layers, want)):
             assert torch.equal(lay["y"], w), (rep, i)
+
+
+def test_read_probe_xors_every_word_once():
+    rng = np.random.default_rng(120)
+    for nbytes in (16, 1024, 8 * 64 * 16 * 3 + 48, 5_000_000 // 16 * 16):
+        a = rng.integers(0, 256, nbytes, dtype=np.uint8)
+        out = torch.zeros(1, dtype=torch.int32, device=DEV)
+        mq.mq_read_probe(dev(a), out)
+        torch.cuda.synchronize()
+        want = np.bitwise_xor.reduce(a.view(np.uint32))
+        assert np.uint32(out.cpu().numpy().view(np.uint32)[0]) == want, nbytes
