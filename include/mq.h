@@ -32,6 +32,12 @@
  *   - c is fixed to 8 for packing and the linear kernels; mq_slice_codes
  *     accepts any 1 <= r <= c <= 8.
  *   - group must be 128 and must divide K.
+ *   - Symmetric quantisation (the paper's own runs, appendix "Additional
+ *     Hyperparameter Details": the zero-offset of every group is 2^(c-1) = 128):
+ *     wherever a call takes the tiled zero-offsets `zeros_t` (or `zeros`), NULL
+ *     means exactly that.  No zero-offset is read then, which takes 0.125 bit per
+ *     weight off the stream; results are those of an array filled with 128,
+ *     bit for bit.
  */
 #ifndef MQ_H
 #define MQ_H
@@ -177,7 +183,8 @@ mq_status mq_reslice_many(const mq_reslice_job *jobs, int n_jobs, int c, mq_stre
  *   scales, zeros     : device, fp16 [N, K/group] row-major
  *   scales_t, zeros_t : device, fp16 [Npad/64][K/group][64], each of
  *                       meta_bytes >= mq_meta_bytes(N,K,group); pad rows get 0.
- * Errors: NULL, BAD_SHAPE, BAD_GROUP, BUF_TOO_SMALL. */
+ *   zeros and zeros_t may both be NULL (symmetric layer: only the scales are tiled).
+ * Errors: NULL (also: only one of zeros, zeros_t given), BAD_SHAPE, BAD_GROUP, BUF_TOO_SMALL. */
 mq_status mq_pack_meta(const mq_half *scales, const mq_half *zeros, int64_t N, int64_t K,
                        int group, mq_half *scales_t, mq_half *zeros_t, size_t meta_bytes,
                        mq_stream stream);
@@ -237,7 +244,7 @@ mq_status mq_matgptq_quantize(float *W, int64_t ldw, int64_t N, int64_t K, const
  *   x        : device, fp16 [M, K], 4-byte aligned
  *   packed_W : device, from mq_pack with the same N, K, r; 16-byte aligned
  *   scales_t, zeros_t : device, from mq_pack_meta; 8-byte aligned when M > 4,
- *                       16-byte aligned when M > 16
+ *                       16-byte aligned when M > 16; zeros_t == NULL: symmetric layer
  *   y        : device, fp16 [M, N]; fully overwritten
  *   ws       : device, 256-byte aligned, ws_bytes >= mq_workspace_bytes(M,N,K,r),
  *              initialised once with mq_workspace_init
@@ -307,7 +314,7 @@ mq_status mq_linear_from_parent(const mq_half *x, int64_t M, const void *packed_
 typedef struct {
     const void *packed_W;    /* device, mq_pack(N, K, r); the 8-bit pack of the parent if from_parent */
     const mq_half *scales_t; /* device, mq_pack_meta */
-    const mq_half *zeros_t;  /* device, mq_pack_meta */
+    const mq_half *zeros_t;  /* device, mq_pack_meta; NULL: symmetric layer (every zero-offset 128) */
     const mq_half *x;        /* device, fp16 [M, K] */
     mq_half *y;              /* device, fp16 [M, N] */
     int64_t N, K;

@@ -204,11 +204,12 @@ def mq_unpack(packed, N: int, K: int, c: int, r: int, out=None, stream=None):
 
 
 def mq_pack_meta(scales, zeros, K: int, group: int = MQ_GROUP, stream=None):
+    """zeros=None: symmetric layer; returns (scales_t, None)."""
     import torch
     N = scales.shape[0]
     nbytes = mq_meta_bytes(N, K, group)
     st = torch.empty(max(nbytes // 2, 1), dtype=torch.float16, device=scales.device)
-    zt = torch.empty(max(nbytes // 2, 1), dtype=torch.float16, device=scales.device)
+    zt = None if zeros is None else torch.empty(max(nbytes // 2, 1), dtype=torch.float16, device=scales.device)
     _check(lib().mq_pack_meta(_ptr(scales), _ptr(zeros), N, K, group, _ptr(st), _ptr(zt), nbytes, _stream(stream)),
            "mq_pack_meta")
     return st, zt
@@ -392,7 +393,8 @@ def mq_linear_stack(plan: StackPlan, stream=None) -> None:
 
 # ----------------------------------------------------------------- convenience
 def prepare_layer(parent, scales, zeros, r: int, c: int = 8, group: int = MQ_GROUP) -> dict:
-    """parent/scales/zeros device tensors -> packed layer (slice, pack, meta), all on the GPU."""
+    """parent/scales/zeros device tensors -> packed layer (slice, pack, meta), all on the GPU.
+    zeros=None: symmetric layer (zeros_t is None in the result)."""
     N, K = parent.shape
     S = mq_slice_codes(parent, c, r)
     packed = mq_pack(S, c, r)

@@ -67,7 +67,7 @@ size_t xsum_bytes(int64_t M, int64_t K) {
 }
 
 mq_status layer_status(const mq_layer &l, int64_t M) {
-    if (!l.packed_W || !l.scales_t || !l.zeros_t || !l.x || !l.y) return MQ_ERR_NULL;
+    if (!l.packed_W || !l.scales_t || !l.x || !l.y) return MQ_ERR_NULL;  // zeros_t may be NULL: symmetric layer
     if (!valid_pack_r(l.r)) return MQ_ERR_BAD_R;
     if (M < 1 || M > MQ_MAX_M) return MQ_ERR_BAD_SHAPE;
     if (mq_status st = check_shape(l.N, l.K, l.group)) return st;
@@ -304,7 +304,8 @@ mq_status mq_unpack(const void *packed, int64_t N, int64_t K, int c, int r, uint
 
 mq_status mq_pack_meta(const mq_half *scales, const mq_half *zeros, int64_t N, int64_t K, int group,
                        mq_half *scales_t, mq_half *zeros_t, size_t meta_bytes, mq_stream stream) {
-    if (!scales || !zeros || !scales_t || !zeros_t) return MQ_ERR_NULL;
+    if (!scales || !scales_t) return MQ_ERR_NULL;
+    if ((zeros == nullptr) != (zeros_t == nullptr)) return MQ_ERR_NULL;  // both (asymmetric) or neither (symmetric)
     if (mq_status st = check_shape(N, K, group)) return st;
     if (!aligned(scales, 2) || !aligned(zeros, 2) || !aligned(scales_t, 2) || !aligned(zeros_t, 2))
         return MQ_ERR_ALIGN;
@@ -575,7 +576,7 @@ size_t mq_linear_plain_workspace_bytes(int64_t M, int64_t N, int64_t K, int r) {
 mq_status mq_linear_plain(const mq_half *x, int64_t M, const void *packed_W, const mq_half *scales, const mq_half *zeros,
                           int64_t N, int64_t K, int r, int group, mq_half *y, void *ws, size_t ws_bytes,
                           mq_stream stream) {
-    if (!scales || !zeros || !ws) return MQ_ERR_NULL;
+    if (!scales || !ws) return MQ_ERR_NULL;  // zeros may be NULL: symmetric layer
     if (!valid_pack_r(r)) return MQ_ERR_BAD_R;
     if (M < 1 || M > MQ_MAX_M) return MQ_ERR_BAD_SHAPE;
     if (mq_status st = check_shape(N, K, group)) return st;
@@ -583,7 +584,8 @@ mq_status mq_linear_plain(const mq_half *x, int64_t M, const void *packed_W, con
     if (ws_bytes < mq_linear_plain_workspace_bytes(M, N, K, r)) return MQ_ERR_BUF_TOO_SMALL;
     const size_t inner = align_up(mq_workspace_bytes(M, N, K, r), 256), meta = align_up(mq_meta_bytes(N, K, group), 256);
     char *base = static_cast<char *>(ws);
-    mq_half *st = reinterpret_cast<mq_half *>(base + inner), *zt = reinterpret_cast<mq_half *>(base + inner + meta);
+    mq_half *st = reinterpret_cast<mq_half *>(base + inner);
+    mq_half *zt = zeros ? reinterpret_cast<mq_half *>(base + inner + meta) : nullptr;
     // validate the linear call before anything is enqueued (a failing call enqueues nothing)
     const mq_layer l{packed_W, st, zt, x, y, N, K, r, group, 0, 0};
     if (mq_status s = layer_status(l, M)) return s;

@@ -316,7 +316,8 @@ __device__ __forceinline__ void run_gemm_units(const LayerDesc &L, const StackPa
         const u32x2 MQ_GLOBAL *sp = gl(reinterpret_cast<const u32x2 *>(L.st + (size_t)ut * 64 + lm.rowbase));
 #pragma unroll
         for (int q = 0; q < 4; ++q) t.s4[q] = __builtin_nontemporal_load(sp + 2 * q);
-        t.zl = __builtin_nontemporal_load(gl(L.zt) + (size_t)ut * 64 + lane);
+        // symmetric layer (no zero-offset array): every zero-offset is 2^(c-1)
+        t.zl = L.zt ? __builtin_nontemporal_load(gl(L.zt) + (size_t)ut * 64 + lane) : (_Float16)(float)(1 << (kC - 1));
         t.F = gl(L.xsum)[(size_t)(c * L.G + gt) * kChunkCols + lm.col];
     };
     {

@@ -38,7 +38,8 @@ __device__ __forceinline__ void load_tile(TileRegs<R, M> &t, const LayerDesc &L,
         t.w[4 * i] = v.x; t.w[4 * i + 1] = v.y; t.w[4 * i + 2] = v.z; t.w[4 * i + 3] = v.w;
     }
     t.s = __builtin_nontemporal_load(gl(L.st) + (size_t)u * 64 + lane);
-    t.z = __builtin_nontemporal_load(gl(L.zt) + (size_t)u * 64 + lane);
+    // symmetric layer (no zero-offset array): every zero-offset is 2^(c-1); the branch is uniform over the launch's layer
+    t.z = L.zt ? __builtin_nontemporal_load(gl(L.zt) + (size_t)u * 64 + lane) : (_Float16)(float)(1 << (kC - 1));
 #pragma unroll
     for (int m = 0; m < M; ++m)
         t.xl[m] = gl(reinterpret_cast<const uint32_t *>(L.x + (size_t)m * L.K + (size_t)g * kGroup))[lane];

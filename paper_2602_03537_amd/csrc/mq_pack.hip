@@ -342,7 +342,7 @@ __global__ __launch_bounds__(256) void pack_meta_kernel(const _Float16 *__restri
     const int64_t g = tile - rb * G;
     const int64_t n = rb * kRowBlock + lane;
     st[i] = n < N ? sc[n * G + g] : (_Float16)0.f;
-    zt[i] = n < N ? zr[n * G + g] : (_Float16)0.f;
+    if (zt) zt[i] = n < N ? zr[n * G + g] : (_Float16)0.f;  // a symmetric layer has no zero-offsets to tile
 }
 
 hipError_t launch_pack_meta(const _Float16 *sc, const _Float16 *zr, int64_t N, int64_t G, _Float16 *st, _Float16 *zt,

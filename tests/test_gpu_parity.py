@@ -1034,3 +1034,56 @@ def test_read_probe_xors_every_word_once():
         torch.cuda.synchronize()
         want = np.bitwise_xor.reduce(a.view(np.uint32))
         assert np.uint32(out.cpu().numpy().view(np.uint32)[0]) == want, nbytes
+
+
+# ------------------------------------------------------------------ symmetric layers (no zero-offset array)
+@pytest.mark.parametrize("r", WIDTHS)
+@pytest.mark.parametrize("shape_m", [(200, 768, 1), (130, 384, 3), (512, 4096, 4), (257, 1280, 8), (448, 2048, 16),
+                                     (320, 640, 40), (700, 1152, 200), (1, 256, 1)])
+def test_symmetric_layer_without_zero_offsets(r, shape_m):
+    # zeros_t = NULL means every zero-offset is 128 (the paper's own setting): the oracle gets an array of 128s,
+    # and the library's result equals, bit for bit, what it computes from such an array
+    N, K, M = shape_m
+    L = synth.make_layer(N, K, M=M, seed=[130, N, K, M])
+    L["zeros"] = np.full_like(L["zeros"], 128.0)
+    lay = mq.prepare_layer(dev(L["parent"]), dev(L["scales"]), None, r)
+    assert lay["zeros_t"] is None
+    x = dev(L["x"])
+    ws = mq.new_workspace(M, N, K, r)
+    y = mq.mq_linear(x, lay["packed_W"], lay["scales_t"], None, N, K, r, 128, ws)
+    torch.cuda.synchronize()
+    check_layer(y, L, r, f"symmetric {shape_m} r={r}")
+    full = mq.prepare_layer(dev(L["parent"]), dev(L["scales"]), dev(L["zeros"]), r)
+    y2 = mq.mq_linear(x, full["packed_W"], full["scales_t"], full["zeros_t"], N, K, r, 128, ws)
+    assert torch.equal(y, y2)
+
+
+@pytest.mark.parametrize("M", [1, 8, 40])
+def test_symmetric_stack_from_parent_and_plain(M):
+    shapes_r = [(256, 512, 2), (64, 128, 8), (200, 1280, 3), (512, 256, 6), (130, 384, 4), (1024, 1024, 3)]
+    host, layers = [], []
+    for i, (N, K, r) in enumerate(shapes_r):
+        L = synth.make_layer(N, K, M=M, seed=[131, i, N, K])
+        L["zeros"] = np.full_like(L["zeros"], 128.0)
+        sym = i % 2 == 0                                   # symmetric and asymmetric layers in one stack
+        lay = mq.prepare_layer(dev(L["parent"]), dev(L["scales"]), None if sym else dev(L["zeros"]), r)
+        lay.update(x=dev(L["x"]), y=torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV))
+        host.append(dict(L, r=r))
+        layers.append(lay)
+    plan = mq.mq_stack_plan(layers, M)
+    mq.mq_linear_stack(plan)
+    torch.cuda.synchronize()
+    for i, (lay, L) in enumerate(zip(layers, host)):
+        check_layer(lay["y"], L, L["r"], f"symmetric stack M={M} layer {i}")
+    L = host[2]
+    N, K = L["parent"].shape
+    packed = mq.mq_slice_pack(dev(L["parent"]), C, 3)
+    ws = torch.empty(mq.mq_linear_plain_workspace_bytes(M, N, K, 3), dtype=torch.uint8, device=DEV)
+    mq.mq_workspace_init(ws)
+    y = mq.mq_linear_plain(dev(L["x"]), packed, dev(L["scales"]), None, N, K, 3, 128, ws)
+    check_layer(y, L, 3, f"symmetric plain M={M}")
+    if M <= 4:
+        p8 = mq.mq_pack(dev(L["parent"]), C, 8)
+        st, _ = mq.mq_pack_meta(dev(L["scales"]), None, K)
+        y = mq.mq_linear_from_parent(dev(L["x"]), p8, st, None, N, K, 3, 128, mq.new_workspace(M, N, K, 8))
+        check_layer(y, L, 3, f"symmetric from parent M={M}")

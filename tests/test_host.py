@@ -96,7 +96,9 @@ def test_pack_validation():
     assert L.mq_unpack(FAKE, 64, 128, 8, 7, FAKE, None) == _st("MQ_ERR_BAD_R")
     assert L.mq_unpack(FAKE + 8, 64, 128, 8, 4, FAKE, None) == _st("MQ_ERR_ALIGN")
     assert L.mq_pack_meta(FAKE, FAKE, 64, 256, 64, FAKE, FAKE, big, None) == _st("MQ_ERR_BAD_GROUP")
-    assert L.mq_pack_meta(FAKE, None, 64, 256, 128, FAKE, FAKE, big, None) == _st("MQ_ERR_NULL")
+    assert L.mq_pack_meta(FAKE, None, 64, 256, 128, FAKE, FAKE, big, None) == _st("MQ_ERR_NULL")    # zeros without ...
+    assert L.mq_pack_meta(FAKE, FAKE, 64, 256, 128, FAKE, None, big, None) == _st("MQ_ERR_NULL")    # ... or with only one side
+    assert L.mq_pack_meta(FAKE, None, 64, 256, 128, FAKE, None, 10, None) == _st("MQ_ERR_BUF_TOO_SMALL")   # symmetric: judged on
     assert L.mq_pack_meta(FAKE, FAKE, 64, 256, 128, FAKE, FAKE, 10, None) == _st("MQ_ERR_BUF_TOO_SMALL")
     assert L.mq_pack_meta(FAKE, FAKE + 1, 64, 256, 128, FAKE, FAKE, big, None) == _st("MQ_ERR_ALIGN")
 
@@ -229,8 +231,11 @@ def _linear(L, **kw):
 
 def test_linear_validation():
     L = mq.lib()
-    for k in ("x", "W", "st", "zt", "y", "ws"):
+    for k in ("x", "W", "st", "y", "ws"):
         assert _linear(L, **{k: None}) == _st("MQ_ERR_NULL"), k
+    # zeros_t == NULL is the symmetric layer (every zero-offset 128), not an error: such a call is judged like any
+    # other (here it stops at the next check, the misaligned workspace, so nothing is launched)
+    assert _linear(L, zt=None, ws=FAKE + 64) == _st("MQ_ERR_ALIGN")
     assert _linear(L, r=5) == _st("MQ_ERR_BAD_R")
     assert _linear(L, r=1) == _st("MQ_ERR_BAD_R")
     assert _linear(L, M=0) == _st("MQ_ERR_BAD_SHAPE")
@@ -329,7 +334,8 @@ def test_linear_plain_validation():
 
     def call(x=FAKE, M=1, W=FAKE, s=FAKE, z=FAKE, N=64, K=128, r=4, group=128, y=FAKE, ws=FAKE, wsb=None):
         return L.mq_linear_plain(x, M, W, s, z, N, K, r, group, y, ws, need if wsb is None else wsb, None)
-    assert call(s=None) == _st("MQ_ERR_NULL") and call(z=None) == _st("MQ_ERR_NULL") and call(ws=None) == _st("MQ_ERR_NULL")
+    assert call(s=None) == _st("MQ_ERR_NULL") and call(ws=None) == _st("MQ_ERR_NULL")
+    assert call(z=None, wsb=need - 1) == _st("MQ_ERR_BUF_TOO_SMALL")      # zeros == NULL: symmetric layer, judged on
     assert call(x=None) == _st("MQ_ERR_NULL") and call(W=None) == _st("MQ_ERR_NULL") and call(y=None) == _st("MQ_ERR_NULL")
     assert call(r=5) == _st("MQ_ERR_BAD_R")
     assert call(M=0) == _st("MQ_ERR_BAD_SHAPE") and call(M=257) == _st("MQ_ERR_BAD_SHAPE")
