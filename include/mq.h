@@ -243,8 +243,8 @@ mq_status mq_matgptq_quantize(float *W, int64_t ldw, int64_t N, int64_t K, const
  * accumulation, fp16 output (round to nearest even).
  *   x        : device, fp16 [M, K], 4-byte aligned
  *   packed_W : device, from mq_pack with the same N, K, r; 16-byte aligned
- *   scales_t, zeros_t : device, from mq_pack_meta; 8-byte aligned when M > 4,
- *                       16-byte aligned when M > 16; zeros_t == NULL: symmetric layer
+ *   scales_t, zeros_t : device, from mq_pack_meta; 16-byte aligned when M > 4;
+ *                       zeros_t == NULL: symmetric layer
  *   y        : device, fp16 [M, N]; fully overwritten
  *   ws       : device, 256-byte aligned, ws_bytes >= mq_workspace_bytes(M,N,K,r),
  *              initialised once with mq_workspace_init
@@ -267,8 +267,9 @@ mq_status mq_linear(const mq_half *x, int64_t M, const void *packed_W, const mq_
  * nothing, frees nothing and initialises what it needs itself (one small fill kernel ahead of the
  * layer's launches, all on `stream`).
  *   1 <= M <= 16; larger batches return MQ_ERR_UNSUPPORTED (their partial sums alone exceed the array).
- *   Shapes whose counters + prepared activations + at least 256 partial-sum slot pairs do not fit
- *   the array return MQ_ERR_BUF_TOO_SMALL (every Llama-2-7B and Llama-3-70B linear fits at M <= 16).
+ *   Shapes whose counters + prepared activations + a minimum of partial-sum slot pairs (256 of
+ *   64 x M floats up to M = 4, 32 of 8192 floats above) do not fit the array return
+ *   MQ_ERR_BUF_TOO_SMALL (every Llama-2-7B and Llama-3-70B linear fits at M <= 16).
  * Every call on a GPU uses that GPU's one array: two calls that may overlap in time on the same
  * GPU (different streams, or graphs replayed concurrently) race; calls on one stream do not.  The
  * device current to the calling thread must be the stream's device.  The first call on a device
@@ -327,7 +328,7 @@ typedef struct {
 } mq_layer;
 
 /* Kernels by batch: as mq_linear, except that a stack of packed layers already runs on the matrix
- * cores at M = 4 (scales_t / zeros_t 8-byte aligned from M = 4 on for a stack); stacks computed
+ * cores at M = 4 (scales_t / zeros_t 16-byte aligned from M = 4 on for a stack); stacks computed
  * from the parent stay on the vector ALUs (M <= 4).  A small stack (at most 16 layers and 12288
  * tiles of 64 rows x 128 columns in all, M <= 4: the q/k/v or gate/up linears of a decoder block,
  * which may share one x) is launched for latency, one workgroup per (layer, row block, K slice);

@@ -48,23 +48,22 @@ int64_t chunks(int64_t M) {
 }
 int64_t counters_of(int64_t M, int64_t N) { return chunks(M) * (pad_rows(N) / kRowBlock); }
 int slot_floats(int64_t M) {
-    return use_wide(M) ? 4 * wide_chunks_per_pass(M) * 32 * 64 : use_mfma(M) ? 64 * kChunkCols : 64 * (int)M;
+    return use_wide(M)   ? 4 * wide_chunks_per_pass(M) * 32 * 64
+           : use_mfma(M) ? kNarrowRowBlocks * 64 * kChunkCols
+                         : 64 * (int)M;
 }
-size_t partial_bytes(int64_t M) {
-    const size_t workers = use_wide(M)   ? (size_t)wide_max_groups(wide_chunks_per_pass(M))
-                           : use_mfma(M) ? (size_t)kMaxWavesMfma
-                                         : (size_t)max_workers_valu(M);
-    return workers * 2 * (size_t)slot_floats(M) * sizeof(float);
+size_t max_workers(int64_t M) {
+    return use_wide(M)   ? (size_t)wide_max_groups(wide_chunks_per_pass(M))
+           : use_mfma(M) ? (size_t)kMaxGroupsNarrow
+                         : (size_t)max_workers_valu(M);
 }
-// MFMA paths: re-ordered activations and their group sums for one layer
-size_t xt_bytes(int64_t M, int64_t K, int r) {
+size_t partial_bytes(int64_t M) { return max_workers(M) * 2 * (size_t)slot_floats(M) * sizeof(float); }
+// MFMA paths: prepared activations of one layer (group sums and rescale factors live inside the blocks)
+size_t xt_bytes(int64_t M, int64_t K, int) {
     if (use_wide(M)) return align_up((size_t)wide_chunks_padded(M) * (size_t)(K / kGroup) * kWideXtBlockBytes, 256);
-    return use_mfma(M) ? (size_t)chunks(M) * (size_t)(K / kGroup) * (size_t)(mfma_per_tile(r) + 1) * 256 : 0;
+    return use_mfma(M) ? (size_t)(K / kGroup) * kNarrowXtBlockBytes : 0;
 }
-size_t xsum_bytes(int64_t M, int64_t K) {
-    if (use_wide(M)) return 0;  // the sums live inside the activation blocks
-    return use_mfma(M) ? align_up((size_t)chunks(M) * (size_t)(K / kGroup) * kChunkCols * sizeof(float), 256) : 0;
-}
+size_t xsum_bytes(int64_t, int64_t) { return 0; }
 
 mq_status layer_status(const mq_layer &l, int64_t M) {
     if (!l.packed_W || !l.scales_t || !l.x || !l.y) return MQ_ERR_NULL;  // zeros_t may be NULL: symmetric layer
@@ -73,8 +72,8 @@ mq_status layer_status(const mq_layer &l, int64_t M) {
     if (mq_status st = check_shape(l.N, l.K, l.group)) return st;
     if ((l.from_parent != 0 && l.from_parent != 1) || l.reserved != 0) return MQ_ERR_UNSUPPORTED;
     if (l.from_parent && use_mfma(M)) return MQ_ERR_UNSUPPORTED;  // slicing in registers: vector-ALU kernels only
-    // the MFMA paths read scales / zeros 8 bytes (M <= 16) or 16 bytes (M > 16) at a time
-    const size_t meta_align = use_wide(M) ? 16 : use_mfma(M) ? 8 : 2;
+    // the matrix-core paths move scales / zeros 16 bytes at a time
+    const size_t meta_align = use_mfma(M) ? 16 : 2;
     if (!aligned(l.packed_W, 16) || !aligned(l.x, 4) || !aligned(l.scales_t, meta_align) ||
         !aligned(l.zeros_t, meta_align) || !aligned(l.y, 2))
         return MQ_ERR_ALIGN;
@@ -104,7 +103,10 @@ LayerDesc make_desc(const mq_layer &l, int64_t M, int64_t Mp, uint64_t cost_star
         d.rs = l.r;
         d.cost = valu_tile_cost(kC, (int)M);
     }
-    if (use_mfma(Mp) && !use_wide(Mp)) d.cost = mfma_tile_cost(l.r);
+    if (use_mfma(Mp) && !use_wide(Mp)) {  // scheduled in super-tiles of kNarrowRowBlocks row blocks
+        d.RB = (d.RB + kNarrowRowBlocks - 1) / kNarrowRowBlocks;
+        d.cost = mfma_tile_cost(l.r);
+    }
     if (use_wide(Mp)) {  // scheduled in super-tiles of four row blocks
         d.RB = (d.RB + 3) / 4;
         d.cost = wide_tile_cost(l.r, wide_chunks_per_pass(Mp));
@@ -137,7 +139,8 @@ constexpr uint64_t kPlanMagic = 0x4d51504c414e3037ull;  // "MQPLAN07"
 // The array's name is only a host-side stand-in; its device address is looked up once per device (each device
 // holds its own copy at its own address) and only that pointer is ever handed to a kernel.
 constexpr size_t kScratchBytes = MQ_NOALLOC_SCRATCH_BYTES;
-constexpr size_t kNoallocMinWorkers = 256;  // fewer schedule shares than this would leave most of the chip idle
+constexpr size_t kNoallocMinWorkers = 256;  // fewer schedule shares (waves) than this would leave most of the chip idle
+constexpr size_t kNoallocMinGroups = 32;    // the same for the narrow matrix-core path, whose shares are workgroups of 8 waves
 static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mutex;
@@ -549,9 +552,10 @@ mq_status mq_linear_noalloc(const mq_half *x, int64_t M, const void *packed_W, c
     const size_t cnt_b = counter_bytes(counters_of(M, N));
     const size_t act_b = xt_bytes(M, K, r) + xsum_bytes(M, K);
     const size_t pair_b = 2 * (size_t)slot_floats(M) * sizeof(float);
-    if (cnt_b + act_b + kNoallocMinWorkers * pair_b > kScratchBytes) return MQ_ERR_BUF_TOO_SMALL;
+    const size_t min_workers = use_mfma(M) ? kNoallocMinGroups : kNoallocMinWorkers;
+    if (cnt_b + act_b + min_workers * pair_b > kScratchBytes) return MQ_ERR_BUF_TOO_SMALL;
     size_t cap = (kScratchBytes - cnt_b - act_b) / pair_b;
-    const size_t most = use_mfma(M) ? (size_t)kMaxWavesMfma : (size_t)max_workers_valu(M);
+    const size_t most = max_workers(M);
     if (cap > most) cap = most;
     void *ws = nullptr;
     if (mq_status st = scratch_of_current_device(&ws)) return st;

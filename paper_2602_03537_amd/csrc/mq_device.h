@@ -134,7 +134,7 @@ __device__ __forceinline__ void finish_row_block(const LayerDesc &L, const Stack
     const int w_hi = wave_of(a + (uint64_t)(L.G - 1) * L.cost, p.nworkers, p.cost_total);
     // Fixed summation order (w_lo's slot 1, then slot 0 of w_lo+1 .. w_hi); loads are issued
     // in batches so that their round trips overlap.
-    constexpr int kBatch = NV >= 8 ? 2 : 16;
+    constexpr int kBatch = NV >= 8 ? 8 : 16;  // slots fetched per round trip (NV * kBatch registers)
     float tot[NV];
     const float MQ_GLOBAL *first = gl(p.part + (size_t)(w_lo * 2 + 1) * slot_floats + lane);
 #pragma unroll

@@ -1,62 +1,62 @@
-// Small / medium batch (4 < M <= 256): the same sliced linear layer on the
-// matrix cores (Section 4 of the paper switches to TensorCores from batch 8;
-// here the switch is at M = 5).  Same packed tiles, same persistent schedule and
+// Small batch (4 < M <= 16): the same sliced linear layer on the matrix cores (Section 4 of the paper switches to
+// TensorCores from batch 8; here the switch is at M = 5).  Same packed tiles, same persistent schedule and
 // split-K hand-off (mq_device.h) as the vector-ALU kernel.
 //
-// MFMA mapping.  v_mfma_f32_32x32x16_f16 computes D[32x32] += A[32x16] * B[16x32];
-// lane l supplies A[l%32][8*(l/32) .. +7] and B[8*(l/32) .. +7][l%32].  In the tile
-// layout lane l owns row l of the 64-row tile, and four masked dwords of a lane
-// (the same bit-field of four units) are eight fp16 subnormals = eight columns
-// k_0..k_7 of that row, i.e. already a valid A operand: lanes 0..31 feed tile
-// rows 0..31 as the first k-half, lanes 32..63 feed tile rows 32..63 as the
-// second k-half, both halves carrying the SAME eight columns.  B separates the
-// two halves again: for output column j < 16 it holds x[j][k_e] in the first
-// k-half and zero in the second, for j >= 16 the other way round.  Then
-//   D[i][j]      = sum_e W[row i     ][k_e] * x[j     ][k_e]     (j <  16)
-//   D[i][j]      = sum_e W[row 32 + i][k_e] * x[j - 16][k_e]     (j >= 16)
-// so one MFMA handles 64 rows x 8 columns of W x 16 batch rows (half of B is
-// zeros: the price of sharing one weight layout with the batch-1 kernel).
-// The B operands are prepared once per call by xprep_kernel into the order the
-// MFMAs consume them; lanes whose B is zero read out of range of a buffer
-// resource, which returns 0 without touching memory.
+// MFMA mapping.  v_mfma_f32_32x32x16_f16 computes D[32x32] += A[32x16] * B[16x32]; lane l supplies
+// A[l%32][8*(l/32) .. +7] and B[8*(l/32) .. +7][l%32].  In the tile layout lane l owns row l of the 64-row tile,
+// and four masked dwords of a lane (the same bit-field of four units) are eight fp16 subnormals = eight columns
+// k_0..k_7 of that row, i.e. already a valid A operand: lanes 0..31 feed tile rows 0..31 as the first k-half,
+// lanes 32..63 feed tile rows 32..63 as the second k-half, both halves carrying the SAME eight columns.  B separates
+// the two halves again: for output column j < 16 it holds x[j][k_e] in the first k-half and zero in the second, for
+// j >= 16 the other way round.  Then
+//   D[i][j] = sum_e W[row i][k_e] * x[j][k_e] (j < 16),   D[i][j] = sum_e W[row 32 + i][k_e] * x[j - 16][k_e] (j >= 16)
+// so one MFMA handles 64 rows x 8 columns of W x 16 batch rows (half of B is zeros: the price of sharing one weight
+// layout with the batch-1 kernel; the matrix pipe is not what bounds this kernel).
 //
-// A batch of more than 16 rows is served in chunks of 16 columns; a chunk is
-// scheduled like a layer of its own (chunk index slowest).
-//
-// One accumulator per tile.  A masked field is the fp16 subnormal digit * 2^(p-24) and stands for
-// digit * 2^d of the code (p = position of the field in its half, d = first code bit it carries), so
-// fields with different p - d ("keys") would need accumulators of their own.  Instead the B operand
-// of each MFMA is the activations times 2^(e - (p - d)): every MFMA of a tile then adds
-// code-part * x * 2^(e-24) into the SAME 32x32 accumulator, and no vector instruction touches the
-// accumulator before the group is complete.  e is a block exponent chosen by the prep kernel per
-// (chunk, group, batch column) so that the largest |x| of the group lands in [2^14, 2^15): the scaling
-// is exact for every element within 2^-22 of the group's largest (smaller ones lose low bits worth
-// less than 2^-38 of the largest product: far below the fp32 accumulation itself).
+// One accumulation per tile.  A masked field is the fp16 subnormal digit * 2^(p-24) and stands for digit * 2^d of the
+// code (p = position of the field in its half, d = first code bit it carries).  The B operand of each MFMA is the
+// activations times 2^(e - (p - d)), prepared once per call by xprep_kernel: every MFMA of a tile then adds
+// code-part * x * 2^(e-24) into the same accumulators and no vector instruction touches them before the group is
+// complete.  e is a block exponent per (group, batch column) chosen so that the largest |x| of the group lands in
+// [2^14, 2^15): the scaling is exact for every element within 2^-22 of the group's largest (smaller ones lose low
+// bits worth less than 2^-38 of the largest product: far below the fp32 accumulation itself).
 // The zero-offset rides on the matrix core as well: one more MFMA per tile multiplies the row's zero
-// (A = z * 2^(r-17), exact for every zero >= 2) by -X_g * 2^(e-15) split into three fp16 pieces
-// (relative error 2^-33), so that D = 2^(e+r-32) * sum_k x_k * (S_k - z).  Per group and accumulator
-// element what is left for the vector ALUs is  y += scale * (F * D),  F = 2^(32-r-e)  from the prep
-// kernel: integer codes stay exact and scales are never rounded to fp16, as on the vector-ALU path.
+// (A = z * 2^(r-17), exact for every zero >= 2) by -X_g * 2^(e-15) split into three fp16 pieces (relative error 2^-33),
+// so that D = 2^(e+r-32) * sum_k x_k * (S_k - z).  Per group and accumulator element what is left for the vector ALUs
+// is  y += scale * (F * D),  F = 2^(32-r-e)  from the prep kernel: integer codes stay exact and scales are never
+// rounded to fp16, as on the vector-ALU path.
+//
+// Work split and memory pipeline.  A workgroup of eight waves walks a run of super-tiles (512 rows x one group);
+// wave w owns row block 8*srb + w.  Everything travels global -> LDS without registers (mq_dma.h): the prepared
+// activations of a group (6 KB, shared by the eight waves) into one of the stages, each wave's next weight tiles
+// with their scales and zeros into a ring of its own.  Loads retire in order per wave, so whatever a tile needs must
+// be as old as its weights when it is needed: with every transfer issued from assembly and every wait written out
+// (how many LATER transfers may still be in flight), a tile's operands are always the oldest transfers of the wave
+// and the prefetch distance is what the ring says.  (Left to the compiler, the activation and scale loads of the next
+// tile, issued behind the weight prefetch of a tile three ahead, made every tile wait for that prefetch.)
 #include "mq_device.h"
+#include "mq_dma.h"
 
 namespace mq {
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
-typedef u32x4 uint4_t;
 
 template <int R> struct Mfma {
     using T = Layout<R>;
     static constexpr int NU = 4 * R / T::UD;       // units per lane and tile
     static constexpr int NQ = NU / 4;              // unit quads
-    static constexpr int NMF = NQ * T::NOPS;       // MFMAs per tile
+    static constexpr int NMF = NQ * T::NOPS;       // MFMAs per tile on the masked fields
+    static constexpr int NBLK = NMF + 1;           // operand blocks per tile: theirs and the zero-offset's
     static_assert(NU % 4 == 0, "units must come in quads");
+    static_assert(NBLK * 256 + 64 <= kNarrowXtBlockBytes, "operand blocks and factors must fit the activation block");
 };
+constexpr int kFactorOff = kNarrowXtBlockBytes - 64;  // 16 floats F at the end of an activation block
 
 // ------------------------------------------------------------------ activation prep
-// One wave per (layer, chunk, group): writes the B operands of the NMF MFMAs of a tile
-// (16 columns x 8 halves each) and the per-column group sums X_g.  Branch-free: columns
-// beyond M read column 0 and are masked to zero, all loads are issued before the stores.
+// One wave per (layer, group): writes the activation block of the group: the B operands of the NMF MFMAs of a tile
+// (16 columns x 8 halves each, scaled), the zero-offset block, and the factors F.  Branch-free: columns beyond M
+// read column 0 and are masked to zero, all loads are issued before the stores.
 template <int CTRL> __device__ __forceinline__ float dpp_max(float v) {
     const int t = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false);
     return fmaxf(v, __builtin_bit_cast(float, t));
@@ -67,16 +67,15 @@ __device__ __forceinline__ uint32_t scale_pair(uint32_t v, float scale) {
     const half2_t o = {(_Float16)((float)h.x * scale), (_Float16)((float)h.y * scale)};
     return __builtin_bit_cast(uint32_t, o);
 }
-template <int R> __device__ __forceinline__ void xprep_job(const LayerDesc &L, int c, int g, int lane) {
+template <int R> __device__ __forceinline__ void xprep_job(const LayerDesc &L, int g, int lane) {
     using T = Layout<R>;
     constexpr int NMF = Mfma<R>::NMF;
     const int m = lane >> 2, j = lane & 3;
-    const int col = c * kChunkCols + m;
-    const uint32_t live = col < L.M ? 0xFFFFFFFFu : 0u;
+    const uint32_t live = m < L.M ? 0xFFFFFFFFu : 0u;
     const uint32_t MQ_GLOBAL *xrow =
-        gl(reinterpret_cast<const uint32_t *>(L.x + (size_t)(live ? col : 0) * L.K) + (size_t)g * 64);
-    uint32_t MQ_GLOBAL *out =
-        gl(reinterpret_cast<uint32_t *>(const_cast<uint4 *>(L.xt)) + ((size_t)(c * L.G + g) * (NMF + 1)) * 64 + lane);
+        gl(reinterpret_cast<const uint32_t *>(L.x + (size_t)(live ? m : 0) * L.K) + (size_t)g * 64);
+    uint8_t *block = reinterpret_cast<uint8_t *>(const_cast<uint4 *>(L.xt)) + (size_t)g * kNarrowXtBlockBytes;
+    uint32_t MQ_GLOBAL *out = gl(reinterpret_cast<uint32_t *>(block)) + lane;
     uint32_t v[NMF];
     static_for<NMF>([&](auto mf) {
         constexpr int Q = mf / T::NOPS;
@@ -119,7 +118,7 @@ template <int R> __device__ __forceinline__ void xprep_job(const LayerDesc &L, i
     const half2_t d0 = {p0, p1}, d1 = {p2, (_Float16)0.f};
     out[NMF * 64] = j == 0 ? __builtin_bit_cast(uint32_t, d0) : j == 1 ? __builtin_bit_cast(uint32_t, d1) : 0u;
     // F = 2^(32 - r - e): what turns the accumulator back into code units times Eq. 1's rescale
-    if (j == 0) gl(const_cast<float *>(L.xsum))[(size_t)(c * L.G + g) * kChunkCols + m] = __builtin_ldexpf(1.f, 32 - R - e);
+    if (j == 0) gl(reinterpret_cast<float *>(block + kFactorOff))[m] = __builtin_ldexpf(1.f, 32 - R - e);
 }
 
 __global__ __launch_bounds__(256) void xprep_kernel(const StackParams p) {
@@ -136,14 +135,13 @@ __global__ __launch_bounds__(256) void xprep_kernel(const StackParams p) {
         li = lo;
     }
     const LayerDesc L = p.table ? load_desc(p.table + li) : p.single;
-    const int local = job - L.job_start;
-    const int c = local / L.G, g = local - c * L.G;
+    const int g = job - L.job_start;
     switch (L.r) {
-        case 2: xprep_job<2>(L, c, g, lane); break;
-        case 3: xprep_job<3>(L, c, g, lane); break;
-        case 4: xprep_job<4>(L, c, g, lane); break;
-        case 6: xprep_job<6>(L, c, g, lane); break;
-        default: xprep_job<8>(L, c, g, lane); break;
+        case 2: xprep_job<2>(L, g, lane); break;
+        case 3: xprep_job<3>(L, g, lane); break;
+        case 4: xprep_job<4>(L, g, lane); break;
+        case 6: xprep_job<6>(L, g, lane); break;
+        default: xprep_job<8>(L, g, lane); break;
     }
 }
 
@@ -151,7 +149,7 @@ __global__ __launch_bounds__(256) void xprep_kernel(const StackParams p) {
 // D layout of a 32x32 accumulator: register v of lane l is D[8*(v/4) + 4*(l/32) + v%4][l%32];
 // output column j = l%32 maps to batch column j%16 and tile-row half j/16.
 struct LaneMap {
-    int col;        // batch column inside the chunk
+    int col;        // batch column
     int rowbase;    // tile row of v = 0: 32*(j/16) + 4*(l/32); row(v) = rowbase + 8*(v/4) + v%4
     bool b_live;    // as a B supplier the lane is k-half l/32 of output column j: non-zero only if l/32 == j/16
 };
@@ -164,12 +162,22 @@ __device__ __forceinline__ LaneMap lane_map(int lane) {
     return m;
 }
 
-// Per-wave LDS: two stages of prepared activations (the B operands of one tile each) so
-// that B is read just in time with ds_read instead of being held in 64..80 registers.
-constexpr int kStageBytes = 6 * 1024;                 // >= (NMF + 1) * 256 for every width (NMF <= 20)
-constexpr int kWaveLds = 2 * kStageBytes;
-constexpr int kZeroOff = 4 * kWaveLds;                // 16 zero bytes after the four waves' stages
-constexpr int kLdsBytes = kZeroOff + 16;
+// LDS plan of a workgroup (one per compute unit): activation stages shared by the eight waves (one being read, the
+// others landing) and per wave a ring of NBR weight tiles with their scale and zero lines.
+constexpr int kNarrowWaves = kNarrowRowBlocks;  // waves per workgroup = row blocks per super-tile
+constexpr int kStageBytes = kNarrowXtBlockBytes;
+constexpr int narrow_slot_bytes(int R) { return R * 1024 + 256; }
+constexpr int narrow_ring(int R) { return R <= 4 ? 3 : 2; }
+constexpr int narrow_stages(int R) { return narrow_ring(R) + 1; }  // activations need the same lead as the weights
+constexpr int narrow_lds_bytes(int R) {
+    return narrow_stages(R) * kStageBytes + kNarrowWaves * narrow_ring(R) * narrow_slot_bytes(R);
+}
+constexpr int narrow_lds_bytes_max() {
+    int m = 0;
+    for (int r : {2, 3, 4, 6, 8}) m = narrow_lds_bytes(r) > m ? narrow_lds_bytes(r) : m;
+    return m;
+}
+static_assert(narrow_lds_bytes_max() <= 160 * 1024, "LDS plan does not fit");
 
 __device__ __forceinline__ float half_of(u32x2 v, int e) {
     const uint32_t w = e < 2 ? v.x : v.y;
@@ -177,178 +185,191 @@ __device__ __forceinline__ float half_of(u32x2 v, int e) {
     return (float)__builtin_bit_cast(_Float16, h);
 }
 
-template <int R> struct GemmCtx {
-    using MF = Mfma<R>;
-    static constexpr int NBLK = MF::NMF + 1;                // operand blocks per tile: the MFMAs' and the zero-offset's
-    static constexpr int NXL = (NBLK * 256 + 1023) / 1024;  // 1 KiB wave-loads per tile of activations
-    const LayerDesc &L;
-    const LaneMap lm;
-    const int lane, c;
-    __amdgpu_buffer_rsrc_t xt;
-    uint8_t *lds;   // this wave's two stages
-    uint8_t *zero;  // 16 zero bytes
-
-    __device__ __forceinline__ void load_w(uint32_t (&w)[4 * R], int u) const {
-        const u32x4 MQ_GLOBAL *src = gl(reinterpret_cast<const u32x4 *>(L.Wp) + (size_t)u * (R * 64) + lane);
-#pragma unroll
-        for (int i = 0; i < R; ++i) {
-            const u32x4 v = __builtin_nontemporal_load(src + i * 64);  // read once per call: streaming hint
-            w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
-        }
-    }
-    // activations of group g of this chunk: NXL coalesced 16-byte loads (past the end of the buffer -> 0).
-    // A lane copies the 16 bytes of batch column lane % 16 of four MFMA blocks; columns beyond M hold zeros,
-    // so their lanes read out of range instead (0 comes back and no memory is touched: at M = 8 half the
-    // activation traffic, which is as large as a 4-bit weight tile, is never requested).
-    __device__ __forceinline__ void load_x(u32x4 (&xb)[NXL], int g) const {
-        const bool live = c * kChunkCols + (lane & 15) < L.M;
-        const uint32_t off = live ? (uint32_t)(c * L.G + g) * (NBLK * 256u) + (uint32_t)lane * 16u : 0x80000000u;
-#pragma unroll
-        for (int i = 0; i < NXL; ++i) xb[i] = __builtin_amdgcn_raw_buffer_load_b128(xt, off + i * 1024, 0, 0);
-    }
-    // (lanes that copy a batch column beyond M have nothing to store: nobody reads those bytes)
-    __device__ __forceinline__ void store_x(const u32x4 (&xb)[NXL], int stage) const {
-        if (c * kChunkCols + (lane & 15) >= L.M) return;
-        u32x4 *dst = reinterpret_cast<u32x4 *>(lds + stage * kStageBytes) + lane;
-#pragma unroll
-        for (int i = 0; i < NXL; ++i) dst[i * 64] = xb[i];
-    }
-};
-
-// One tile: NMF MFMAs on the masked fields, one on the zero-offset, then y += scale * (F * D).  B comes from LDS
-// stage `stage`, read four MFMAs ahead of its use so that the LDS latency overlaps the previous MFMAs.
-//   zl : zero-offset of the lane's OWN row (the lane is an A supplier of that row)
-//   s4 : scales of the 16 rows the lane holds accumulator elements of
+// Super-tiles [u_begin, u_end) of one layer (u = srb * G + g), for the whole workgroup.
 template <int R>
-__device__ __forceinline__ void gemm_tile_math(const GemmCtx<R> &cx, const uint32_t (&w)[4 * R], int stage,
-                                               const u32x2 (&s4)[4], _Float16 zl, float F, float (&yacc)[16]) {
+__device__ __forceinline__ void run_narrow_units(const LayerDesc &L, const StackParams &p, int u_begin, int u_end,
+                                                 int worker, int wv, int lane, MQ_LDS uint8_t *lds) {
     using T = Layout<R>;
     using MF = Mfma<R>;
-    constexpr int kAhead = 4;
-    constexpr int NBLK = MF::NMF + 1;
-    // Lanes whose B operand is zero do not read at all (their registers are cleared once per tile): an LDS read
-    // costs its bandwidth per active lane, and B operands are what the LDS pipe is busy with in this kernel.
-    const u32x4 *bsrc = reinterpret_cast<const u32x4 *>(cx.lds + stage * kStageBytes) + cx.lm.col;
-    constexpr int bstep = 16;  // u32x4 elements per operand block (256 bytes)
-    u32x4 bq[kAhead];          // ring of B operands in flight
-    static_for<kAhead>([&](auto i) { bq[i] = u32x4{0u, 0u, 0u, 0u}; });
-    if (cx.lm.b_live) static_for<kAhead>([&](auto i) { bq[i] = bsrc[i * bstep]; });
-    float16_t D;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) D[v] = 0.f;
-    static_for<MF::NMF>([&](auto mf) {
-        constexpr int Q = mf / T::NOPS;
-        constexpr Op o = T::op(mf % T::NOPS);
-        uint32_t a[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            uint32_t v = w[(4 * Q + j) * T::UD + o.dw];
-            if constexpr (o.sh != 0) v >>= o.sh;
-            a[j] = v & ((uint32_t)o.mask * 0x10001u);
-        }
-        const u32x4 av = {a[0], a[1], a[2], a[3]};
-        const u32x4 bv = bq[mf % kAhead];
-        if constexpr (mf + kAhead < NBLK) {
-            if (cx.lm.b_live) bq[mf % kAhead] = bsrc[(mf + kAhead) * bstep];
-        }
-        D = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, av), __builtin_bit_cast(half8_t, bv), D,
-                                                   0, 0, 0);
-    });
-    {   // zero-offset: A = (z', z', z', 0, ...) with z' = z * 2^(r-17), B = -X_g * 2^(e-15) in three pieces
-        const _Float16 zs = zl * (_Float16)__builtin_ldexpf(1.f, R - 17);
-        const half2_t zz = {zs, zs}, z0 = {zs, (_Float16)0.f};
-        const u32x4 av = {__builtin_bit_cast(uint32_t, zz), __builtin_bit_cast(uint32_t, z0), 0u, 0u};
-        D = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, av),
-                                                   __builtin_bit_cast(half8_t, bq[MF::NMF % kAhead]), D, 0, 0, 0);
-    }
-#pragma unroll
-    for (int v = 0; v < 16; ++v) yacc[v] = fmaf(half_of(s4[v >> 2], v & 3), D[v] * F, yacc[v]);
-}
+    constexpr int NBR = narrow_ring(R), NST = narrow_stages(R);
+    constexpr int kSlot = narrow_slot_bytes(R);
+    constexpr int kTileOps = R + 2;         // transfers per weight tile: R lines, scales, zeros
+    constexpr int kBody = 1 + kTileOps;     // transfers a wave issues per tile body: one activation line first
+    const int G = L.G;
+    const int rb_real = (L.N + kRowBlock - 1) / kRowBlock;
+    const uint8_t *xt = reinterpret_cast<const uint8_t *>(L.xt);
+    MQ_LDS uint8_t *ring = lds + NST * kStageBytes + wv * (NBR * kSlot);
+    const LaneMap lm = lane_map(lane);
+    const bool b_live = lm.b_live && lm.col < L.M;  // a lane whose batch column lies beyond M supplies zeros as well
 
-// Weight tiles a wave keeps in flight ahead of the one it is working on.  The ring has an even number of
-// buffers (depth + 1) so that the two-deep ring of scales / zero / factor below keeps compile-time indices.
-template <int R> struct GemmDepth {
-    static constexpr int value = R <= 6 ? 3 : 1;
-};
-
-// Tiles [u_begin, u_end) of chunk c of one layer (tile index u = rb*G + g).
-template <int R>
-__device__ __forceinline__ void run_gemm_units(const LayerDesc &L, const StackParams &p, int c, int u_begin, int u_end,
-                                               int wave, int lane, uint8_t *lds_wave, uint8_t *lds_zero) {
-    using MF = Mfma<R>;
-    using Ctx = GemmCtx<R>;
-    constexpr int D = GemmDepth<R>::value, NB = D + 1;
-    const uint32_t xt_bytes = (uint32_t)L.CB * L.G * (MF::NMF + 1) * 256u;
-    LaneMap lmap = lane_map(lane);
-    // a lane whose output column lies beyond M supplies zeros as B: it reads the 16 zero bytes instead of its stage
-    lmap.b_live = lmap.b_live && c * kChunkCols + lmap.col < L.M;
-    const Ctx cx{L, lmap, lane, c,
-                 __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(L.xt), 0, (int)xt_bytes, 0x00020000), lds_wave,
-                 lds_zero};
-    const LaneMap &lm = cx.lm;
-    int rb = u_begin / L.G;
-    int g = u_begin - rb * L.G;
+    int srb = u_begin / G;
+    int g = u_begin - srb * G;
     int ga = g;
     float yacc[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) yacc[v] = 0.f;
-    const int col = c * kChunkCols + lm.col;
-    const bool fast_store = (L.N & 3) == 0 && (reinterpret_cast<uintptr_t>(L.y) & 7) == 0;
 
-    // ring of NB weight buffers with compile-time indices (no register copies); past the end
-    // of the run the last tile is fetched again instead of branching around the loads
-    uint32_t w[NB][4 * R];
-    int u_pf = u_begin;
-    auto prefetch_w = [&](uint32_t (&dst)[4 * R]) {
-        cx.load_w(dst, u_pf);
-        if (u_pf + 1 < u_end) ++u_pf;
+    // ---- weights: kTileOps transfers per tile into ring slot `slot`; past the end of the run the last tile is
+    // fetched again (the number of transfers per tile body must not depend on the data)
+    int s_pf = srb, g_pf = g, n_pf = u_end - u_begin;  // tile to fetch next, tiles left to fetch
+    constexpr int kWBlocks = (R + 3) / 4;  // pieces of a tile transfer: weight blocks of up to four lines, scales, zeros
+    auto fetch_tile_piece = [&](auto piece, int slot) {
+        int rb = kNarrowRowBlocks * s_pf + wv;
+        if (rb >= rb_real) rb = rb_real - 1;  // a wave without rows of its own repeats the last block and discards the result
+        const size_t tile = (size_t)rb * G + g_pf;
+        MQ_LDS uint8_t *dst = ring + slot * kSlot;
+        if constexpr (piece < kWBlocks) {
+            dma_block<R, piece, true>(reinterpret_cast<const uint8_t *>(L.Wp) + tile * (R * 1024) + lane * 16, dst);
+        } else if constexpr (piece == kWBlocks) {
+            if (lane < 8) dma_lines<1, true>(reinterpret_cast<const uint8_t *>(L.st) + tile * 128 + lane * 16, dst + R * 1024);
+        } else {
+            // a symmetric layer has no zero-offset array: its scales line is transferred once more (a cache hit),
+            // because the number of transfers per body is what the waits count
+            const uint8_t *zsrc = reinterpret_cast<const uint8_t *>(L.zt ? L.zt : L.st);
+            if (lane < 8) dma_lines<1, true>(zsrc + tile * 128 + lane * 16, dst + R * 1024 + 128);
+            if (n_pf > 1) {
+                --n_pf;
+                if (++g_pf == G) { g_pf = 0; ++s_pf; }
+            }
+        }
     };
-    // Scales, zero-offset and rescale factor of a tile are fetched one tile ahead, BEFORE that iteration's weight
-    // prefetch: loads return in order, so waiting for anything issued after the prefetch would wait for the prefetch
-    // itself (a full trip to HBM per tile).  Every wait of the loop is then for a load at least one tile old.
-    static_assert(NB % 2 == 0, "the two-deep meta ring relies on an even unroll");
-    struct TileMeta {
-        u32x2 s4[4];
-        _Float16 zl;
-        float F;
-    } meta[2];
-    auto load_meta = [&](TileMeta &t, int ut, int gt) {
-        const u32x2 MQ_GLOBAL *sp = gl(reinterpret_cast<const u32x2 *>(L.st + (size_t)ut * 64 + lm.rowbase));
+    auto fetch_tile = [&](int slot) { static_for<kWBlocks + 2>([&](auto piece) { fetch_tile_piece(piece, slot); }); };
+    // ---- activations of the next group in line -> LDS stage; one 1 KB line per wave (the block has six lines:
+    // waves 6 and 7 repeat lines 4 and 5, the same bytes to the same place); past the end the last group again
+    int g_x = g, n_x = u_end - u_begin;
+    const int xline = wv < 6 ? wv : wv - 2;
+    auto fetch_x = [&](int stage) {
+        dma_lines<1>(xt + (size_t)g_x * kNarrowXtBlockBytes + xline * 1024 + lane * 16, lds + stage * kStageBytes + xline * 1024);
+        if (n_x > 1) {
+            --n_x;
+            if (++g_x == G) g_x = 0;
+        }
+    };
+    // ---- ring slot -> registers: lane dwords, scales of the 16 rows the lane holds accumulator elements of, and the
+    // zero-offset of the lane's own row (the lane is an A supplier of that row)
+    uint32_t w[4 * R];
+    u32x2 s4[4];
+    _Float16 zl;
+    auto open_tile = [&](int slot) {
+        const MQ_LDS uint8_t *src = ring + slot * kSlot;
+        const MQ_LDS u32x4 *wsrc = reinterpret_cast<const MQ_LDS u32x4 *>(src) + lane;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) t.s4[q] = __builtin_nontemporal_load(sp + 2 * q);
-        // symmetric layer (no zero-offset array): every zero-offset is 2^(c-1)
-        t.zl = L.zt ? __builtin_nontemporal_load(gl(L.zt) + (size_t)ut * 64 + lane) : (_Float16)(float)(1 << (kC - 1));
-        t.F = gl(L.xsum)[(size_t)(c * L.G + gt) * kChunkCols + lm.col];
+        for (int i = 0; i < R; ++i) {
+            const u32x4 v = wsrc[i * 64];
+            w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
+        }
+        const MQ_LDS u32x2 *sp = reinterpret_cast<const MQ_LDS u32x2 *>(src + R * 1024 + 2 * lm.rowbase);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) s4[q] = sp[2 * q];
+        zl = reinterpret_cast<const MQ_LDS _Float16 *>(src + R * 1024 + 128)[lane];
+        if (!L.zt) zl = (_Float16)(float)(1 << (kC - 1));
     };
+
     {
-        u32x4 xb[Ctx::NXL];
-        cx.load_x(xb, g);
-        load_meta(meta[0], u_begin, g);
-        static_for<D>([&](auto j) { prefetch_w(w[j]); });
-        cx.store_x(xb, 0);
+        lds_barrier();  // the previous run's readers are done with all stages
+#pragma unroll
+        for (int k = 0; k < NST - 1; ++k) fetch_x(k);
+#pragma unroll
+        for (int k = 0; k < NBR; ++k) fetch_tile(k);
+        wait_transfers<0>();
+        open_tile(0);
+        lds_barrier();
     }
-    int u = u_begin;
-    int st = 0;  // LDS stage holding the current tile's activations
-    while (u < u_end) {
-        static_for<NB>([&](auto j) {
-            if (u >= u_end) return;
-            const bool more = u + 1 < u_end;
-            const int g_next = more ? (g + 1 == L.G ? 0 : g + 1) : g;
-            u32x4 xb[Ctx::NXL];
-            cx.load_x(xb, g_next);              // first: it is awaited first (loads return in order)
-            load_meta(meta[(j + 1) % 2], more ? u + 1 : u, g_next);
-            __builtin_amdgcn_sched_barrier(0);  // ... and these must really be issued ahead of the prefetch
-            prefetch_w(w[(j + D) % NB]);
-            __builtin_amdgcn_sched_barrier(0);  // keep the loads up here, ahead of the math
-            gemm_tile_math<R>(cx, w[j], st, meta[j % 2].s4, meta[j % 2].zl, meta[j % 2].F, yacc);
-            cx.store_x(xb, st ^ 1);
-            st ^= 1;
-            ++g;
-            ++u;
-            if (g == L.G || u == u_end) {
-                const uint64_t a = L.cost_start + ((uint64_t)c * L.RB * L.G + (uint64_t)rb * L.G) * L.cost;
+
+    int st = 0;
+    int slot_cur = 0;  // ring slot of tile u (already in registers)
+    for (int u = u_begin; u < u_end; ++u) {
+        const bool more = u + 1 < u_end;
+        const int slot_next = slot_cur + 1 == NBR ? 0 : slot_cur + 1;
+        const int st_next = st + 1 == NST ? 0 : st + 1;
+        const int st_fill = st == 0 ? NST - 1 : st - 1;
+        // This body's transfers, in this order: the stage read during the previous body takes the activations NST-1
+        // tiles ahead, the ring slot of tile u (all of it is in registers) takes tile u + NBR.  They are issued piece by
+        // piece between the MFMAs below: the eight waves of a compute unit share one path from the caches (64 bytes per
+        // clock), and issued in one burst ahead of the math their transfers queue up behind each other while the matrix
+        // pipe idles, and the waves reach the barrier as far apart as the queue is long.
+        constexpr int kPieces = 1 + kWBlocks + 2;
+        constexpr int kPieceStride = MF::NMF / kPieces;
+        static_assert(kPieceStride >= 1, "more pieces than MFMAs");
+        auto issue_piece = [&](auto pc) {
+            if constexpr (pc == 0) fetch_x(st_fill);
+            else fetch_tile_piece(IntC<pc - 1>{}, slot_cur);
+        };
+
+        // ---- one tile: NMF MFMAs on the masked fields, one on the zero-offset, into two accumulators taken
+        // alternately (an MFMA that adds to the result of the one before it cannot issue until that result has left
+        // the pipe), then y += scale * (F * D).  B operands come from the stage, read a few MFMAs ahead; lanes whose
+        // operand is zero do not read.
+        const MQ_LDS u32x4 *bsrc = reinterpret_cast<const MQ_LDS u32x4 *>(lds + st * kStageBytes) + lm.col;
+        const float F = reinterpret_cast<const MQ_LDS float *>(lds + st * kStageBytes + kFactorOff)[lm.col];
+        constexpr int kAhead = 4;
+        u32x4 bq[kAhead];
+        static_for<kAhead>([&](auto i) { bq[i] = u32x4{0u, 0u, 0u, 0u}; });
+        if (b_live) static_for<kAhead>([&](auto i) { bq[i] = bsrc[i * 16]; });
+        float16_t D0, D1;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) D0[v] = D1[v] = 0.f;
+        static_for<MF::NMF>([&](auto mf) {
+            constexpr int Q = mf / T::NOPS;
+            constexpr Op o = T::op(mf % T::NOPS);
+            uint32_t a[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t v = w[(4 * Q + j) * T::UD + o.dw];
+                if constexpr (o.sh != 0) v >>= o.sh;
+                a[j] = v & ((uint32_t)o.mask * 0x10001u);
+            }
+            const u32x4 av = {a[0], a[1], a[2], a[3]};
+            const u32x4 bv = bq[mf % kAhead];
+            if constexpr (mf + kAhead < MF::NBLK) {
+                if (b_live) bq[mf % kAhead] = bsrc[(mf + kAhead) * 16];
+            }
+            if constexpr (mf % 2 == 0)
+                D0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, av), __builtin_bit_cast(half8_t, bv),
+                                                            D0, 0, 0, 0);
+            else
+                D1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, av), __builtin_bit_cast(half8_t, bv),
+                                                            D1, 0, 0, 0);
+            if constexpr (mf % kPieceStride == 0 && mf / kPieceStride < kPieces) {
+                __builtin_amdgcn_sched_barrier(0);
+                issue_piece(IntC<mf / kPieceStride>{});
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        });
+        {   // zero-offset: A = (z', z', z', 0, ...) with z' = z * 2^(r-17), B = -X_g * 2^(e-15) in three pieces
+            const _Float16 zs = zl * (_Float16)__builtin_ldexpf(1.f, R - 17);
+            const half2_t zz = {zs, zs}, z0 = {zs, (_Float16)0.f};
+            const u32x4 av = {__builtin_bit_cast(uint32_t, zz), __builtin_bit_cast(uint32_t, z0), 0u, 0u};
+            const u32x4 bv = bq[MF::NMF % kAhead];
+            if constexpr (MF::NMF % 2 == 0)
+                D0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, av), __builtin_bit_cast(half8_t, bv),
+                                                            D0, 0, 0, 0);
+            else
+                D1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, av), __builtin_bit_cast(half8_t, bv),
+                                                            D1, 0, 0, 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) yacc[v] = fmaf(half_of(s4[v >> 2], v & 3), (D0[v] + D1[v]) * F, yacc[v]);
+
+        // tile u+1 has landed once at most the transfers of the NBR-1 bodies after its own are in flight
+        wait_transfers<(NBR - 1) * kBody>();
+        open_tile(slot_next);
+        // the next tile's activations were issued NST-2 bodies ago, ahead of that body's weight tile
+        wait_transfers<(NST - 2) * kBody + kTileOps>();
+        lds_barrier();  // next stage complete for every wave, current stage free
+        st = st_next;
+        slot_cur = slot_next;
+        ++g;
+        if (g == G || !more) {
+            const int rb = kNarrowRowBlocks * srb + wv;
+            if (rb < rb_real) {
+                const uint64_t a = L.cost_start + (uint64_t)srb * G * L.cost;
+                StackParams pw = p;  // this wave's eighth of the workgroup's slots
+                pw.part = p.part + (size_t)wv * (16 * 64);
                 const int row0 = rb * kRowBlock + lm.rowbase;
-                finish_row_block<16>(L, p, p.cnt + L.cnt_off + c * L.RB + rb, a, ga, g, yacc, wave, lane,
+                const int col = lm.col;
+                const bool fast_store = (L.N & 3) == 0 && (reinterpret_cast<uintptr_t>(L.y) & 7) == 0;
+                finish_row_block<16>(L, pw, p.cnt + L.cnt_off + rb, a, ga, g, yacc, worker, lane,
                                      [&](const float(&tot)[16]) {
                                          if (col >= L.M) return;
                                          _Float16 MQ_GLOBAL *yrow = gl(L.y + (size_t)col * L.N);
@@ -368,69 +389,86 @@ __device__ __forceinline__ void run_gemm_units(const LayerDesc &L, const StackPa
                                              }
                                          }
                                      });
-                ++rb;
-                g = 0;
-                ga = 0;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) yacc[v] = 0.f;
             }
-        });
+            if (g == G) { ++srb; g = 0; }
+            ga = g;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) yacc[v] = 0.f;
+            // Everything the hand-over loaded or stored has retired before the tile loop goes on: the compiler keeps
+            // count of ITS memory instructions only and would otherwise protect their registers at the top of every
+            // following tile with a wait that also drains the transfers in flight.
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), other counters untouched
+        }
     }
+    wait_transfers<0>();  // nothing of this run may land in LDS after the next run has started
 }
 
-__global__ __launch_bounds__(256, 2) void gemm_stack_kernel(const StackParams p) {
-    __shared__ __attribute__((aligned(16))) uint8_t lds[kLdsBytes];
+__global__ __launch_bounds__(64 * kNarrowWaves, 1) void gemm_stack_kernel(const StackParams p) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_generic[];
+    MQ_LDS uint8_t *lds = (MQ_LDS uint8_t *)lds_generic;
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane((int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6));
-    if (wave >= p.nwaves) return;
-    uint8_t *lds_wave = lds + (threadIdx.x >> 6) * kWaveLds;
-    uint8_t *lds_zero = lds + kZeroOff;
-    if (lane < 4) reinterpret_cast<uint32_t *>(lds_zero)[lane] = 0u;  // every wave writes the same zeros before it reads them
-    walk_tiles(p, wave, [&](const LayerDesc &L, int u_begin, int u_end) {
-        const int per_chunk = L.RB * L.G;
-        for (int c = u_begin / per_chunk; c < L.CB && c * per_chunk < u_end; ++c) {
-            const int lo = (u_begin > c * per_chunk ? u_begin : c * per_chunk) - c * per_chunk;
-            const int hi = (u_end < (c + 1) * per_chunk ? u_end : (c + 1) * per_chunk) - c * per_chunk;
-            if (lo >= hi) continue;
-            switch (L.r) {
-                case 2: run_gemm_units<2>(L, p, c, lo, hi, wave, lane, lds_wave, lds_zero); break;
-                case 3: run_gemm_units<3>(L, p, c, lo, hi, wave, lane, lds_wave, lds_zero); break;
-                case 4: run_gemm_units<4>(L, p, c, lo, hi, wave, lane, lds_wave, lds_zero); break;
-                case 6: run_gemm_units<6>(L, p, c, lo, hi, wave, lane, lds_wave, lds_zero); break;
-                default: run_gemm_units<8>(L, p, c, lo, hi, wave, lane, lds_wave, lds_zero); break;
-            }
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int worker = blockIdx.x;
+    walk_tiles(p, worker, [&](const LayerDesc &L, int u_begin, int u_end) __attribute__((always_inline)) {
+        switch (L.r) {
+            case 2: run_narrow_units<2>(L, p, u_begin, u_end, worker, wv, lane, lds); break;
+            case 3: run_narrow_units<3>(L, p, u_begin, u_end, worker, wv, lane, lds); break;
+            case 4: run_narrow_units<4>(L, p, u_begin, u_end, worker, wv, lane, lds); break;
+            case 6: run_narrow_units<6>(L, p, u_begin, u_end, worker, wv, lane, lds); break;
+            default: run_narrow_units<8>(L, p, u_begin, u_end, worker, wv, lane, lds); break;
         }
     });
 }
 
-static int gemm_resident_waves() {
-    static int cached = 0;
-    if (cached) return cached;
+// workgroups the device keeps resident for a launch with lds_bytes of LDS per workgroup
+static int narrow_resident_groups(int lds_bytes) {
+    static int cached_bytes[2] = {0, 0}, cached[2] = {0, 0};
+    for (int i = 0; i < 2; ++i)
+        if (cached_bytes[i] == lds_bytes) return cached[i];
     int dev = 0, cus = 0, blocks = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, gemm_stack_kernel, 256, 0) != hipSuccess) return 0;
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_stack_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            narrow_lds_bytes_max()) != hipSuccess)
+        return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, gemm_stack_kernel, 64 * kNarrowWaves, lds_bytes) != hipSuccess)
+        return 0;
     if (blocks < 1) blocks = 1;
-    int w = cus * blocks * 4;
-    if (w > kMaxWavesMfma) w = kMaxWavesMfma;
-    cached = w;
+    int w = cus * blocks;
+    if (w > kMaxGroupsNarrow) w = kMaxGroupsNarrow;
+    const int slot = cached_bytes[0] == 0 ? 0 : 1;
+    cached_bytes[slot] = lds_bytes;
+    cached[slot] = w;
     return w;
 }
 
 hipError_t launch_stack_mfma(StackParams p, int max_cost, hipStream_t s) {
-    int hw = gemm_resident_waves();
+    // LDS per workgroup: a single layer takes the plan of its width, a stack the largest plan
+    int lds_bytes = narrow_lds_bytes_max();
+    if (!p.table) {
+        switch (p.single.r) {
+            case 2: lds_bytes = narrow_lds_bytes(2); break;
+            case 3: lds_bytes = narrow_lds_bytes(3); break;
+            case 4: lds_bytes = narrow_lds_bytes(4); break;
+            case 6: lds_bytes = narrow_lds_bytes(6); break;
+            default: lds_bytes = narrow_lds_bytes(8); break;
+        }
+    }
+    int hw = narrow_resident_groups(lds_bytes);
     if (hw <= 0) return hipErrorUnknown;
     if (p.worker_cap && hw > p.worker_cap) hw = p.worker_cap;
-    // shares of at least four tiles: with one tile per wave a small layer (a 4096 x 4096 one has 2048 tiles) hands
-    // every row block over between as many waves as it has groups, which costs more than the parallelism gains
-    // (measured on the Llama-2-7B shapes at M = 8: 26 -> 19 us per call)
+    // every share at least one super-tile long (that makes a row block's contributor list exact); small layers are not
+    // cut finer than four super-tiles per share, because every cut is a hand-over between workgroups and a workgroup's
+    // start-up (first transfers, one full trip to memory) is worth several tiles (measured on the Llama-2-7B shapes
+    // at M = 8 and 16: 23.0 -> 20.1, 24.4 -> 23.0, 33.6 -> 31.1 us per call against two)
     uint64_t cap = p.cost_total / ((uint64_t)max_cost * 4);
     if (cap < 1) cap = 1;
-    p.nwaves = (int)(cap < (uint64_t)hw ? cap : (uint64_t)hw);
-    p.nworkers = p.nwaves;
+    p.nworkers = (int)(cap < (uint64_t)hw ? cap : (uint64_t)hw);
+    p.nwaves = p.nworkers * kNarrowWaves;
+    p.slot_floats = kNarrowWaves * 16 * 64;
     const hipError_t e = launch(xprep_kernel, dim3((unsigned)((p.n_jobs + 3) / 4)), dim3(256), 0, s, p);
     if (e != hipSuccess) return e;
-    return launch(gemm_stack_kernel, dim3((unsigned)((p.nwaves + 3) / 4)), dim3(256), 0, s, p);
+    return launch(gemm_stack_kernel, dim3((unsigned)p.nworkers), dim3(64 * kNarrowWaves), (unsigned)lds_bytes, s, p);
 }
 
 }  // namespace mq

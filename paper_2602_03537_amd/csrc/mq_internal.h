@@ -17,7 +17,11 @@ namespace mq {
 // and the kernel's occupancy and launches min(what is resident there, the cap), so a smaller or larger part stays
 // correct and only loses the slots it cannot use.  (8192 = 256 compute units x 32 waves, the MI355X.)
 constexpr int kMaxWaves = 8192;
-constexpr int kMaxWavesMfma = 4096;  // the MFMA kernel runs at most 2 waves per SIMD
+// Narrow matrix-core path (kValuMaxM < M <= kNarrowMaxM): a workgroup of kNarrowRowBlocks waves owns a super-tile of
+// kNarrowRowBlocks row blocks x one group; one workgroup per compute unit.
+constexpr int kNarrowRowBlocks = 8;
+constexpr int kMaxGroupsNarrow = 256;
+constexpr int kNarrowXtBlockBytes = 6 * 1024;  // prepared activations of one group: operand blocks + 16 factors
 // Vector-ALU stack kernel: each wave serves several interleaved shares of the schedule, so that
 // layers of different widths (different speed per byte) even out over the waves.
 constexpr int kSharesPerWave = 8;
@@ -55,8 +59,8 @@ struct LayerDesc {
     const _Float16 *x;
     _Float16 *y;
     const uint4 *xt;        // MFMA path: activations re-ordered (narrow path: and scaled) per (chunk, group, MFMA) by the prep kernel
-    const float *xsum;      // narrow MFMA path: per (chunk, group, column) the factor F that rescales a tile's accumulator
-    int32_t N, K, G, RB;    // RB = row blocks = ceil(N/64); on the wide path super row blocks = ceil(N/256)
+    const float *xsum;      // unused
+    int32_t N, K, G, RB;    // RB = row blocks = ceil(N/64); super row blocks on the matrix-core paths: ceil(N/512) narrow, ceil(N/256) wide
     int32_t r;
     int32_t cost;           // schedule cost of one (row block, group) tile
     int32_t cnt_off;        // index of this layer's first row-block counter (CB*RB counters)
@@ -77,22 +81,11 @@ struct StackParams {
     float *part;             // [nworkers][2][slot_floats] partial sums
     int32_t *cnt;            // row-block counters, zero between launches
     int32_t M;
-    int32_t slot_floats;     // floats per partial-sum slot (64*M, or 64*16 on the MFMA path)
+    int32_t slot_floats;     // floats per partial-sum slot (64*M; a workgroup's 8 x 64*16 on the narrow matrix-core path)
     int32_t n_jobs;          // prep kernel jobs (MFMA path)
     int32_t worker_cap;      // 0, or: `part` holds slots for this many schedule shares only (a small workspace)
     LayerDesc single;
 };
-
-// MFMA instructions per tile on the MFMA path: (units / 4) * fields per unit
-inline int mfma_per_tile(int r) {
-    switch (r) {
-        case 2: return 16;
-        case 3: return 18;
-        case 4: return 16;
-        case 6: return 20;
-        default: return 16;
-    }
-}
 
 // Schedule cost of a tile on the vector-ALU path: measured times of uniform stacks (12 Llama-3-70B blocks, units of
 // 10 us) per batch M = 1..4.  At M = 1 the kernel is HBM-bound and the cost close to a tile's bytes (4r + 2 lines of

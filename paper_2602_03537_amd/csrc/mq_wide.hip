@@ -34,6 +34,7 @@
 // tile; more columns take further passes over the weights (pass index slowest in the
 // schedule); the chunk count is padded to passes * C with all-zero chunks.
 #include "mq_device.h"
+#include "mq_dma.h"
 
 namespace mq {
 
@@ -168,13 +169,6 @@ __global__ __launch_bounds__(256) void xprep_wide_kernel(const StackParams p) {
 }
 
 // ------------------------------------------------------------------ main kernel
-// Workgroup barrier that orders LDS traffic only: a wave's global loads stay in flight across it.
-__device__ __forceinline__ void lds_barrier() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
 __device__ __forceinline__ void swap32(uint32_t &a, uint32_t &b) {
     const u32x2 r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
     a = r.x;
@@ -350,58 +344,6 @@ __device__ __forceinline__ void finish_row_block_blocked(const LayerDesc &L, con
     if (lane == 0) __hip_atomic_store(gl(cnt), 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// ---- memory pipeline.  Weights and activations travel from global memory straight into LDS
-// (global_load_lds: 16 bytes per lane, no registers), issued from inline assembly so that the waits are
-// ours: loads retire in order, and a wait the compiler derives for one load of a deep software pipeline
-// tends to retire the whole pipeline.  Every wait below names how many LATER transfers of this wave may
-// still be in flight; transfers the wave issues elsewhere only make such a wait stricter, never wrong.
-// N consecutive 1 KB lines (16 bytes per lane each): lane addresses src_lane + i * 1024 -> LDS dst_wave + i * 1024.
-// The instruction offset of global_load_lds applies to the global and to the LDS address alike, so four
-// lines share one address register pair and one setting of M0 (the LDS base of the wave's transfer).
-// NT: non-temporal (streaming) transfers for data that is read once per call -- the weights, scales and zeros; the
-// activations are shared by every workgroup and stay ordinary transfers.
-template <int N, bool NT = false>
-__device__ __forceinline__ void dma_lines(const uint8_t *src_lane, MQ_LDS uint8_t *dst_wave) {
-    static_assert(N >= 1 && N <= 8, "one or two blocks of up to four lines");
-    const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst_wave);
-    const uint8_t MQ_GLOBAL *src = gl(src_lane);
-    constexpr int N0 = N < 4 ? N : 4;
-#define MQ_DMA_LINES(POL)                                                                                              \
-    if constexpr (N0 == 1)                                                                                             \
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" POL ::"s"(base), "v"(src)         \
-                     : "memory");                                                                                      \
-    else if constexpr (N0 == 2)                                                                                        \
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" POL "\n\t"                        \
-                     "global_load_lds_dwordx4 %1, off offset:1024" POL ::"s"(base),                                    \
-                     "v"(src)                                                                                          \
-                     : "memory");                                                                                      \
-    else if constexpr (N0 == 3)                                                                                        \
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" POL "\n\t"                        \
-                     "global_load_lds_dwordx4 %1, off offset:1024" POL "\n\t"                                          \
-                     "global_load_lds_dwordx4 %1, off offset:2048" POL ::"s"(base),                                    \
-                     "v"(src)                                                                                          \
-                     : "memory");                                                                                      \
-    else                                                                                                               \
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" POL "\n\t"                        \
-                     "global_load_lds_dwordx4 %1, off offset:1024" POL "\n\t"                                          \
-                     "global_load_lds_dwordx4 %1, off offset:2048" POL "\n\t"                                          \
-                     "global_load_lds_dwordx4 %1, off offset:3072" POL ::"s"(base),                                    \
-                     "v"(src)                                                                                          \
-                     : "memory");
-    if constexpr (NT) {
-        MQ_DMA_LINES(" nt")
-    } else {
-        MQ_DMA_LINES("")
-    }
-#undef MQ_DMA_LINES
-    if constexpr (N > 4) dma_lines<N - 4, NT>(src_lane + 4096, dst_wave + 4096);
-}
-// block B (four lines each, the last one shorter) of an N-line transfer
-template <int N, int B, bool NT = false>
-__device__ __forceinline__ void dma_block(const uint8_t *src_lane, MQ_LDS uint8_t *dst_wave) {
-    static_assert(4 * B < N, "no such block");
-    dma_lines<(N - 4 * B < 4 ? N - 4 * B : 4), NT>(src_lane + 4096 * B, dst_wave + 4096 * B);
-}
 // acc += A * B with the accumulator pinned to the accumulation registers: the C * 32 accumulators of a
 // wave live there for a whole row block and no vector instruction touches them in between (left to
 // itself the register allocator keeps shuttling them to vector registers and back).  Operands come from
@@ -430,11 +372,6 @@ __device__ __forceinline__ float16_t read_acc(const float16_t &acc) {
     }
     return r;
 }
-template <int N> __device__ __forceinline__ void wait_transfers() {
-    static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
 constexpr int kWideLdsBytes = 160 * 1024;
 constexpr int wide_slot_bytes(int R) { return R * 1024 + 256; }  // lane dwords of a tile + its 64 scales + 64 zeros
 // LDS plan of a workgroup: NST activation stages (one being read, the others landing) and per wave a

@@ -218,7 +218,7 @@ def test_linear_rejects_oversized_batch_loudly():
     ws = mq.new_workspace(1, 64, 128, 4)
     with pytest.raises(mq.MqError):
         mq.mq_linear(x, lay["packed_W"], lay["scales_t"], lay["zeros_t"], 64, 128, 4, 128, ws)
-    small_ws = mq.new_workspace(1, 64, 128, 4)          # sized for M=1, used with M=8
+    small_ws = torch.empty(mq.mq_workspace_bytes(8, 64, 128, 4) - 256, dtype=torch.uint8, device=DEV)   # one line short
     with pytest.raises(mq.MqError):
         mq.mq_linear(x[:8], lay["packed_W"], lay["scales_t"], lay["zeros_t"], 64, 128, 4, 128, small_ws)
 
