@@ -63,6 +63,7 @@ typedef enum {
 
 typedef void *mq_stream; /* hipStream_t */
 typedef uint16_t mq_half; /* IEEE binary16 bits */
+typedef uint16_t mq_bf16; /* bfloat16 bits (the upper half of an IEEE binary32) */
 
 /* Rows of W are processed in blocks of MQ_ROW_BLOCK; packed buffers pad N up. */
 #define MQ_ROW_BLOCK 64
@@ -259,6 +260,12 @@ mq_status mq_linear(const mq_half *x, int64_t M, const void *packed_W, const mq_
                     const mq_half *zeros_t, int64_t N, int64_t K, int r, int group, mq_half *y,
                     void *ws, size_t ws_bytes, mq_stream stream);
 
+/* mq_linear on bfloat16 activations with a bfloat16 result (flags MQ_X_BF16 | MQ_Y_BF16 of mq_layer;
+ * a stack may also mix the two per layer).  Everything else as mq_linear. */
+mq_status mq_linear_bf16(const mq_bf16 *x, int64_t M, const void *packed_W, const mq_half *scales_t,
+                         const mq_half *zeros_t, int64_t N, int64_t K, int r, int group, mq_bf16 *y,
+                         void *ws, size_t ws_bytes, mq_stream stream);
+
 /* mq_linear for callers that cannot allocate and have no workspace to hand over: code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and results
  * as mq_linear (to rounding: the split-K shares may be cut differently), but the counters, the
@@ -324,8 +331,20 @@ typedef struct {
     int32_t from_parent; /* 0: packed_W holds r-bit codes.  1: packed_W is the resident 8-bit parent and
                             Eq. 1 is applied in registers (as mq_linear_from_parent; M <= 4, and all
                             layers of a stack must agree, else MQ_ERR_UNSUPPORTED) */
-    int32_t reserved;    /* 0 */
+    int32_t flags;       /* 0, or MQ_X_BF16 | MQ_Y_BF16 (below); other bits: MQ_ERR_UNSUPPORTED */
 } mq_layer;
+
+/* bf16 activations and outputs, per layer.
+ *   MQ_X_BF16 : x points to bfloat16 values.  They are converted to fp16 where the kernels consume
+ *               them, which is exact for every value whose magnitude is within the fp16 range
+ *               (2^-14 <= |x| <= 65504, and 0): results are then those of the same values given as
+ *               fp16, bit for bit.  Larger magnitudes become infinities, smaller ones keep what
+ *               fp16 subnormals hold (absolute error <= 2^-25).
+ *   MQ_Y_BF16 : y is written as bfloat16, the fp32 sums rounded to nearest even.  (An 8-bit
+ *               significand rounds by up to 2^-9 relative: such outputs are within one bf16 rounding
+ *               of the fp16-output result, not within its 1e-3 relative-L2 distance of the exact y.) */
+#define MQ_X_BF16 1
+#define MQ_Y_BF16 2
 
 /* Kernels by batch: as mq_linear, except that a stack of packed layers already runs on the matrix
  * cores at M = 4 (scales_t / zeros_t 16-byte aligned from M = 4 on for a stack); stacks computed

@@ -15,7 +15,7 @@ __all__ = [
     "mq_slice_pack", "mq_reslice", "mq_reslice_many", "MqResliceJob", "mq_linear_from_parent", "mq_quant_matgptq",
     "mq_matgptq_workspace_bytes", "mq_matgptq_quantize",
     "mq_stack_workspace_bytes", "mq_stack_plan", "mq_linear_stack", "MqLayer", "MqPlan", "StackPlan",
-    "mq_read_probe", "mq_linear_plain", "mq_linear_plain_workspace_bytes", "mq_linear_noalloc", "MQ_NOALLOC_SCRATCH_BYTES",
+    "mq_read_probe", "mq_linear_bf16", "MQ_X_BF16", "MQ_Y_BF16", "mq_linear_plain", "mq_linear_plain_workspace_bytes", "mq_linear_noalloc", "MQ_NOALLOC_SCRATCH_BYTES",
     "new_workspace", "prepare_layer",
 ]
 
@@ -23,6 +23,8 @@ MQ_ROW_BLOCK = 64
 MQ_GROUP = 128
 MQ_MAX_M = 256
 MQ_NOALLOC_SCRATCH_BYTES = 8 << 20
+MQ_X_BF16 = 1
+MQ_Y_BF16 = 2
 STATUS = {
     0: "MQ_OK", 1: "MQ_ERR_NULL", 2: "MQ_ERR_BAD_R", 3: "MQ_ERR_BAD_SHAPE", 4: "MQ_ERR_BAD_GROUP",
     5: "MQ_ERR_ALIGN", 6: "MQ_ERR_BUF_TOO_SMALL", 7: "MQ_ERR_HIP", 8: "MQ_ERR_UNSUPPORTED",
@@ -45,7 +47,7 @@ class MqLayer(ctypes.Structure):
         ("packed_W", ctypes.c_void_p), ("scales_t", ctypes.c_void_p), ("zeros_t", ctypes.c_void_p),
         ("x", ctypes.c_void_p), ("y", ctypes.c_void_p),
         ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("r", ctypes.c_int32), ("group", ctypes.c_int32),
-        ("from_parent", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("from_parent", ctypes.c_int32), ("flags", ctypes.c_int32),
     ]
 
 
@@ -113,6 +115,7 @@ def lib():
         "mq_stack_plan": (i32, [vp, i32, i64, vp, sz, vp, vp]),
         "mq_linear_stack": (i32, [vp, vp]),
         "mq_read_probe": (i32, [vp, sz, vp, vp]),
+        "mq_linear_bf16": (i32, [vp, i64, vp, vp, vp, i64, i64, i32, i32, vp, vp, sz, vp]),
         "mq_linear_noalloc": (i32, [vp, i64, vp, vp, vp, i64, i64, i32, i32, vp, vp]),
         "mq_linear_plain_workspace_bytes": (sz, [i64, i64, i64, i32]),
         "mq_linear_plain": (i32, [vp, i64, vp, vp, vp, i64, i64, i32, i32, vp, vp, sz, vp]),
@@ -228,6 +231,17 @@ def mq_linear(x, packed_W, scales_t, zeros_t, N: int, K: int, r: int, group: int
 def mq_read_probe(buf, out, stream=None) -> None:
     """xor of all 32-bit words of buf (uint8 tensor, a multiple of 16 bytes) is xor-ed into out (one int32/uint32)."""
     _check(lib().mq_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _ptr(out), _stream(stream)), "mq_read_probe")
+
+
+def mq_linear_bf16(x, packed_W, scales_t, zeros_t, N: int, K: int, r: int, group: int, ws, y=None, stream=None):
+    """mq_linear on bfloat16 activations (torch.bfloat16 [M, K]) with a bfloat16 result."""
+    import torch
+    M = x.shape[0]
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    _check(lib().mq_linear_bf16(_ptr(x), M, _ptr(packed_W), _ptr(scales_t), _ptr(zeros_t), N, K, r, group, _ptr(y),
+                                _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "mq_linear_bf16")
+    return y
 
 
 def mq_linear_noalloc(x, packed_W, scales_t, zeros_t, N: int, K: int, r: int, group: int, y, stream=None):
@@ -362,7 +376,8 @@ def _layer_array(layers: Sequence[dict]):
     arr = (MqLayer * len(layers))()
     for i, L in enumerate(layers):
         arr[i] = MqLayer(_ptr(L["packed_W"]), _ptr(L["scales_t"]), _ptr(L["zeros_t"]), _ptr(L["x"]), _ptr(L["y"]),
-                         L["N"], L["K"], L["r"], L.get("group", MQ_GROUP), int(L.get("from_parent", 0)), 0)
+                         L["N"], L["K"], L["r"], L.get("group", MQ_GROUP), int(L.get("from_parent", 0)),
+                         int(L.get("flags", 0)))
     return arr
 
 

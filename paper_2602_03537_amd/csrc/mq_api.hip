@@ -70,7 +70,7 @@ mq_status layer_status(const mq_layer &l, int64_t M) {
     if (!valid_pack_r(l.r)) return MQ_ERR_BAD_R;
     if (M < 1 || M > MQ_MAX_M) return MQ_ERR_BAD_SHAPE;
     if (mq_status st = check_shape(l.N, l.K, l.group)) return st;
-    if ((l.from_parent != 0 && l.from_parent != 1) || l.reserved != 0) return MQ_ERR_UNSUPPORTED;
+    if ((l.from_parent != 0 && l.from_parent != 1) || (l.flags & ~(MQ_X_BF16 | MQ_Y_BF16))) return MQ_ERR_UNSUPPORTED;
     if (l.from_parent && use_mfma(M)) return MQ_ERR_UNSUPPORTED;  // slicing in registers: vector-ALU kernels only
     // the matrix-core paths move scales / zeros 16 bytes at a time
     const size_t meta_align = use_mfma(M) ? 16 : 2;
@@ -111,6 +111,7 @@ LayerDesc make_desc(const mq_layer &l, int64_t M, int64_t Mp, uint64_t cost_star
         d.RB = (d.RB + 3) / 4;
         d.cost = wide_tile_cost(l.r, wide_chunks_per_pass(Mp));
     }
+    d.flags = l.flags;
     d.cnt_off = cnt_off;
     d.M = (int32_t)M;
     d.CB = (int32_t)chunks(Mp);
@@ -324,6 +325,12 @@ mq_status mq_linear(const mq_half *x, int64_t M, const void *packed_W, const mq_
                     const mq_half *zeros_t, int64_t N, int64_t K, int r, int group, mq_half *y, void *ws,
                     size_t ws_bytes, mq_stream stream) {
     const mq_layer l{packed_W, scales_t, zeros_t, x, y, N, K, r, group, 0, 0};
+    return run_single(l, M, ws, ws_bytes, stream);
+}
+
+mq_status mq_linear_bf16(const mq_bf16 *x, int64_t M, const void *packed_W, const mq_half *scales_t, const mq_half *zeros_t,
+                         int64_t N, int64_t K, int r, int group, mq_bf16 *y, void *ws, size_t ws_bytes, mq_stream stream) {
+    const mq_layer l{packed_W, scales_t, zeros_t, x, y, N, K, r, group, 0, MQ_X_BF16 | MQ_Y_BF16};
     return run_single(l, M, ws, ws_bytes, stream);
 }
 

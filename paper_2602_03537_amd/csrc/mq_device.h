@@ -36,6 +36,31 @@ typedef const uint32_t __attribute__((address_space(4))) *cptr32;  // scalar (SG
 
 __device__ __forceinline__ cptr32 as_const(const void *p) { return (cptr32)(uintptr_t)p; }
 
+// bf16 activations and outputs (LayerDesc::flags).  A bf16 value inside the fp16 range is an fp16 value with mantissa
+// bits to spare, so activations are converted where they are consumed and every product stays exact; beyond +-65504
+// they become infinities, below 2^-14 they keep what fp16 subnormals can hold.  Outputs are the fp32 sums rounded to
+// nearest even in the type asked for.
+constexpr int kFlagXBf16 = 1, kFlagYBf16 = 2;
+__device__ __forceinline__ uint32_t bf16_pair_to_f16_pair(uint32_t v) {
+    const float lo = __builtin_bit_cast(float, v << 16), hi = __builtin_bit_cast(float, v & 0xFFFF0000u);
+    const half2_t h = {(_Float16)lo, (_Float16)hi};
+    return __builtin_bit_cast(uint32_t, h);
+}
+__device__ __forceinline__ uint32_t x_pair(uint32_t v, int flags) { return flags & kFlagXBf16 ? bf16_pair_to_f16_pair(v) : v; }
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+    uint32_t b = __builtin_bit_cast(uint32_t, f);
+    if ((b & 0x7F800000u) == 0x7F800000u) return (uint16_t)((b >> 16) | ((b & 0xFFFFu) ? 0x40u : 0u));  // Inf, NaN stays NaN
+    b += 0x7FFFu + ((b >> 16) & 1u);
+    return (uint16_t)(b >> 16);
+}
+// the 16 bits stored for output value v
+__device__ __forceinline__ uint16_t y_bits(float v, int flags) {
+    return flags & kFlagYBf16 ? f32_to_bf16_bits(v) : __builtin_bit_cast(uint16_t, (_Float16)v);
+}
+__device__ __forceinline__ void store_y(_Float16 *y, size_t idx, float v, int flags) {
+    gl(reinterpret_cast<uint16_t *>(y))[idx] = y_bits(v, flags);
+}
+
 __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
     return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, a), __builtin_bit_cast(half2_t, b), c, false);
 }

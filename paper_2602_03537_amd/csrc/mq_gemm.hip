@@ -81,11 +81,11 @@ template <int R> __device__ __forceinline__ void xprep_job(const LayerDesc &L, i
         constexpr int Q = mf / T::NOPS;
         constexpr Op o = T::op(mf % T::NOPS);
         // dword j of the lane's operand = activation pair of unit 4Q+j, field o
-        v[mf] = xrow[(4 * Q + j) * T::PPU + o.pair] & live;
+        v[mf] = x_pair(xrow[(4 * Q + j) * T::PPU + o.pair], L.flags) & live;
     });
     uint32_t q[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) q[i] = xrow[j * 16 + i] & live;
+    for (int i = 0; i < 16; ++i) q[i] = x_pair(xrow[j * 16 + i], L.flags) & live;
     // X_g and the largest |x| of column m: lanes 4m..4m+3 each cover a quarter of the group
     float s = 0.f, amax = 0.f;
 #pragma unroll
@@ -372,20 +372,20 @@ __device__ __forceinline__ void run_narrow_units(const LayerDesc &L, const Stack
                 finish_row_block<16>(L, pw, p.cnt + L.cnt_off + rb, a, ga, g, yacc, worker, lane,
                                      [&](const float(&tot)[16]) {
                                          if (col >= L.M) return;
-                                         _Float16 MQ_GLOBAL *yrow = gl(L.y + (size_t)col * L.N);
+                                         uint16_t MQ_GLOBAL *yrow = gl(reinterpret_cast<uint16_t *>(L.y) + (size_t)col * L.N);
+                                         const int fl = L.flags;
 #pragma unroll
                                          for (int q = 0; q < 4; ++q) {
                                              const int row = row0 + 8 * q;
                                              if (fast_store && row + 3 < L.N) {
-                                                 const half2_t lo = {(_Float16)tot[4 * q], (_Float16)tot[4 * q + 1]};
-                                                 const half2_t hi = {(_Float16)tot[4 * q + 2], (_Float16)tot[4 * q + 3]};
-                                                 const u32x2 pk = {__builtin_bit_cast(uint32_t, lo),
-                                                                   __builtin_bit_cast(uint32_t, hi)};
+                                                 const u32x2 pk = {
+                                                     (uint32_t)y_bits(tot[4 * q], fl) | ((uint32_t)y_bits(tot[4 * q + 1], fl) << 16),
+                                                     (uint32_t)y_bits(tot[4 * q + 2], fl) | ((uint32_t)y_bits(tot[4 * q + 3], fl) << 16)};
                                                  *(u32x2 MQ_GLOBAL *)(yrow + row) = pk;
                                              } else {
 #pragma unroll
                                                  for (int e = 0; e < 4; ++e)
-                                                     if (row + e < L.N) yrow[row + e] = (_Float16)tot[4 * q + e];
+                                                     if (row + e < L.N) yrow[row + e] = y_bits(tot[4 * q + e], fl);
                                              }
                                          }
                                      });

@@ -68,7 +68,7 @@ struct LayerDesc {
     int32_t CB;             // column chunks: 1 on the vector-ALU path, ceil(M/16) on the MFMA path; wide path: passes
     int32_t job_start;      // prep kernel: sum of CB*G over the preceding layers
     int32_t rs;             // 0, or: Wp is the 8-bit parent (r == 8) and Eq. 1 to rs bits is applied in registers
-    int32_t reserved;
+    int32_t flags;          // kFlagXBf16: x holds bf16 values; kFlagYBf16: y is written as bf16
     uint64_t cost_start;    // sum of CB*RB*G*cost over the preceding layers
 };
 

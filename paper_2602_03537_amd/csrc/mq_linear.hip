@@ -76,11 +76,12 @@ __device__ __forceinline__ void tile_math(const TileRegs<R, M> &t, const LayerDe
     cptr32 xs[M];
 #pragma unroll
     for (int m = 0; m < M; ++m) {
-        xg[m] = wave_sum(dot2(t.xl[m], 0x3C003C00u, 0.f));  // (1.0, 1.0)
+        const uint32_t xl = x_pair(t.xl[m], L.flags);          // bf16 activations become fp16 here, where they have arrived
+        xg[m] = wave_sum(dot2(xl, 0x3C003C00u, 0.f));  // (1.0, 1.0)
         if constexpr (XP == kXLds)
-            xlds[m * 64 + lane] = t.xl[m];
+            xlds[m * 64 + lane] = xl;
         else
-            xs[m] = as_const(L.x + (size_t)m * L.K + (size_t)g * kGroup);
+            xs[m] = as_const(L.x + (size_t)m * L.K + (size_t)g * kGroup);  // fp16 activations only
     }
     float acc[M][T::NKEYS];
 #pragma unroll
@@ -183,7 +184,7 @@ __device__ __forceinline__ void run_units(const LayerDesc &L, const StackParams 
                                     yacc, wave, lane, [&](const float(&tot)[M]) {
 #pragma unroll
                                         for (int m = 0; m < M; ++m)
-                                            if (row < L.N) gl(L.y)[(size_t)m * L.N + row] = (_Float16)tot[m];
+                                            if (row < L.N) store_y(L.y, (size_t)m * L.N + row, tot[m], L.flags);
                                     });
                 ++rb;
                 g = 0;
@@ -296,7 +297,7 @@ __device__ __forceinline__ void linear_rb_body(const LayerDesc &L, const int KS,
     }
 #pragma unroll
     for (int m = 0; m < M; ++m)
-        if (row < L.N) gl(L.y)[(size_t)m * L.N + row] = (_Float16)tot[m];
+        if (row < L.N) store_y(L.y, (size_t)m * L.N + row, tot[m], L.flags);
 }
 
 template <int R, int M, int XP, bool SL = false>

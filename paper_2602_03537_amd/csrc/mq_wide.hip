@@ -130,7 +130,7 @@ __device__ __forceinline__ void xprep_wide_job(const LayerDesc &L, int g, int c,
         static_for<2>([&](auto ds) {
             static_for<4>([&](auto i) {
                 constexpr WField f = Wide<R>::fld(2 * q + ds, i);
-                v[ds][i] = xrow[h ? f.pair_hi : f.pair_lo] & live;
+                v[ds][i] = x_pair(xrow[h ? f.pair_hi : f.pair_lo], L.flags) & live;
             });
         });
         static_for<2>([&](auto ds) {
@@ -588,15 +588,16 @@ __device__ __forceinline__ void run_wide_units(const LayerDesc &L, const StackPa
                         const int row = row0 + 32 * hrow;
                         const int col0 = (c0 + c) * kWideCols + colq;
                         if (row >= L.N || col0 >= L.M) return;
-                        _Float16 MQ_GLOBAL *dst = gl(L.y) + (size_t)col0 * L.N + row;
+                        uint16_t MQ_GLOBAL *dst = gl(reinterpret_cast<uint16_t *>(L.y)) + (size_t)col0 * L.N + row;
+                        const int fl = L.flags;
                         if (col0 + 28 <= L.M) {  // all 16 columns of this lane are inside the batch
 #pragma unroll
-                            for (int v = 0; v < 16; ++v) dst[(size_t)(8 * (v >> 2) + (v & 3)) * L.N] = (_Float16)tot[v];
+                            for (int v = 0; v < 16; ++v) dst[(size_t)(8 * (v >> 2) + (v & 3)) * L.N] = y_bits(tot[v], fl);
                         } else {
 #pragma unroll
                             for (int v = 0; v < 16; ++v) {
                                 const int dc = 8 * (v >> 2) + (v & 3);
-                                if (col0 + dc < L.M) dst[(size_t)dc * L.N] = (_Float16)tot[v];
+                                if (col0 + dc < L.M) dst[(size_t)dc * L.N] = y_bits(tot[v], fl);
                             }
                         }
                     });

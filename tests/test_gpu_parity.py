@@ -1087,3 +1087,70 @@ def test_symmetric_stack_from_parent_and_plain(M):
         st, _ = mq.mq_pack_meta(dev(L["scales"]), None, K)
         y = mq.mq_linear_from_parent(dev(L["x"]), p8, st, None, N, K, 3, 128, mq.new_workspace(M, N, K, 8))
         check_layer(y, L, 3, f"symmetric from parent M={M}")
+
+
+# ------------------------------------------------------------------ bf16 activations and outputs
+def _bf16_round(a):
+    """float64 array -> nearest-even bfloat16 values, as float64"""
+    b = np.asarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    b = (b + 0x7FFF + ((b >> 16) & 1)) >> 16 << 16
+    return b.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+@pytest.mark.parametrize("r", WIDTHS)
+@pytest.mark.parametrize("shape_m", [(200, 768, 1), (130, 384, 3), (512, 2048, 4), (257, 1280, 8), (448, 2048, 16),
+                                     (320, 640, 40), (700, 1152, 200)])
+def test_bf16_activations_and_outputs(r, shape_m):
+    N, K, M = shape_m
+    L = synth.make_layer(N, K, M=M, seed=[140, N, K, M])
+    xb = torch.from_numpy(L["x"].astype(np.float32)).to(torch.bfloat16)         # bf16 activations (rounded once, here)
+    Lb = dict(L, x=xb.to(torch.float16).numpy())                                # the same values: all inside the fp16 range
+    assert np.array_equal(Lb["x"].astype(np.float32), xb.float().numpy())
+    lay = mq.prepare_layer(dev(L["parent"]), dev(L["scales"]), dev(L["zeros"]), r)
+    ws = mq.new_workspace(M, N, K, r)
+    # bf16 in, fp16 out (a stack of one layer with MQ_X_BF16): the fp16 bar, and the bits of the same values given as fp16
+    y16 = torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV)
+    plan = mq.mq_stack_plan([dict(lay, x=xb.to(DEV), y=y16, flags=mq.MQ_X_BF16)], M)
+    mq.mq_linear_stack(plan)
+    torch.cuda.synchronize()
+    check_layer(y16, Lb, r, f"bf16 x {shape_m} r={r}")
+    y16b = torch.empty_like(y16)
+    mq.mq_linear_stack(mq.mq_stack_plan([dict(lay, x=dev(Lb["x"]), y=y16b)], M))
+    torch.cuda.synchronize()
+    assert torch.equal(y16, y16b)
+    # bf16 in, bf16 out: one bf16 rounding of the fp32 sums
+    yb = mq.mq_linear_bf16(xb.to(DEV), lay["packed_W"], lay["scales_t"], lay["zeros_t"], N, K, r, 128, ws)
+    torch.cuda.synchronize()
+    assert yb.dtype == torch.bfloat16 and torch.isfinite(yb).all()
+    ref = oracle.linear(Lb["x"], L["parent"], L["scales"], L["zeros"], C, r, 128)
+    got = yb.float().cpu().numpy().astype(np.float64)
+    # within one bf16 spacing of the exact result (half a spacing from rounding, the rest from the fp32 sums), and
+    # exactly the rounding of a value within the fp16-output bar
+    assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 3e-3), f"bf16 y {shape_m} r={r}"
+    assert np.linalg.norm(got - ref) <= 2.5e-3 * np.linalg.norm(ref)
+    assert np.array_equal(got, _bf16_round(got))
+
+
+def test_bf16_flags_in_a_mixed_stack():
+    M = 2
+    shapes_r = [(256, 512, 2), (64, 128, 8), (200, 1280, 3), (512, 256, 6)]
+    host, layers = [], []
+    for i, (N, K, r) in enumerate(shapes_r):
+        L = synth.make_layer(N, K, M=M, seed=[141, i])
+        xb = torch.from_numpy(L["x"].astype(np.float32)).to(torch.bfloat16)
+        flags = (0, mq.MQ_X_BF16, mq.MQ_Y_BF16, mq.MQ_X_BF16 | mq.MQ_Y_BF16)[i]
+        lay = mq.prepare_layer(dev(L["parent"]), dev(L["scales"]), dev(L["zeros"]), r)
+        xin = xb.to(DEV) if flags & mq.MQ_X_BF16 else dev(L["x"])
+        y = torch.full((M, N), float("nan"), dtype=torch.bfloat16 if flags & mq.MQ_Y_BF16 else torch.float16, device=DEV)
+        lay.update(x=xin, y=y, flags=flags)
+        layers.append(lay)
+        host.append(dict(L, x=xb.to(torch.float16).numpy() if flags & mq.MQ_X_BF16 else L["x"], r=r, flags=flags))
+    mq.mq_linear_stack(mq.mq_stack_plan(layers, M))
+    torch.cuda.synchronize()
+    for i, (lay, L) in enumerate(zip(layers, host)):
+        ref = oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, L["r"], 128)
+        got = lay["y"].float().cpu().numpy().astype(np.float64)
+        if L["flags"] & mq.MQ_Y_BF16:
+            assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 3e-3), i
+        else:
+            check_layer(lay["y"], L, L["r"], f"mixed flags layer {i}")

@@ -284,6 +284,13 @@ def test_workspace_and_stack_validation():
     assert L.mq_stack_plan(p, 2, 8, FAKE, 1 << 40, hp, None) == _st("MQ_ERR_UNSUPPORTED")   # batch above the ALU path
     lay[0].from_parent = lay[1].from_parent = 2
     assert L.mq_stack_plan(p, 2, 1, FAKE, need, hp, None) == _st("MQ_ERR_UNSUPPORTED")
+    lay[0].from_parent = lay[1].from_parent = 0
+    lay[1].flags = 4                              # only MQ_X_BF16 | MQ_Y_BF16 are flags
+    assert L.mq_stack_plan(p, 2, 1, FAKE, need, hp, None) == _st("MQ_ERR_UNSUPPORTED")
+    lay[1].flags = mq.MQ_X_BF16 | mq.MQ_Y_BF16
+    assert L.mq_stack_plan(p, 2, 1, FAKE, need - 1, hp, None) == _st("MQ_ERR_BUF_TOO_SMALL")   # valid flags: judged on
+    assert L.mq_linear_bf16(None, 1, FAKE, FAKE, FAKE, 64, 128, 4, 128, FAKE, FAKE, 1 << 30, None) == _st("MQ_ERR_NULL")
+    assert L.mq_linear_bf16(FAKE, 1, FAKE, FAKE, FAKE, 64, 128, 5, 128, FAKE, FAKE, 1 << 30, None) == _st("MQ_ERR_BAD_R")
     assert bytes(h) == bytes(ctypes.sizeof(h))    # a refused plan leaves the caller's header untouched
 
 
