@@ -61,9 +61,9 @@ size_t partial_bytes(int64_t M) { return max_workers(M) * 2 * (size_t)slot_float
 // MFMA paths: prepared activations of one layer (group sums and rescale factors live inside the blocks)
 size_t xt_bytes(int64_t M, int64_t K, int) {
     if (use_wide(M)) return align_up((size_t)wide_chunks_padded(M) * (size_t)(K / kGroup) * kWideXtBlockBytes, 256);
-    return use_mfma(M) ? (size_t)(K / kGroup) * kNarrowXtBlockBytes : 0;
+    if (use_mfma(M)) return (size_t)(K / kGroup) * kNarrowXtBlockBytes;
+    return align_up((size_t)M * (size_t)K * 2, 256);  // vector-ALU path: bf16 activations converted to fp16
 }
-size_t xsum_bytes(int64_t, int64_t) { return 0; }
 
 mq_status layer_status(const mq_layer &l, int64_t M) {
     if (!l.packed_W || !l.scales_t || !l.x || !l.y) return MQ_ERR_NULL;  // zeros_t may be NULL: symmetric layer
@@ -80,18 +80,58 @@ mq_status layer_status(const mq_layer &l, int64_t M) {
     return MQ_OK;
 }
 
-// xt / xsum: where the MFMA path keeps this layer's prepared activations (nullptr on the ALU path)
+// ---- the zero-offsets of a symmetric layer: kSymLines lines of 64 x 2^(c-1); tile u of such a layer reads line
+// u & (kSymLines - 1) (LayerDesc::zmask), so that no kernel branches on whether a layer has zero-offsets.  Many lines
+// rather than one: every wave of the chip reading one 128-byte line would queue on a single L2 channel.
+// As with any __device__ array the name is a host-side stand-in; kernels get the address looked up per device.
+constexpr int kSymLines = 1024;
+struct SymZeros {
+    uint16_t v[kSymLines * 64];
+    constexpr SymZeros() : v() {
+        for (int i = 0; i < kSymLines * 64; ++i) v[i] = 0x5800;  // fp16 128.0
+    }
+};
+static_assert(kC == 8, "0x5800 is fp16 2^(c-1) for c = 8");
+static __device__ __align__(256) SymZeros sym_zeros = SymZeros();
+constexpr int kMaxDevices = 64;
+std::mutex g_symbol_mutex;
+const _Float16 *g_sym_zero_line[kMaxDevices] = {};
+
+// nullptr when the address cannot be had
+const _Float16 *sym_zero_line() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_symbol_mutex);
+    if (!g_sym_zero_line[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(sym_zeros)) != hipSuccess) return nullptr;
+        g_sym_zero_line[dev] = static_cast<const _Float16 *>(p);
+    }
+    return g_sym_zero_line[dev];
+}
+
+// xt: where the MFMA path keeps this layer's prepared activations (on the ALU path: the fp16 copy of bf16 activations)
+// sym_line: sym_zero_line() of the current device; needed (non-null) when the layer is symmetric
 // Mp: the path batch (== M except for stacks at M = kValuMaxM, see stack_path_m)
 LayerDesc make_desc(const mq_layer &l, int64_t M, int64_t Mp, uint64_t cost_start, int cnt_off, int job_start, void *xt,
-                    void *xsum) {
+                    const _Float16 *sym_line) {
     LayerDesc d{};
     d.Wp = static_cast<const uint4 *>(l.packed_W);
     d.st = reinterpret_cast<const _Float16 *>(l.scales_t);
     d.zt = reinterpret_cast<const _Float16 *>(l.zeros_t);
+    d.zmask = -1;
+    if (!l.zeros_t) {
+        d.zt = sym_line;
+        d.zmask = kSymLines - 1;
+    }
     d.x = reinterpret_cast<const _Float16 *>(l.x);
     d.y = reinterpret_cast<_Float16 *>(l.y);
     d.xt = static_cast<const uint4 *>(xt);
-    d.xsum = static_cast<const float *>(xsum);
+    d.x_bf16 = nullptr;
+    if (!use_mfma(Mp) && (l.flags & MQ_X_BF16)) {  // the vector-ALU kernels read the fp16 copy that launch_xcvt makes at xt
+        d.x_bf16 = l.x;
+        d.x = static_cast<const _Float16 *>(xt);
+    }
     d.N = (int32_t)l.N;
     d.K = (int32_t)l.K;
     d.G = (int32_t)(l.K / kGroup);
@@ -132,6 +172,7 @@ struct PlanHeader {
     uint64_t table_off, cnt_off, part_off, total_bytes;
     int32_t from_parent, path_M;
     int32_t ll_blocks, ll_waves;  // low-latency launch shape of a small stack, or 0
+    int32_t any_x_bf16, pad;      // some layer takes bf16 activations (the vector-ALU launches convert them first)
 };
 static_assert(sizeof(PlanHeader) <= sizeof(mq_plan), "the header must fit the caller's handle");
 constexpr uint64_t kPlanMagic = 0x4d51504c414e3037ull;  // "MQPLAN07"
@@ -143,7 +184,6 @@ constexpr size_t kScratchBytes = MQ_NOALLOC_SCRATCH_BYTES;
 constexpr size_t kNoallocMinWorkers = 256;  // fewer schedule shares (waves) than this would leave most of the chip idle
 constexpr size_t kNoallocMinGroups = 32;    // the same for the narrow matrix-core path, whose shares are workgroups of 8 waves
 static __device__ __align__(256) unsigned char scratch[kScratchBytes];
-constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mutex;
 void *g_scratch_ptr[kMaxDevices] = {};
 
@@ -178,7 +218,7 @@ PlanLayout plan_layout(const mq_layer *layers, int n_layers, int64_t M) {
     size_t act = 0;
     for (int i = 0; i < n_layers; ++i) {
         counters += counters_of(M, layers[i].N);
-        act += xt_bytes(M, layers[i].K, layers[i].r) + xsum_bytes(M, layers[i].K);
+        act += xt_bytes(M, layers[i].K, layers[i].r);
     }
     PlanLayout p;
     p.table_off = 256;
@@ -209,7 +249,9 @@ mq_status run_single(const mq_layer &l, int64_t M, void *ws, size_t ws_bytes, mq
     p.worker_cap = worker_cap;
     p.table = nullptr;
     p.n_layers = 1;
-    p.single = make_desc(l, M, M, 0, 0, 0, use_mfma(M) ? act : nullptr, use_mfma(M) ? act + xt_bytes(M, l.K, l.r) : nullptr);
+    const _Float16 *sym_line = nullptr;
+    if (!l.zeros_t && !(sym_line = sym_zero_line())) return MQ_ERR_HIP;
+    p.single = make_desc(l, M, M, 0, 0, 0, act, sym_line);
     p.cost_total = (uint64_t)p.single.CB * p.single.RB * p.single.G * p.single.cost;
     p.cnt = reinterpret_cast<int32_t *>(base);
     p.part = reinterpret_cast<float *>(base + cnt_b);
@@ -217,6 +259,9 @@ mq_status run_single(const mq_layer &l, int64_t M, void *ws, size_t ws_bytes, mq
     p.slot_floats = slot_floats(M);
     p.n_jobs = (use_wide(M) ? wide_chunks_padded(M) : p.single.CB) * p.single.G;
     hipError_t e;
+    if (!use_mfma(M) && (l.flags & MQ_X_BF16)) {
+        if (launch_xcvt(p, (hipStream_t)stream) != hipSuccess) return MQ_ERR_HIP;
+    }
     if (use_wide(M))
         e = launch_stack_wide(p, p.single.cost, (hipStream_t)stream);
     else if (use_mfma(M))
@@ -261,8 +306,7 @@ size_t mq_meta_bytes(int64_t N, int64_t K, int group) {
 
 size_t mq_workspace_bytes(int64_t M, int64_t N, int64_t K, int r) {
     if (!valid_pack_r(r) || check_shape(N, K, kGroup) != MQ_OK || M < 1 || M > MQ_MAX_M) return 0;
-    return counter_bytes(counters_of(M, N)) + partial_bytes(M) + xt_bytes(M, K, r) +
-           xsum_bytes(M, K);
+    return counter_bytes(counters_of(M, N)) + partial_bytes(M) + xt_bytes(M, K, r);
 }
 
 mq_status mq_workspace_init(void *ws, size_t ws_bytes, mq_stream stream) {
@@ -482,11 +526,12 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
     int max_cost = 0;
     size_t act = pl.act_off;
     std::vector<LayerDesc> table((size_t)n_layers);
+    const _Float16 *sym_line = nullptr;
     for (int i = 0; i < n_layers; ++i) {
-        const size_t xb = xt_bytes(Mp, layers[i].K, layers[i].r), sb = xsum_bytes(Mp, layers[i].K);
-        table[i] = make_desc(layers[i], M, Mp, cost, (int)counters, (int)jobs, xb ? base_dev + act : nullptr,
-                             xb ? base_dev + act + xb : nullptr);
-        act += xb + sb;
+        const size_t xb = xt_bytes(Mp, layers[i].K, layers[i].r);
+        if (!layers[i].zeros_t && !sym_line && !(sym_line = sym_zero_line())) return MQ_ERR_HIP;
+        table[i] = make_desc(layers[i], M, Mp, cost, (int)counters, (int)jobs, xb ? base_dev + act : nullptr, sym_line);
+        act += xb;
         cost += (uint64_t)table[i].CB * table[i].RB * table[i].G * table[i].cost;
         counters += counters_of(Mp, layers[i].N);
         jobs += (int64_t)(use_wide(Mp) ? wide_chunks_padded(Mp) : table[i].CB) * table[i].G;
@@ -501,6 +546,7 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
     h.M = (int32_t)M;
     h.max_cost = max_cost;
     h.n_jobs = (int32_t)jobs;
+    for (int i = 0; i < n_layers; ++i) h.any_x_bf16 |= layers[i].flags & MQ_X_BF16;
     h.table_off = pl.table_off;
     h.cnt_off = pl.cnt_off;
     h.part_off = pl.part_off;
@@ -542,6 +588,9 @@ mq_status mq_linear_stack(const mq_plan *plan, mq_stream stream) {
     p.M = h.M;
     p.slot_floats = slot_floats(h.path_M);
     p.n_jobs = h.n_jobs;
+    if (!use_mfma(h.path_M) && h.any_x_bf16) {
+        if (launch_xcvt(p, (hipStream_t)stream) != hipSuccess) return MQ_ERR_HIP;
+    }
     const hipError_t e = use_wide(h.path_M)   ? launch_stack_wide(p, h.max_cost, (hipStream_t)stream)
                          : use_mfma(h.path_M) ? launch_stack_mfma(p, h.max_cost, (hipStream_t)stream)
                          : h.ll_blocks        ? launch_linear_rb_stack(p, h.ll_blocks, h.ll_waves, h.from_parent != 0,
@@ -557,7 +606,7 @@ mq_status mq_linear_noalloc(const mq_half *x, int64_t M, const void *packed_W, c
     if (M > kNarrowMaxM) return MQ_ERR_UNSUPPORTED;  // the wide path's slots alone exceed the scratch array
     // [counters][slot pairs for `cap` schedule shares][prepared activations] must fit the array
     const size_t cnt_b = counter_bytes(counters_of(M, N));
-    const size_t act_b = xt_bytes(M, K, r) + xsum_bytes(M, K);
+    const size_t act_b = xt_bytes(M, K, r);
     const size_t pair_b = 2 * (size_t)slot_floats(M) * sizeof(float);
     const size_t min_workers = use_mfma(M) ? kNoallocMinGroups : kNoallocMinWorkers;
     if (cnt_b + act_b + min_workers * pair_b > kScratchBytes) return MQ_ERR_BUF_TOO_SMALL;

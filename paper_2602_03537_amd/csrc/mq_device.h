@@ -46,7 +46,11 @@ __device__ __forceinline__ uint32_t bf16_pair_to_f16_pair(uint32_t v) {
     const half2_t h = {(_Float16)lo, (_Float16)hi};
     return __builtin_bit_cast(uint32_t, h);
 }
+// (for the activation prep kernels of the matrix-core paths, where the conversion costs nothing that matters; the
+// vector-ALU kernels read activations that xcvt_kernel has converted ahead of them: computed both ways and selected per
+// tile, the conversion costs the ALU-bound 2-bit tiles 3 %, branched around 10 %)
 __device__ __forceinline__ uint32_t x_pair(uint32_t v, int flags) { return flags & kFlagXBf16 ? bf16_pair_to_f16_pair(v) : v; }
+
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
     uint32_t b = __builtin_bit_cast(uint32_t, f);
     if ((b & 0x7F800000u) == 0x7F800000u) return (uint16_t)((b >> 16) | ((b & 0xFFFFu) ? 0x40u : 0u));  // Inf, NaN stays NaN

@@ -223,10 +223,9 @@ __device__ __forceinline__ void run_narrow_units(const LayerDesc &L, const Stack
         } else if constexpr (piece == kWBlocks) {
             if (lane < 8) dma_lines<1, true>(reinterpret_cast<const uint8_t *>(L.st) + tile * 128 + lane * 16, dst + R * 1024);
         } else {
-            // a symmetric layer has no zero-offset array: its scales line is transferred once more (a cache hit),
-            // because the number of transfers per body is what the waits count
-            const uint8_t *zsrc = reinterpret_cast<const uint8_t *>(L.zt ? L.zt : L.st);
-            if (lane < 8) dma_lines<1, true>(zsrc + tile * 128 + lane * 16, dst + R * 1024 + 128);
+            // a symmetric layer reads constant lines of 2^(c-1) (tile & zmask picks one)
+            const uint8_t *zsrc = reinterpret_cast<const uint8_t *>(L.zt);
+            if (lane < 8) dma_lines<1, true>(zsrc + (tile & (size_t)(int64_t)L.zmask) * 128 + lane * 16, dst + R * 1024 + 128);
             if (n_pf > 1) {
                 --n_pf;
                 if (++g_pf == G) { g_pf = 0; ++s_pf; }
@@ -262,7 +261,6 @@ __device__ __forceinline__ void run_narrow_units(const LayerDesc &L, const Stack
 #pragma unroll
         for (int q = 0; q < 4; ++q) s4[q] = sp[2 * q];
         zl = reinterpret_cast<const MQ_LDS _Float16 *>(src + R * 1024 + 128)[lane];
-        if (!L.zt) zl = (_Float16)(float)(1 << (kC - 1));
     };
 
     {

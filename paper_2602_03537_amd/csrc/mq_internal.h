@@ -58,8 +58,8 @@ struct LayerDesc {
     const _Float16 *zt;
     const _Float16 *x;
     _Float16 *y;
-    const uint4 *xt;        // MFMA path: activations re-ordered (narrow path: and scaled) per (chunk, group, MFMA) by the prep kernel
-    const float *xsum;      // unused
+    const uint4 *xt;        // MFMA paths: activations re-ordered (narrow path: and scaled) by the prep kernel
+    const void *x_bf16;     // vector-ALU path with kFlagXBf16: the caller's bf16 activations (x then points to their fp16 copy)
     int32_t N, K, G, RB;    // RB = row blocks = ceil(N/64); super row blocks on the matrix-core paths: ceil(N/512) narrow, ceil(N/256) wide
     int32_t r;
     int32_t cost;           // schedule cost of one (row block, group) tile
@@ -69,6 +69,8 @@ struct LayerDesc {
     int32_t job_start;      // prep kernel: sum of CB*G over the preceding layers
     int32_t rs;             // 0, or: Wp is the 8-bit parent (r == 8) and Eq. 1 to rs bits is applied in registers
     int32_t flags;          // kFlagXBf16: x holds bf16 values; kFlagYBf16: y is written as bf16
+    int32_t zmask;          // -1; a symmetric layer: zt is zmask + 1 lines of 64 x 128.0, tile u reads line u & zmask
+    int32_t pad;
     uint64_t cost_start;    // sum of CB*RB*G*cost over the preceding layers
 };
 
@@ -165,6 +167,8 @@ hipError_t launch_gptq(float *W, int64_t ldw, int64_t N, int64_t K, const float 
 hipError_t launch_quant(const float *W, int64_t ldw, int64_t N, int64_t ncols, int64_t col0, const _Float16 *scales,
                         const _Float16 *zeros, int64_t G, const float *lambda, uint8_t *Q, int64_t ldq, bool vec4,
                         hipStream_t s);
+// bf16 activations of the layers that carry kFlagXBf16 -> fp16 in their LayerDesc::xt (ahead of a vector-ALU launch)
+hipError_t launch_xcvt(const StackParams &p, hipStream_t s);
 // Fills p.nwaves and launches (vector-ALU path, M <= kValuMaxM).  max_cost = largest tile cost in the stack.
 // from_parent: every layer has rs != 0 (the kernel variant that slices in registers).
 hipError_t launch_stack(StackParams p, int max_cost, bool from_parent, hipStream_t s);

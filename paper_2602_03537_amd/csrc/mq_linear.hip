@@ -38,8 +38,10 @@ __device__ __forceinline__ void load_tile(TileRegs<R, M> &t, const LayerDesc &L,
         t.w[4 * i] = v.x; t.w[4 * i + 1] = v.y; t.w[4 * i + 2] = v.z; t.w[4 * i + 3] = v.w;
     }
     t.s = __builtin_nontemporal_load(gl(L.st) + (size_t)u * 64 + lane);
-    // symmetric layer (no zero-offset array): every zero-offset is 2^(c-1); the branch is uniform over the launch's layer
-    t.z = L.zt ? __builtin_nontemporal_load(gl(L.zt) + (size_t)u * 64 + lane) : (_Float16)(float)(1 << (kC - 1));
+    // A symmetric layer has no zero-offset array: its zt is a few lines of 64 x 128.0 inside the library and zmask
+    // folds every tile onto them (cache hits, no HBM traffic).  The load is neither branched around nor selected -- either
+    // costs the ALU-bound 2-bit tiles and the mixed Llama-3-70B stack 3-9 % -- and an asymmetric layer pays one scalar AND.
+    t.z = __builtin_nontemporal_load(gl(L.zt) + (size_t)(u & L.zmask) * 64 + lane);
 #pragma unroll
     for (int m = 0; m < M; ++m)
         t.xl[m] = gl(reinterpret_cast<const uint32_t *>(L.x + (size_t)m * L.K + (size_t)g * kGroup))[lane];
@@ -76,12 +78,12 @@ __device__ __forceinline__ void tile_math(const TileRegs<R, M> &t, const LayerDe
     cptr32 xs[M];
 #pragma unroll
     for (int m = 0; m < M; ++m) {
-        const uint32_t xl = x_pair(t.xl[m], L.flags);          // bf16 activations become fp16 here, where they have arrived
+        const uint32_t xl = t.xl[m];
         xg[m] = wave_sum(dot2(xl, 0x3C003C00u, 0.f));  // (1.0, 1.0)
         if constexpr (XP == kXLds)
             xlds[m * 64 + lane] = xl;
         else
-            xs[m] = as_const(L.x + (size_t)m * L.K + (size_t)g * kGroup);  // fp16 activations only
+            xs[m] = as_const(L.x + (size_t)m * L.K + (size_t)g * kGroup);
     }
     float acc[M][T::NKEYS];
 #pragma unroll
@@ -482,6 +484,26 @@ hipError_t launch_stack(StackParams p, int max_cost, bool from_parent, hipStream
         case 4: return launch_stack_m<4>(p, max_cost, from_parent, s);
     }
     return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------------------------ bf16 activations for the kernels above
+// One small launch ahead of a vector-ALU launch whose layers (some of them) take bf16 activations: those layers'
+// activations (LayerDesc::x_bf16) go, as fp16, to the room the workspace keeps for them, which is where LayerDesc::x of
+// such a layer points: the kernels above never see the difference.  32 workgroups per layer; layers without the flag
+// return at once.
+constexpr int kXcvtBlocks = 32;
+__global__ __launch_bounds__(256) void xcvt_kernel(const StackParams p) {
+    const int li = (int)(blockIdx.x / kXcvtBlocks), bx = (int)(blockIdx.x % kXcvtBlocks);
+    const LayerDesc L = p.table ? load_desc(p.table + li) : p.single;
+    if (!(L.flags & kFlagXBf16)) return;
+    const uint32_t MQ_GLOBAL *src = gl(reinterpret_cast<const uint32_t *>(L.x_bf16));
+    uint32_t MQ_GLOBAL *dst = gl(reinterpret_cast<uint32_t *>(const_cast<_Float16 *>(L.x)));
+    const int64_t pairs = (int64_t)L.M * L.K / 2;
+    for (int64_t i = (int64_t)bx * 256 + threadIdx.x; i < pairs; i += (int64_t)kXcvtBlocks * 256)
+        dst[i] = bf16_pair_to_f16_pair(src[i]);
+}
+hipError_t launch_xcvt(const StackParams &p, hipStream_t s) {
+    return launch(xcvt_kernel, dim3((unsigned)(p.n_layers * kXcvtBlocks)), dim3(256), 0, s, p);
 }
 
 }  // namespace mq

@@ -445,11 +445,9 @@ __device__ __forceinline__ void run_wide_units(const LayerDesc &L, const StackPa
         } else if constexpr (piece == kWBlocks) {
             if (lane < 8) dma_lines<1, true>(reinterpret_cast<const uint8_t *>(L.st) + tile * 128 + lane * 16, dst + R * 1024);
         } else {
-            // A symmetric layer has no zero-offset array (every zero-offset is 2^(c-1), see open_tile): its scales line is
-            // transferred once more instead (a cache hit), because the number of transfers per tile body is what the
-            // waits count and must not depend on the layer.
-            const uint8_t *zsrc = reinterpret_cast<const uint8_t *>(L.zt ? L.zt : L.st);
-            if (lane < 8) dma_lines<1, true>(zsrc + tile * 128 + lane * 16, dst + R * 1024 + 128);
+            // A symmetric layer reads constant lines of 2^(c-1) (tile & zmask picks one).
+            const uint8_t *zsrc = reinterpret_cast<const uint8_t *>(L.zt);
+            if (lane < 8) dma_lines<1, true>(zsrc + (tile & (size_t)(int64_t)L.zmask) * 128 + lane * 16, dst + R * 1024 + 128);
             if (n_pf > 1) {
                 --n_pf;
                 if (++g_pf == G) { g_pf = 0; ++s_pf; }
@@ -471,7 +469,6 @@ __device__ __forceinline__ void run_wide_units(const LayerDesc &L, const StackPa
         }
         t.s = reinterpret_cast<const MQ_LDS _Float16 *>(src + R * 1024)[lane];
         t.z = reinterpret_cast<const MQ_LDS _Float16 *>(src + R * 1024 + 128)[lane];
-        if (!L.zt) t.z = (_Float16)(float)(1 << (kC - 1));
         wide_prework<R>(t, e, sc, nz);
     };
     // ---- activations of the next group in line (the C chunks of this pass) -> LDS stage; kXLines transfers
