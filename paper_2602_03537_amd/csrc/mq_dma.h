@@ -58,6 +58,42 @@ __device__ __forceinline__ void dma_lines(const uint8_t *src_lane, MQ_LDS uint8_
 #undef MQ_DMA_LINES
     if constexpr (N > 4) dma_lines<N - 4, NT>(src_lane + 4096, dst_wave + 4096);
 }
+// N transfers (N <= 4) of ONE line to one place: for a wave that must issue as many transfers as the others but has
+// nothing left to fetch (after the first they are cache hits)
+template <int N, bool NT = false>
+__device__ __forceinline__ void dma_same_line(const uint8_t *src_lane, MQ_LDS uint8_t *dst_wave) {
+    static_assert(N >= 1 && N <= 4, "up to four transfers");
+    const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst_wave);
+    const uint8_t MQ_GLOBAL *src = gl(src_lane);
+#define MQ_DMA_SAME(POL)                                                                                               \
+    if constexpr (N == 1)                                                                                              \
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" POL ::"s"(base), "v"(src)         \
+                     : "memory");                                                                                      \
+    else if constexpr (N == 2)                                                                                         \
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" POL "\n\t"                        \
+                     "global_load_lds_dwordx4 %1, off" POL ::"s"(base),                                                \
+                     "v"(src)                                                                                          \
+                     : "memory");                                                                                      \
+    else if constexpr (N == 3)                                                                                         \
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" POL "\n\t"                        \
+                     "global_load_lds_dwordx4 %1, off" POL "\n\t"                                                      \
+                     "global_load_lds_dwordx4 %1, off" POL ::"s"(base),                                                \
+                     "v"(src)                                                                                          \
+                     : "memory");                                                                                      \
+    else                                                                                                               \
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" POL "\n\t"                        \
+                     "global_load_lds_dwordx4 %1, off" POL "\n\t"                                                      \
+                     "global_load_lds_dwordx4 %1, off" POL "\n\t"                                                      \
+                     "global_load_lds_dwordx4 %1, off" POL ::"s"(base),                                                \
+                     "v"(src)                                                                                          \
+                     : "memory");
+    if constexpr (NT) {
+        MQ_DMA_SAME(" nt")
+    } else {
+        MQ_DMA_SAME("")
+    }
+#undef MQ_DMA_SAME
+}
 // block B (four lines each, the last one shorter) of an N-line transfer
 template <int N, int B, bool NT = false>
 __device__ __forceinline__ void dma_block(const uint8_t *src_lane, MQ_LDS uint8_t *dst_wave) {

@@ -49,9 +49,16 @@ template <int R> struct Mfma {
     static constexpr int NMF = NQ * T::NOPS;       // MFMAs per tile on the masked fields
     static constexpr int NBLK = NMF + 1;           // operand blocks per tile: theirs and the zero-offset's
     static_assert(NU % 4 == 0, "units must come in quads");
-    static_assert(NBLK * 256 + 64 <= kNarrowXtBlockBytes, "operand blocks and factors must fit the activation block");
 };
+// Activation block of a group: NBLK operand blocks of 272 bytes = 16 batch columns x 16 bytes (the eight halves a lane
+// supplies as B) followed by 16 bytes that are always zero: a lane whose B operand is zero (the other k-half) reads
+// those, so that no B read is masked.  The 16 factors F sit at the end.
+constexpr int kOpBlockStride = 272;
 constexpr int kFactorOff = kNarrowXtBlockBytes - 64;  // 16 floats F at the end of an activation block
+static_assert(Mfma<2>::NBLK * kOpBlockStride <= kFactorOff && Mfma<3>::NBLK * kOpBlockStride <= kFactorOff &&
+                  Mfma<4>::NBLK * kOpBlockStride <= kFactorOff && Mfma<6>::NBLK * kOpBlockStride <= kFactorOff &&
+                  Mfma<8>::NBLK * kOpBlockStride <= kFactorOff,
+              "operand blocks and factors must fit the activation block");
 
 // ------------------------------------------------------------------ activation prep
 // One wave per (layer, group): writes the activation block of the group: the B operands of the NMF MFMAs of a tile
@@ -76,6 +83,7 @@ template <int R> __device__ __forceinline__ void xprep_job(const LayerDesc &L, i
         gl(reinterpret_cast<const uint32_t *>(L.x + (size_t)(live ? m : 0) * L.K) + (size_t)g * 64);
     uint8_t *block = reinterpret_cast<uint8_t *>(const_cast<uint4 *>(L.xt)) + (size_t)g * kNarrowXtBlockBytes;
     uint32_t MQ_GLOBAL *out = gl(reinterpret_cast<uint32_t *>(block)) + lane;
+    constexpr int kBlkDw = kOpBlockStride / 4;  // block stride in dwords
     uint32_t v[NMF];
     static_for<NMF>([&](auto mf) {
         constexpr int Q = mf / T::NOPS;
@@ -107,8 +115,13 @@ template <int R> __device__ __forceinline__ void xprep_job(const LayerDesc &L, i
     static_for<NMF>([&](auto mf) {
         constexpr Op o = T::op(mf % T::NOPS);
         constexpr int key = ctz16(o.mask) - o.d;
-        out[mf * 64] = scale_pair(v[mf], base * __builtin_ldexpf(1.f, -key));
+        out[mf * kBlkDw] = scale_pair(v[mf], base * __builtin_ldexpf(1.f, -key));
     });
+    // the always-zero 16 bytes behind every operand block
+    if (lane < 4) {
+#pragma unroll
+        for (int b = 0; b <= NMF; ++b) out[b * kBlkDw + 64] = 0u;
+    }
     // the zero-offset block: -X_g * 2^(e-15) in three fp16 pieces (hi, mid, lo), then zeros
     const float xs = -s * base * 0x1p-15f;
     const _Float16 p0 = (_Float16)xs;
@@ -116,7 +129,7 @@ template <int R> __device__ __forceinline__ void xprep_job(const LayerDesc &L, i
     const _Float16 p1 = (_Float16)r1;
     const _Float16 p2 = (_Float16)(r1 - (float)p1);
     const half2_t d0 = {p0, p1}, d1 = {p2, (_Float16)0.f};
-    out[NMF * 64] = j == 0 ? __builtin_bit_cast(uint32_t, d0) : j == 1 ? __builtin_bit_cast(uint32_t, d1) : 0u;
+    out[NMF * kBlkDw] = j == 0 ? __builtin_bit_cast(uint32_t, d0) : j == 1 ? __builtin_bit_cast(uint32_t, d1) : 0u;
     // F = 2^(32 - r - e): what turns the accumulator back into code units times Eq. 1's rescale
     if (j == 0) gl(reinterpret_cast<float *>(block + kFactorOff))[m] = __builtin_ldexpf(1.f, 32 - R - e);
 }
@@ -200,7 +213,6 @@ __device__ __forceinline__ void run_narrow_units(const LayerDesc &L, const Stack
     const uint8_t *xt = reinterpret_cast<const uint8_t *>(L.xt);
     MQ_LDS uint8_t *ring = lds + NST * kStageBytes + wv * (NBR * kSlot);
     const LaneMap lm = lane_map(lane);
-    const bool b_live = lm.b_live && lm.col < L.M;  // a lane whose batch column lies beyond M supplies zeros as well
 
     int srb = u_begin / G;
     int g = u_begin - srb * G;
@@ -209,9 +221,12 @@ __device__ __forceinline__ void run_narrow_units(const LayerDesc &L, const Stack
 #pragma unroll
     for (int v = 0; v < 16; ++v) yacc[v] = 0.f;
 
-    // ---- weights: kTileOps transfers per tile into ring slot `slot`; past the end of the run the last tile is
-    // fetched again (the number of transfers per tile body must not depend on the data)
+    // ---- weights: kTileOps transfers per tile into ring slot `slot`.  The number of transfers per tile body must
+    // not depend on the data, so past the end of the run there are as many, but of one line of the last tile over and
+    // over (cache hits: a run of a single call is short, and whole tiles fetched for nothing would be a fifth of its
+    // traffic); nobody reads what they bring.
     int s_pf = srb, g_pf = g, n_pf = u_end - u_begin;  // tile to fetch next, tiles left to fetch
+    bool past_end = false;
     constexpr int kWBlocks = (R + 3) / 4;  // pieces of a tile transfer: weight blocks of up to four lines, scales, zeros
     auto fetch_tile_piece = [&](auto piece, int slot) {
         int rb = kNarrowRowBlocks * s_pf + wv;
@@ -219,7 +234,9 @@ __device__ __forceinline__ void run_narrow_units(const LayerDesc &L, const Stack
         const size_t tile = (size_t)rb * G + g_pf;
         MQ_LDS uint8_t *dst = ring + slot * kSlot;
         if constexpr (piece < kWBlocks) {
-            dma_block<R, piece, true>(reinterpret_cast<const uint8_t *>(L.Wp) + tile * (R * 1024) + lane * 16, dst);
+            const uint8_t *src = reinterpret_cast<const uint8_t *>(L.Wp) + tile * (R * 1024) + lane * 16;
+            if (past_end) dma_same_line<(R - 4 * piece < 4 ? R - 4 * piece : 4), true>(src, dst);
+            else dma_block<R, piece, true>(src, dst);
         } else if constexpr (piece == kWBlocks) {
             if (lane < 8) dma_lines<1, true>(reinterpret_cast<const uint8_t *>(L.st) + tile * 128 + lane * 16, dst + R * 1024);
         } else {
@@ -229,6 +246,8 @@ __device__ __forceinline__ void run_narrow_units(const LayerDesc &L, const Stack
             if (n_pf > 1) {
                 --n_pf;
                 if (++g_pf == G) { g_pf = 0; ++s_pf; }
+            } else {
+                past_end = true;
             }
         }
     };
@@ -297,13 +316,15 @@ __device__ __forceinline__ void run_narrow_units(const LayerDesc &L, const Stack
         // ---- one tile: NMF MFMAs on the masked fields, one on the zero-offset, into two accumulators taken
         // alternately (an MFMA that adds to the result of the one before it cannot issue until that result has left
         // the pipe), then y += scale * (F * D).  B operands come from the stage, read a few MFMAs ahead; lanes whose
-        // operand is zero do not read.
-        const MQ_LDS u32x4 *bsrc = reinterpret_cast<const MQ_LDS u32x4 *>(lds + st * kStageBytes) + lm.col;
+        // operand is zero read the zeros behind the block.
+        // (the activation block holds zeros for batch columns beyond M)
+        const MQ_LDS u32x4 *bsrc =
+            reinterpret_cast<const MQ_LDS u32x4 *>(lds + st * kStageBytes + (lm.b_live ? lm.col * 16 : 256));
         const float F = reinterpret_cast<const MQ_LDS float *>(lds + st * kStageBytes + kFactorOff)[lm.col];
+        constexpr int kBlk = kOpBlockStride / 16;  // block stride in 16-byte units
         constexpr int kAhead = 4;
         u32x4 bq[kAhead];
-        static_for<kAhead>([&](auto i) { bq[i] = u32x4{0u, 0u, 0u, 0u}; });
-        if (b_live) static_for<kAhead>([&](auto i) { bq[i] = bsrc[i * 16]; });
+        static_for<kAhead>([&](auto i) { bq[i] = bsrc[i * kBlk]; });
         float16_t D0, D1;
 #pragma unroll
         for (int v = 0; v < 16; ++v) D0[v] = D1[v] = 0.f;
@@ -319,9 +340,7 @@ __device__ __forceinline__ void run_narrow_units(const LayerDesc &L, const Stack
             }
             const u32x4 av = {a[0], a[1], a[2], a[3]};
             const u32x4 bv = bq[mf % kAhead];
-            if constexpr (mf + kAhead < MF::NBLK) {
-                if (b_live) bq[mf % kAhead] = bsrc[(mf + kAhead) * 16];
-            }
+            if constexpr (mf + kAhead < MF::NBLK) bq[mf % kAhead] = bsrc[(mf + kAhead) * kBlk];
             if constexpr (mf % 2 == 0)
                 D0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, av), __builtin_bit_cast(half8_t, bv),
                                                             D0, 0, 0, 0);
