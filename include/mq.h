@@ -335,8 +335,9 @@ typedef struct {
 } mq_layer;
 
 /* bf16 activations and outputs, per layer.
- *   MQ_X_BF16 : x points to bfloat16 values.  They are converted to fp16 where the kernels consume
- *               them, which is exact for every value whose magnitude is within the fp16 range
+ *   MQ_X_BF16 : x points to bfloat16 values.  They are converted to fp16 before they are multiplied
+ *               (M <= 4: by a small launch of its own ahead of the layer's, into the workspace; M > 4:
+ *               inside the activation preparation), which is exact for every value whose magnitude is within the fp16 range
  *               (2^-14 <= |x| <= 65504, and 0): results are then those of the same values given as
  *               fp16, bit for bit.  Larger magnitudes become infinities, smaller ones keep what
  *               fp16 subnormals hold (absolute error <= 2^-25).
