@@ -1039,7 +1039,9 @@ def test_read_probe_xors_every_word_once():
 # ------------------------------------------------------------------ symmetric layers (no zero-offset array)
 @pytest.mark.parametrize("r", WIDTHS)
 @pytest.mark.parametrize("shape_m", [(200, 768, 1), (130, 384, 3), (512, 4096, 4), (257, 1280, 8), (448, 2048, 16),
-                                     (320, 640, 40), (700, 1152, 200), (1, 256, 1)])
+                                     (320, 640, 40), (700, 1152, 200), (1, 256, 1),
+                                     # more than 1024 tiles: the constant lines a symmetric layer reads are used many times over
+                                     (2304, 4096, 1), (2304, 4096, 8), (2240, 4224, 24)])
 def test_symmetric_layer_without_zero_offsets(r, shape_m):
     # zeros_t = NULL means every zero-offset is 128 (the paper's own setting): the oracle gets an array of 128s,
     # and the library's result equals, bit for bit, what it computes from such an array
