@@ -172,10 +172,12 @@ struct PlanHeader {
     uint64_t table_off, cnt_off, part_off, total_bytes;
     int32_t from_parent, path_M;
     int32_t ll_blocks, ll_waves;  // low-latency launch shape of a small stack, or 0
-    int32_t any_x_bf16, pad;      // some layer takes bf16 activations (the vector-ALU launches convert them first)
+    int32_t any_x_bf16;           // some layer takes bf16 activations (the vector-ALU launches convert them first)
+    int32_t ll_ks_cap;            // low-latency launch shape: most K slices per row block
+    int32_t ll_start[16];         // ... and each layer's first workgroup
 };
 static_assert(sizeof(PlanHeader) <= sizeof(mq_plan), "the header must fit the caller's handle");
-constexpr uint64_t kPlanMagic = 0x4d51504c414e3037ull;  // "MQPLAN07"
+constexpr uint64_t kPlanMagic = 0x4d51504c414e3038ull;  // "MQPLAN08"
 
 // ---- scratch of mq_linear_noalloc: device memory that exists without anybody allocating it.
 // The array's name is only a host-side stand-in; its device address is looked up once per device (each device
@@ -554,10 +556,12 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
     h.from_parent = layers[0].from_parent;
     h.path_M = (int32_t)Mp;
     {
-        int nb = 0, nw = 0;
-        if (!use_mfma(Mp) && linear_rb_stack_shape(table.data(), n_layers, partial_bytes(Mp), &nb, &nw)) {
+        int nb = 0, nw = 0, kc = 0;
+        if (!use_mfma(Mp) && linear_rb_stack_shape(table.data(), n_layers, partial_bytes(Mp), layers[0].from_parent != 0,
+                                                   &nb, &nw, &kc, h.ll_start)) {
             h.ll_blocks = nb;
             h.ll_waves = nw;
+            h.ll_ks_cap = kc;
         }
     }
     h.check = plan_check(h);
@@ -588,6 +592,8 @@ mq_status mq_linear_stack(const mq_plan *plan, mq_stream stream) {
     p.M = h.M;
     p.slot_floats = slot_floats(h.path_M);
     p.n_jobs = h.n_jobs;
+    p.ks_cap = h.ll_ks_cap;
+    std::memcpy(p.ll_start, h.ll_start, sizeof(p.ll_start));
     if (!use_mfma(h.path_M) && h.any_x_bf16) {
         if (launch_xcvt(p, (hipStream_t)stream) != hipSuccess) return MQ_ERR_HIP;
     }

@@ -86,6 +86,8 @@ struct StackParams {
     int32_t slot_floats;     // floats per partial-sum slot (64*M; a workgroup's 8 x 64*16 on the narrow matrix-core path)
     int32_t n_jobs;          // prep kernel jobs (MFMA path)
     int32_t worker_cap;      // 0, or: `part` holds slots for this many schedule shares only (a small workspace)
+    int32_t ks_cap;          // low-latency launch of a small stack: most K slices per row block (0: as one layer would choose)
+    int32_t ll_start[16];    // ... and the first workgroup of each layer (a workgroup finds its layer without reading the table)
     LayerDesc single;
 };
 
@@ -177,7 +179,10 @@ bool linear_rb_fits(const LayerDesc &L, size_t part_bytes);
 hipError_t launch_linear_rb(const LayerDesc &L, float *part, int32_t *cnt, hipStream_t s);
 // The same shape for a small stack (M <= kValuMaxM): all layers' workgroups in one launch.  `table` is the host copy
 // of the descriptors; false = the stack is too big for it.
-bool linear_rb_stack_shape(const LayerDesc *table, int n_layers, size_t part_bytes, int *blocks, int *waves);
+// ks_cap: see StackParams.
+// ll_start: see StackParams (16 entries).
+bool linear_rb_stack_shape(const LayerDesc *table, int n_layers, size_t part_bytes, bool from_parent, int *blocks,
+                           int *waves, int *ks_cap, int32_t *ll_start);
 hipError_t launch_linear_rb_stack(const StackParams &p, int blocks, int waves, bool from_parent, hipStream_t s);
 // MFMA path (M > kValuMaxM): activation prep kernel + persistent MFMA kernel.
 hipError_t launch_stack_mfma(StackParams p, int max_cost, hipStream_t s);

@@ -321,11 +321,23 @@ __host__ __device__ static inline int pick_k_slices(const LayerDesc &L) {
     return ks < 1 ? 1 : ks;
 }
 
+// K slices of a layer inside a small stack: as alone, but no more than the stack's launch shape allows
+__host__ __device__ static inline int stack_k_slices(const LayerDesc &L, int ks_cap) {
+    const int ks = pick_k_slices(L);
+    return ks_cap > 0 && ks > ks_cap ? ks_cap : ks;
+}
+
+// Waves per workgroup for a K slice of per_block groups (sweeps on the Llama-2-7B shapes, r = 2, 4, 8: 16 waves from 16
+// groups on, e.g. 4096 x 11008 in four slices of 21-22 groups: 8.3 / 9.6 / 12.9 -> 7.9 / 9.1 / 11.8 us)
+static int rb_waves(const LayerDesc &L, int KS) {
+    const int per_block = (L.G + KS - 1) / KS;
+    return (per_block >= 16 || (KS == 1 && per_block >= 12)) ? 16 : per_block >= 6 ? 8 : 4;
+}
+
 template <int R, int M, bool SL = false>
 static hipError_t launch_linear_rb_rm(const LayerDesc &L, float *part, int32_t *cnt, hipStream_t s) {
     const int KS = pick_k_slices(L);
-    const int per_block = (L.G + KS - 1) / KS;
-    const int W = (per_block >= 24 || (KS == 1 && per_block >= 12)) ? 16 : per_block >= 6 ? 8 : 4;
+    const int W = rb_waves(L, KS);
     return launch((linear_rb_kernel<R, M, kXLds, SL>), dim3((unsigned)(L.RB * KS)), dim3(64 * W), 0, s, L, KS, part,
                        cnt);
 }
@@ -362,15 +374,16 @@ template <int M, int XP, bool SL>
 __global__ __launch_bounds__(1024) void linear_rb_stack_kernel(const StackParams p) {
     __shared__ float red[16][M][64];
     __shared__ __attribute__((aligned(16))) uint32_t xlds_all[XP == kXLds ? 16 * M * 64 : 4];
-    int blk = (int)blockIdx.x, slot0 = 0, li = 0;
-    LayerDesc L = load_desc(p.table);
-    int KS = pick_k_slices(L);
-    while (blk >= L.RB * KS && li + 1 < p.n_layers) {  // the grid holds exactly sum(RB * KS) workgroups
-        blk -= L.RB * KS;
-        slot0 += L.RB * KS;
-        L = load_desc(p.table + ++li);
-        KS = pick_k_slices(L);
-    }
+    // the grid holds exactly sum(RB * KS) workgroups; each layer's first one comes with the kernel arguments, so the only
+    // thing a workgroup reads before its tiles is its own descriptor (a walk along the table was a chain of dependent
+    // loads, 0.5 us each, for the later layers)
+    int li = 0;
+#pragma unroll
+    for (int i = 1; i < 16; ++i)
+        if (i < p.n_layers && (int)blockIdx.x >= p.ll_start[i]) li = i;
+    const int slot0 = p.ll_start[li], blk = (int)blockIdx.x - slot0;
+    const LayerDesc L = load_desc(p.table + li);
+    const int KS = stack_k_slices(L, p.ks_cap);
     int32_t *cnt = p.cnt + L.cnt_off;
     if constexpr (SL) {
         linear_rb_body<8, M, XP, true>(L, KS, blk, slot0, p.part, cnt, red, xlds_all);
@@ -385,28 +398,71 @@ __global__ __launch_bounds__(1024) void linear_rb_stack_kernel(const StackParams
     }
 }
 
-static int rb_waves(const LayerDesc &L) {
-    const int KS = pick_k_slices(L);
-    const int per_block = (L.G + KS - 1) / KS;
-    return (per_block >= 24 || (KS == 1 && per_block >= 12)) ? 16 : per_block >= 6 ? 8 : 4;
+// workgroups of `waves` waves of the small-stack kernel that the device holds at one time
+template <int M, bool SL> static int rb_stack_resident(int waves) {
+    static int cached[3] = {0, 0, 0};
+    const int slot = waves == 16 ? 0 : waves == 8 ? 1 : 2;
+    if (cached[slot]) return cached[slot];
+    int dev = 0, cus = 0, b = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&b, linear_rb_stack_kernel<M, kXLds, SL>, 64 * waves, 0) != hipSuccess)
+        return 0;
+    cached[slot] = cus * (b < 1 ? 1 : b);
+    return cached[slot];
+}
+static int rb_stack_resident_m(int M, bool from_parent, int waves) {
+    switch (M) {
+        case 1: return from_parent ? rb_stack_resident<1, true>(waves) : rb_stack_resident<1, false>(waves);
+        case 2: return from_parent ? rb_stack_resident<2, true>(waves) : rb_stack_resident<2, false>(waves);
+        case 3: return from_parent ? rb_stack_resident<3, true>(waves) : rb_stack_resident<3, false>(waves);
+        default: return from_parent ? rb_stack_resident<4, true>(waves) : rb_stack_resident<4, false>(waves);
+    }
 }
 
 // A stack is "small" when all its layers together still fit the low-latency shape (same bound as for one layer).
-// Returns the launch shape: workgroups = sum of RB * KS, waves per workgroup = the most any layer wants.
-bool linear_rb_stack_shape(const LayerDesc *table, int n_layers, size_t part_bytes, int *blocks, int *waves) {
+// Returns the launch shape: workgroups = sum of RB * KS, waves per workgroup = the most any layer wants -- unless the
+// device cannot hold all those workgroups at one time: the ones left over would start when the first have finished,
+// and a launch this short then takes half as long again (three 4096 x 4096 layers: 768 workgroups of 8 waves where 512
+// fit).  Then first the waves per workgroup are halved (a wave takes more tiles), then the K slices.
+bool linear_rb_stack_shape(const LayerDesc *table, int n_layers, size_t part_bytes, bool from_parent, int *blocks,
+                           int *waves, int *ks_cap, int32_t *ll_start) {
     if (n_layers > 16 || table[0].M > kValuMaxM) return false;
     int64_t tiles = 0, slots = 0;
-    int nb = 0, W = 4;
     for (int i = 0; i < n_layers; ++i) {
         tiles += (int64_t)table[i].RB * table[i].G;
         slots += (int64_t)table[i].RB * 8;
-        nb += table[i].RB * pick_k_slices(table[i]);
-        const int w = rb_waves(table[i]);
-        if (w > W) W = w;
     }
     if (tiles > 12288 || (size_t)slots * (size_t)table[0].M * 64 * sizeof(float) > part_bytes) return false;
+    auto shape = [&](int cap, int *nb, int *W) {
+        *nb = 0;
+        *W = 4;
+        for (int i = 0; i < n_layers; ++i) {
+            const int ks = stack_k_slices(table[i], cap);
+            *nb += table[i].RB * ks;
+            const int w = rb_waves(table[i], ks);
+            if (w > *W) *W = w;
+        }
+    };
+    int nb = 0, W = 4, cap = 0;
+    shape(0, &nb, &W);
+    for (;;) {
+        const int fit = rb_stack_resident_m(table[0].M, from_parent, W);
+        if (fit <= 0 || nb <= fit) break;
+        if (W > 4) { W /= 2; continue; }
+        const int next = cap == 0 ? 4 : cap / 2;
+        if (next < 1) break;
+        cap = next;
+        shape(cap, &nb, &W);
+    }
     *blocks = nb;
     *waves = W;
+    *ks_cap = cap;
+    int start = 0;
+    for (int i = 0; i < 16; ++i) {
+        ll_start[i] = start;
+        if (i < n_layers) start += table[i].RB * stack_k_slices(table[i], cap);
+    }
     return true;
 }
 
