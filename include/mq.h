@@ -363,7 +363,7 @@ size_t mq_stack_workspace_bytes(const mq_layer *layers, int n_layers, int64_t M)
  * as long as that workspace and the layers' buffers are, may be copied freely, and must be filled
  * again if the workspace is reused for anything else. */
 typedef struct {
-    uint64_t opaque[32];
+    uint64_t opaque[272];
 } mq_plan;
 
 /* Validate the layers and build the schedule of the stack: the descriptor table is written into

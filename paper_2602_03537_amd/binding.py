@@ -53,7 +53,7 @@ class MqLayer(ctypes.Structure):
 
 class MqPlan(ctypes.Structure):
     """mq_plan of include/mq.h: the host-side header of a planned stack (opaque)."""
-    _fields_ = [("opaque", ctypes.c_uint64 * 32)]
+    _fields_ = [("opaque", ctypes.c_uint64 * 272)]
 
 
 class StackPlan:

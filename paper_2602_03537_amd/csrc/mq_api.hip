@@ -176,7 +176,10 @@ struct PlanHeader {
     int32_t ll_ks_cap;            // low-latency launch shape: most K slices per row block
     int32_t ll_start[16];         // ... and each layer's first workgroup
 };
-static_assert(sizeof(PlanHeader) <= sizeof(mq_plan), "the header must fit the caller's handle");
+// the caller's handle: the header, then (small stacks) the descriptors that travel with the kernel arguments
+constexpr size_t kPlanTableOff = 256;
+static_assert(sizeof(PlanHeader) <= kPlanTableOff && kPlanTableOff + sizeof(SmallTable) <= sizeof(mq_plan),
+              "header and descriptors must fit the caller's handle");
 constexpr uint64_t kPlanMagic = 0x4d51504c414e3038ull;  // "MQPLAN08"
 
 // ---- scratch of mq_linear_noalloc: device memory that exists without anybody allocating it.
@@ -202,13 +205,20 @@ mq_status scratch_of_current_device(void **out) {
     return MQ_OK;
 }
 
-uint64_t plan_check(const PlanHeader &h) {
+// fold of the header (check field as zero) and, for a small stack, of the descriptors behind it
+uint64_t plan_check(const PlanHeader &h, const SmallTable *small) {
     PlanHeader t = h;
     t.check = 0;
     uint64_t w[sizeof(PlanHeader) / 8 + 1] = {};
     std::memcpy(w, &t, sizeof(t));
     uint64_t acc = 0x9e3779b97f4a7c15ull;
     for (uint64_t v : w) acc = (acc ^ v) * 0x100000001b3ull + (acc >> 29);
+    if (small) {
+        static_assert(sizeof(SmallTable) % 8 == 0, "descriptors are folded as 64-bit words");
+        uint64_t d[sizeof(SmallTable) / 8];
+        std::memcpy(d, small, sizeof(d));
+        for (uint64_t v : d) acc = (acc ^ v) * 0x100000001b3ull + (acc >> 29);
+    }
     return acc;
 }
 
@@ -564,7 +574,10 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
             h.ll_ks_cap = kc;
         }
     }
-    h.check = plan_check(h);
+    SmallTable small{};
+    if (h.ll_blocks)
+        for (int i = 0; i < n_layers; ++i) small.d[i] = table[i];
+    h.check = plan_check(h, h.ll_blocks ? &small : nullptr);
 
     // The descriptor table travels to the device inside kernel arguments (copied when the launch is enqueued), so the
     // host arrays may go away as soon as this returns and nothing is waited for.
@@ -574,6 +587,7 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
     if (launch_fill_zero(base_dev + pl.cnt_off, pl.cnt_bytes, s) != hipSuccess) return MQ_ERR_HIP;
     std::memset(plan, 0, sizeof(*plan));
     std::memcpy(plan, &h, sizeof(h));
+    if (h.ll_blocks) std::memcpy(reinterpret_cast<char *>(plan) + kPlanTableOff, &small, sizeof(small));
     return MQ_OK;
 }
 
@@ -581,7 +595,10 @@ mq_status mq_linear_stack(const mq_plan *plan, mq_stream stream) {
     if (!plan) return MQ_ERR_NULL;
     PlanHeader h{};
     std::memcpy(&h, plan, sizeof(h));
-    if (h.magic != kPlanMagic || h.check != plan_check(h) || !h.ws) return MQ_ERR_BAD_SHAPE;  // not a filled plan
+    if (h.magic != kPlanMagic || !h.ws) return MQ_ERR_BAD_SHAPE;  // not a filled plan
+    SmallTable small{};
+    if (h.ll_blocks) std::memcpy(&small, reinterpret_cast<const char *>(plan) + kPlanTableOff, sizeof(small));
+    if (h.check != plan_check(h, h.ll_blocks ? &small : nullptr)) return MQ_ERR_BAD_SHAPE;
     char *base = static_cast<char *>(h.ws);
     StackParams p{};
     p.table = reinterpret_cast<const LayerDesc *>(base + h.table_off);
@@ -599,7 +616,7 @@ mq_status mq_linear_stack(const mq_plan *plan, mq_stream stream) {
     }
     const hipError_t e = use_wide(h.path_M)   ? launch_stack_wide(p, h.max_cost, (hipStream_t)stream)
                          : use_mfma(h.path_M) ? launch_stack_mfma(p, h.max_cost, (hipStream_t)stream)
-                         : h.ll_blocks        ? launch_linear_rb_stack(p, h.ll_blocks, h.ll_waves, h.from_parent != 0,
+                         : h.ll_blocks        ? launch_linear_rb_stack(p, small, h.ll_blocks, h.ll_waves, h.from_parent != 0,
                                                                        (hipStream_t)stream)
                                               : launch_stack(p, h.max_cost, h.from_parent != 0, (hipStream_t)stream);
     return e == hipSuccess ? MQ_OK : MQ_ERR_HIP;

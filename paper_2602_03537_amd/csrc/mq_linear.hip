@@ -371,7 +371,7 @@ hipError_t launch_linear_rb(const LayerDesc &L, float *part, int32_t *cnt, hipSt
 // The same shape for a SMALL stack (the linears of a decoder block that share their input, say): the workgroups of all
 // layers in one launch; a workgroup finds its layer by walking the table (a handful of entries).
 template <int M, int XP, bool SL>
-__global__ __launch_bounds__(1024) void linear_rb_stack_kernel(const StackParams p) {
+__global__ __launch_bounds__(1024) void linear_rb_stack_kernel(const StackParams p, const SmallTable t) {
     __shared__ float red[16][M][64];
     __shared__ __attribute__((aligned(16))) uint32_t xlds_all[XP == kXLds ? 16 * M * 64 : 4];
     // the grid holds exactly sum(RB * KS) workgroups; each layer's first one comes with the kernel arguments, so the only
@@ -382,7 +382,7 @@ __global__ __launch_bounds__(1024) void linear_rb_stack_kernel(const StackParams
     for (int i = 1; i < 16; ++i)
         if (i < p.n_layers && (int)blockIdx.x >= p.ll_start[i]) li = i;
     const int slot0 = p.ll_start[li], blk = (int)blockIdx.x - slot0;
-    const LayerDesc L = load_desc(p.table + li);
+    const LayerDesc L = t.d[li];
     const int KS = stack_k_slices(L, p.ks_cap);
     int32_t *cnt = p.cnt + L.cnt_off;
     if constexpr (SL) {
@@ -427,7 +427,7 @@ static int rb_stack_resident_m(int M, bool from_parent, int waves) {
 // fit).  Then first the waves per workgroup are halved (a wave takes more tiles), then the K slices.
 bool linear_rb_stack_shape(const LayerDesc *table, int n_layers, size_t part_bytes, bool from_parent, int *blocks,
                            int *waves, int *ks_cap, int32_t *ll_start) {
-    if (n_layers > 16 || table[0].M > kValuMaxM) return false;
+    if (n_layers > kSmallStackLayers || table[0].M > kValuMaxM) return false;
     int64_t tiles = 0, slots = 0;
     for (int i = 0; i < n_layers; ++i) {
         tiles += (int64_t)table[i].RB * table[i].G;
@@ -466,18 +466,19 @@ bool linear_rb_stack_shape(const LayerDesc *table, int n_layers, size_t part_byt
     return true;
 }
 
-template <int M> static hipError_t launch_linear_rb_stack_m(const StackParams &p, int blocks, int waves, bool from_parent,
-                                                            hipStream_t s) {
+template <int M> static hipError_t launch_linear_rb_stack_m(const StackParams &p, const SmallTable &t, int blocks, int waves,
+                                                            bool from_parent, hipStream_t s) {
     if (from_parent)
-        return launch((linear_rb_stack_kernel<M, kXLds, true>), dim3((unsigned)blocks), dim3(64 * waves), 0, s, p);
-    return launch((linear_rb_stack_kernel<M, kXLds, false>), dim3((unsigned)blocks), dim3(64 * waves), 0, s, p);
+        return launch((linear_rb_stack_kernel<M, kXLds, true>), dim3((unsigned)blocks), dim3(64 * waves), 0, s, p, t);
+    return launch((linear_rb_stack_kernel<M, kXLds, false>), dim3((unsigned)blocks), dim3(64 * waves), 0, s, p, t);
 }
-hipError_t launch_linear_rb_stack(const StackParams &p, int blocks, int waves, bool from_parent, hipStream_t s) {
+hipError_t launch_linear_rb_stack(const StackParams &p, const SmallTable &t, int blocks, int waves, bool from_parent,
+                                  hipStream_t s) {
     switch (p.M) {
-        case 1: return launch_linear_rb_stack_m<1>(p, blocks, waves, from_parent, s);
-        case 2: return launch_linear_rb_stack_m<2>(p, blocks, waves, from_parent, s);
-        case 3: return launch_linear_rb_stack_m<3>(p, blocks, waves, from_parent, s);
-        case 4: return launch_linear_rb_stack_m<4>(p, blocks, waves, from_parent, s);
+        case 1: return launch_linear_rb_stack_m<1>(p, t, blocks, waves, from_parent, s);
+        case 2: return launch_linear_rb_stack_m<2>(p, t, blocks, waves, from_parent, s);
+        case 3: return launch_linear_rb_stack_m<3>(p, t, blocks, waves, from_parent, s);
+        case 4: return launch_linear_rb_stack_m<4>(p, t, blocks, waves, from_parent, s);
     }
     return hipErrorInvalidValue;
 }

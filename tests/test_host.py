@@ -302,7 +302,7 @@ def test_stack_run_refuses_a_header_that_no_plan_filled():
     assert L.mq_linear_stack(ctypes.byref(h), None) == _st("MQ_ERR_BAD_SHAPE")
     rng = np.random.default_rng(0)
     for _ in range(20):
-        for i in range(32):
+        for i in range(272):
             h.opaque[i] = int(rng.integers(0, 1 << 63))
         assert L.mq_linear_stack(ctypes.byref(h), None) == _st("MQ_ERR_BAD_SHAPE")
     h.opaque[0] = 0x4d51504c414e3038              # the right magic alone is not enough
