@@ -359,9 +359,11 @@ typedef struct {
 size_t mq_stack_workspace_bytes(const mq_layer *layers, int n_layers, int64_t M);
 
 /* What mq_linear_stack needs to know about a planned stack.  HOST memory owned by the caller,
- * filled by mq_stack_plan, opaque.  It names the device workspace it was built in: it is valid for
- * as long as that workspace and the layers' buffers are, may be copied freely, and must be filled
- * again if the workspace is reused for anything else. */
+ * filled by mq_stack_plan, opaque (2176 bytes: a header and, for a stack of at most 16 layers that
+ * is launched for latency, those layers' descriptors, which then travel with the kernel arguments).
+ * It names the device workspace it was built in: it is valid for as long as that workspace and the
+ * layers' buffers are, may be copied freely, and must be filled again if the workspace is reused for
+ * anything else. */
 typedef struct {
     uint64_t opaque[272];
 } mq_plan;
