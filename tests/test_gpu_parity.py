@@ -937,6 +937,35 @@ def test_stack_shared_input_fusions_qkv_and_gate_up(M):
             check_y(lay["y"], ref, f"shared input M={M} layer {i}", host[i], host[i]["r"])
 
 
+@pytest.mark.parametrize("M", [1, 3])
+def test_stack_shared_input_fusions_at_llama2_7b_size_sampled_rows(M):
+    # the real q/k/v and gate/up launches of a Llama-2-7B block: more workgroups than the device holds at one time
+    # unless the plan shrinks the launch shape (waves per workgroup, then K slices), which is what runs here
+    x = synth.make_x(M, 4096, [97, M])
+    xd = dev(x)
+    for shapes_r in ([(4096, 4096, 3), (4096, 4096, 4), (4096, 4096, 8)], [(11008, 4096, 6), (11008, 4096, 2)]):
+        host, layers = [], []
+        for i, (N, K, r) in enumerate(shapes_r):
+            L = synth.make_layer_device(N, K, M, seed=970 + 10 * M + i, device=DEV)
+            lay = mq.prepare_layer(L["parent"], L["scales"], L["zeros"], r)
+            lay.update(x=xd, y=torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV))
+            layers.append(lay)
+            host.append((L, N, r))
+        plan = mq.mq_stack_plan(layers, M)
+        for rep in range(2):                                     # counters reset themselves
+            for lay in layers:
+                lay["y"].fill_(float("nan"))
+            mq.mq_linear_stack(plan)
+            torch.cuda.synchronize()
+            for i, (lay, (L, N, r)) in enumerate(zip(layers, host)):
+                assert torch.isfinite(lay["y"]).all()
+                rows = np.unique(np.concatenate([[0, 63, 64, N - 1], np.random.default_rng([97, i]).integers(0, N, 124)]))
+                ridx = torch.from_numpy(rows).to(DEV)
+                ref = oracle.linear(x, L["parent"][ridx].cpu().numpy(), L["scales"][ridx].cpu().numpy(),
+                                    L["zeros"][ridx].cpu().numpy(), C, r, 128)
+                check_y(lay["y"][:, ridx], ref, f"7B-size shared input M={M} layer {i} r={r} rep {rep}")
+
+
 # ------------------------------------------------------------------ boundary conventions
 @pytest.mark.parametrize("shape_m_r", [(512, 512, 1, 4), (200, 1280, 3, 3), (130, 384, 8, 6), (320, 640, 40, 2), (1, 256, 1, 8)])
 def test_linear_plain_on_row_major_scales_and_zeros(shape_m_r):
