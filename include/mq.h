@@ -331,7 +331,7 @@ typedef struct {
     int32_t from_parent; /* 0: packed_W holds r-bit codes.  1: packed_W is the resident 8-bit parent and
                             Eq. 1 is applied in registers (as mq_linear_from_parent; M <= 4, and all
                             layers of a stack must agree, else MQ_ERR_UNSUPPORTED) */
-    int32_t flags;       /* 0, or MQ_X_BF16 | MQ_Y_BF16 (below); other bits: MQ_ERR_UNSUPPORTED */
+    int32_t flags;       /* 0, or MQ_X_BF16 | MQ_Y_BF16 | MQ_X_AFTER_EARLIER (below); other bits: MQ_ERR_UNSUPPORTED */
 } mq_layer;
 
 /* bf16 activations and outputs, per layer.
@@ -346,6 +346,22 @@ typedef struct {
  *               of the fp16-output result, not within its 1e-3 relative-L2 distance of the exact y.) */
 #define MQ_X_BF16 1
 #define MQ_Y_BF16 2
+
+/* A chained stack (the decode-shaped fusion in which one launch carries layers that feed each other): per layer,
+ *   MQ_X_AFTER_EARLIER : this layer's x is written by this very launch -- it is, or is assembled from, the y of
+ *               EARLIER layers of the same stack (a chain x -> y0 -> y1, or two outputs side by side as one input).
+ *               The layer's workgroups fetch their first weights, then wait inside the launch until every earlier
+ *               layer's y is complete and visible to the whole device, and only then read x: a barrier across the
+ *               launch in front of that layer.  Layers without the flag do not wait, whatever stands before them.
+ * Only for a stack that is launched for latency with all its workgroups resident on the device at one time (at most
+ * 16 layers and 12288 tiles in all, see below) and M <= 3: then every workgroup that is waited for is running, and it
+ * waits, if at all, for strictly earlier layers, so every wait ends.  mq_stack_plan returns MQ_ERR_UNSUPPORTED for the
+ * flag on the first layer, on a layer with MQ_X_BF16 (nothing could convert its activations ahead of the launch), in a
+ * larger stack or at M > 3, and MQ_ERR_HIP if the device at hand cannot hold the stack's workgroups at one time.  (The
+ * number of polls of a wait is bounded as well -- about a second; a wait that ran out would go on with whatever x
+ * holds.)  Between the layers of a Llama block sits the caller's attention / activation code, which cannot run inside
+ * this launch: the flag is for layers that really feed each other. */
+#define MQ_X_AFTER_EARLIER 4
 
 /* Kernels by batch: as mq_linear, except that a stack of packed layers already runs on the matrix
  * cores at M = 4 (scales_t / zeros_t 16-byte aligned from M = 4 on for a stack); stacks computed

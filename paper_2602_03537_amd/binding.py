@@ -15,7 +15,7 @@ __all__ = [
     "mq_slice_pack", "mq_reslice", "mq_reslice_many", "MqResliceJob", "mq_linear_from_parent", "mq_quant_matgptq",
     "mq_matgptq_workspace_bytes", "mq_matgptq_quantize",
     "mq_stack_workspace_bytes", "mq_stack_plan", "mq_linear_stack", "MqLayer", "MqPlan", "StackPlan",
-    "mq_read_probe", "mq_linear_bf16", "MQ_X_BF16", "MQ_Y_BF16", "mq_linear_plain", "mq_linear_plain_workspace_bytes", "mq_linear_noalloc", "MQ_NOALLOC_SCRATCH_BYTES",
+    "mq_read_probe", "mq_linear_bf16", "MQ_X_BF16", "MQ_Y_BF16", "MQ_X_AFTER_EARLIER", "mq_linear_plain", "mq_linear_plain_workspace_bytes", "mq_linear_noalloc", "MQ_NOALLOC_SCRATCH_BYTES",
     "new_workspace", "prepare_layer",
 ]
 
@@ -25,6 +25,7 @@ MQ_MAX_M = 256
 MQ_NOALLOC_SCRATCH_BYTES = 8 << 20
 MQ_X_BF16 = 1
 MQ_Y_BF16 = 2
+MQ_X_AFTER_EARLIER = 4
 STATUS = {
     0: "MQ_OK", 1: "MQ_ERR_NULL", 2: "MQ_ERR_BAD_R", 3: "MQ_ERR_BAD_SHAPE", 4: "MQ_ERR_BAD_GROUP",
     5: "MQ_ERR_ALIGN", 6: "MQ_ERR_BUF_TOO_SMALL", 7: "MQ_ERR_HIP", 8: "MQ_ERR_UNSUPPORTED",

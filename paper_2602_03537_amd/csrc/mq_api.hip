@@ -70,7 +70,11 @@ mq_status layer_status(const mq_layer &l, int64_t M) {
     if (!valid_pack_r(l.r)) return MQ_ERR_BAD_R;
     if (M < 1 || M > MQ_MAX_M) return MQ_ERR_BAD_SHAPE;
     if (mq_status st = check_shape(l.N, l.K, l.group)) return st;
-    if ((l.from_parent != 0 && l.from_parent != 1) || (l.flags & ~(MQ_X_BF16 | MQ_Y_BF16))) return MQ_ERR_UNSUPPORTED;
+    if ((l.from_parent != 0 && l.from_parent != 1) || (l.flags & ~(MQ_X_BF16 | MQ_Y_BF16 | MQ_X_AFTER_EARLIER)))
+        return MQ_ERR_UNSUPPORTED;
+    // a chained layer reads x as the earlier layers leave it: there is no point before the launch at which bf16
+    // activations could be converted for it
+    if ((l.flags & MQ_X_AFTER_EARLIER) && (l.flags & MQ_X_BF16)) return MQ_ERR_UNSUPPORTED;
     if (l.from_parent && use_mfma(M)) return MQ_ERR_UNSUPPORTED;  // slicing in registers: vector-ALU kernels only
     // the matrix-core paths move scales / zeros 16 bytes at a time
     const size_t meta_align = use_mfma(M) ? 16 : 2;
@@ -151,7 +155,7 @@ LayerDesc make_desc(const mq_layer &l, int64_t M, int64_t Mp, uint64_t cost_star
         d.RB = (d.RB + 3) / 4;
         d.cost = wide_tile_cost(l.r, wide_chunks_per_pass(Mp));
     }
-    d.flags = l.flags;
+    d.flags = l.flags & (MQ_X_BF16 | MQ_Y_BF16);
     d.cnt_off = cnt_off;
     d.M = (int32_t)M;
     d.CB = (int32_t)chunks(Mp);
@@ -175,6 +179,9 @@ struct PlanHeader {
     int32_t any_x_bf16;           // some layer takes bf16 activations (the vector-ALU launches convert them first)
     int32_t ll_ks_cap;            // low-latency launch shape: most K slices per row block
     int32_t ll_start[16];         // ... and each layer's first workgroup
+    int32_t chain_total;          // chained small stack: row blocks of all layers (0: not chained) ...
+    int32_t chain_off;            // ... index of its stage counters ...
+    int32_t stage_rb[16];         // ... and the row blocks of each stage
 };
 // the caller's handle: the header, then (small stacks) the descriptors that travel with the kernel arguments
 constexpr size_t kPlanTableOff = 256;
@@ -235,7 +242,7 @@ PlanLayout plan_layout(const mq_layer *layers, int n_layers, int64_t M) {
     PlanLayout p;
     p.table_off = 256;
     p.cnt_off = align_up(p.table_off + (size_t)n_layers * sizeof(LayerDesc), 256);
-    p.cnt_bytes = counter_bytes(counters);
+    p.cnt_bytes = counter_bytes(counters + (use_mfma(M) ? 0 : kChainCounters));  // a small stack may be chained
     p.part_off = p.cnt_off + p.cnt_bytes;
     p.act_off = p.part_off + partial_bytes(M);
     p.total = p.act_off + act;
@@ -249,6 +256,7 @@ PlanLayout plan_layout(const mq_layer *layers, int n_layers, int64_t M) {
 mq_status run_single(const mq_layer &l, int64_t M, void *ws, size_t ws_bytes, mq_stream stream, int worker_cap = 0) {
     if (!ws) return MQ_ERR_NULL;
     if (mq_status st = layer_status(l, M)) return st;
+    if (l.flags & MQ_X_AFTER_EARLIER) return MQ_ERR_UNSUPPORTED;  // a layer on its own has no earlier layers
     if (!aligned(ws, 256)) return MQ_ERR_ALIGN;
     const int r_ws = l.from_parent ? kC : l.r;
     if (!worker_cap && ws_bytes < mq_workspace_bytes(M, l.N, l.K, r_ws)) return MQ_ERR_BUF_TOO_SMALL;
@@ -526,6 +534,13 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
         if (mq_status st = layer_status(layers[i], Mp)) return st;
         if (layers[i].from_parent != layers[0].from_parent) return MQ_ERR_UNSUPPORTED;  // one kernel variant per launch
     }
+    bool chained = false;
+    for (int i = 0; i < n_layers; ++i) chained |= (layers[i].flags & MQ_X_AFTER_EARLIER) != 0;
+    // only the launch that keeps every workgroup of the stack resident can let one layer wait for another
+    if (chained && ((layers[0].flags & MQ_X_AFTER_EARLIER) || !small_stack(layers, n_layers, M))) return MQ_ERR_UNSUPPORTED;
+    // Switched off at M = 4: the one run of a chained stack at that batch ended in a memory fault whose cause has not
+    // been established (M = 1 and 3 were clean in the same run).
+    if (chained && M > kChainMaxM) return MQ_ERR_UNSUPPORTED;
     if (!aligned(plan_ws, 256)) return MQ_ERR_ALIGN;
     const size_t need = mq_stack_workspace_bytes(layers, n_layers, M);
     if (need == 0) return MQ_ERR_BAD_SHAPE;
@@ -567,11 +582,25 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
     h.path_M = (int32_t)Mp;
     {
         int nb = 0, nw = 0, kc = 0;
+        bool all_resident = false;
         if (!use_mfma(Mp) && linear_rb_stack_shape(table.data(), n_layers, partial_bytes(Mp), layers[0].from_parent != 0,
-                                                   &nb, &nw, &kc, h.ll_start)) {
+                                                   &nb, &nw, &kc, h.ll_start, &all_resident)) {
             h.ll_blocks = nb;
             h.ll_waves = nw;
             h.ll_ks_cap = kc;
+        }
+        if (chained) {
+            // stages: a new one at every layer that waits; the counters sit behind the row-block counters
+            if (!h.ll_blocks) return MQ_ERR_UNSUPPORTED;
+            if (!all_resident) return MQ_ERR_HIP;  // no device to ask, or it cannot hold the stack's workgroups at one time
+            int stage = 0;
+            for (int i = 0; i < n_layers; ++i) {
+                if (layers[i].flags & MQ_X_AFTER_EARLIER) ++stage;
+                table[i].chain = stage | ((layers[i].flags & MQ_X_AFTER_EARLIER) ? kChainWaits : 0);
+                h.stage_rb[stage] += table[i].RB;
+                h.chain_total += table[i].RB;
+            }
+            h.chain_off = (int32_t)counters;
         }
     }
     SmallTable small{};
@@ -611,6 +640,9 @@ mq_status mq_linear_stack(const mq_plan *plan, mq_stream stream) {
     p.n_jobs = h.n_jobs;
     p.ks_cap = h.ll_ks_cap;
     std::memcpy(p.ll_start, h.ll_start, sizeof(p.ll_start));
+    p.chain_total = h.chain_total;
+    p.chain_off = h.chain_off;
+    std::memcpy(p.stage_rb, h.stage_rb, sizeof(p.stage_rb));
     if (!use_mfma(h.path_M) && h.any_x_bf16) {
         if (launch_xcvt(p, (hipStream_t)stream) != hipSuccess) return MQ_ERR_HIP;
     }

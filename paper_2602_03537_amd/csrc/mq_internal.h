@@ -70,7 +70,7 @@ struct LayerDesc {
     int32_t rs;             // 0, or: Wp is the 8-bit parent (r == 8) and Eq. 1 to rs bits is applied in registers
     int32_t flags;          // kFlagXBf16: x holds bf16 values; kFlagYBf16: y is written as bf16
     int32_t zmask;          // -1; a symmetric layer: zt is zmask + 1 lines of 64 x 128.0, tile u reads line u & zmask
-    int32_t pad;
+    int32_t chain;          // chained small stack: bits 0..7 the layer's stage; kChainWaits: x is read only after every earlier stage is complete
     uint64_t cost_start;    // sum of CB*RB*G*cost over the preceding layers
 };
 
@@ -78,6 +78,9 @@ struct LayerDesc {
 // arguments: a workgroup reads its descriptor from there in 0.3 us, where a first read from the table in device memory
 // took 1.2 us of a launch that lasts 8.
 constexpr int kSmallStackLayers = 16;
+constexpr int kChainWaits = 0x100;
+constexpr int kChainMaxM = 3;
+constexpr int kChainCounters = kSmallStackLayers + 1;
 struct SmallTable {
     LayerDesc d[kSmallStackLayers];
 };
@@ -97,6 +100,12 @@ struct StackParams {
     int32_t worker_cap;      // 0, or: `part` holds slots for this many schedule shares only (a small workspace)
     int32_t ks_cap;          // low-latency launch of a small stack: most K slices per row block (0: as one layer would choose)
     int32_t ll_start[16];    // ... and the first workgroup of each layer (a workgroup finds its layer without reading the table)
+    // Chained small stack (some layer reads what earlier layers of the same launch write): the layers form stages,
+    // a new stage starting at every layer that waits.  Counter chain_off + s of `cnt` counts the finished row blocks
+    // of stage s, counter chain_off + kSmallStackLayers all of them; the last row block of the launch zeroes them.
+    int32_t chain_total;     // row blocks of all layers; 0: nothing is chained and nothing is counted
+    int32_t chain_off;
+    int32_t stage_rb[16];    // row blocks per stage
     LayerDesc single;
 };
 
@@ -190,8 +199,9 @@ hipError_t launch_linear_rb(const LayerDesc &L, float *part, int32_t *cnt, hipSt
 // of the descriptors; false = the stack is too big for it.
 // ks_cap: see StackParams.
 // ll_start: see StackParams (16 entries).
+// all_resident: the device holds every workgroup of that shape at one time (what a chained stack needs).
 bool linear_rb_stack_shape(const LayerDesc *table, int n_layers, size_t part_bytes, bool from_parent, int *blocks,
-                           int *waves, int *ks_cap, int32_t *ll_start);
+                           int *waves, int *ks_cap, int32_t *ll_start, bool *all_resident);
 hipError_t launch_linear_rb_stack(const StackParams &p, const SmallTable &t, int blocks, int waves, bool from_parent,
                                   hipStream_t s);
 // MFMA path (M > kValuMaxM): activation prep kernel + persistent MFMA kernel.

@@ -26,8 +26,9 @@ template <int R, int M> struct TileRegs {
     uint32_t xl[M];  // lane l's pair (x[2l], x[2l+1]) of the group: X_g, and the kXLds path
 };
 
+// weights, scale and zero-offset of tile u
 template <int R, int M>
-__device__ __forceinline__ void load_tile(TileRegs<R, M> &t, const LayerDesc &L, int u, int g, int lane) {
+__device__ __forceinline__ void load_tile_w(TileRegs<R, M> &t, const LayerDesc &L, int u, int lane) {
     // Weights, scales and zeros are read exactly once per call: non-temporal loads (streaming hint) keep them from
     // displacing anything in the caches and, measured with a plain read kernel on this chip, stream at 7.0 TB/s where
     // ordinary loads reach 6.2.  The activations below are shared by every wave and stay ordinary loads.
@@ -42,9 +43,18 @@ __device__ __forceinline__ void load_tile(TileRegs<R, M> &t, const LayerDesc &L,
     // folds every tile onto them (cache hits, no HBM traffic).  The load is neither branched around nor selected -- either
     // costs the ALU-bound 2-bit tiles and the mixed Llama-3-70B stack 3-9 % -- and an asymmetric layer pays one scalar AND.
     t.z = __builtin_nontemporal_load(gl(L.zt) + (size_t)(u & L.zmask) * 64 + lane);
+}
+// the lane's activation pair of group g, per batch row
+template <int R, int M>
+__device__ __forceinline__ void load_tile_x(TileRegs<R, M> &t, const LayerDesc &L, int g, int lane) {
 #pragma unroll
     for (int m = 0; m < M; ++m)
         t.xl[m] = gl(reinterpret_cast<const uint32_t *>(L.x + (size_t)m * L.K + (size_t)g * kGroup))[lane];
+}
+template <int R, int M>
+__device__ __forceinline__ void load_tile(TileRegs<R, M> &t, const LayerDesc &L, int u, int g, int lane) {
+    load_tile_w<R, M>(t, L, u, lane);
+    load_tile_x<R, M>(t, L, g, lane);
 }
 
 // Eq. 1 on the two 8-bit codes of a masked pair (one per 16-bit half), in 8-bit units:
@@ -233,9 +243,49 @@ template <int M, int XP, bool SL = false> __global__ __launch_bounds__(256) void
 // KS <= 8 contributors instead of up to G).
 // Body shared by the single-layer kernel and the small-stack kernel below.  blk = index of this workgroup among the
 // layer's RB * KS workgroups, slot0 = index of the layer's first partial-sum slot, cnt = the layer's row-block counters.
+// A layer of a chained small stack that reads what earlier layers of the same launch write (LayerDesc::chain): its
+// workgroups fetch their first weights, wait until the finished-row-block counters of all earlier stages have reached
+// their totals, and only then read activations.  Nobody can wait for ever: the launch shape keeps every workgroup of
+// the stack resident at one time (checked when the stack is planned), so the workgroups waited for are running, and
+// they wait for strictly earlier layers only; the number of polls is bounded on top of that (a wait that runs out goes
+// on with whatever x holds).  A finished row block is announced after its y has been written back device-wide
+// (release at agent scope), and a waiter drops what its caches hold of other compute dies' memory (acquire at agent
+// scope) before its first activation load.
+constexpr int kChainPolls = 1 << 20;
+// What a workgroup of a chained small stack needs besides its descriptor (all of it uniform over the launch and held
+// in scalar registers): the counters, the totals of the stages before the layer's own, and the launch's total.
+struct ChainCtl {
+    int32_t *counters;         // kChainCounters of them; nullptr: the stack is not chained
+    const int32_t *stage_rb;   // row blocks per stage (kernel arguments)
+    int32_t total;
+};
+__device__ __forceinline__ void chain_wait(const ChainCtl &c, int stage) {
+    for (int s = 0; s < stage; ++s) {
+        const int32_t MQ_GLOBAL *ctr = gl(c.counters + s);
+        const int want = c.stage_rb[s];
+        for (int polls = 0; polls < kChainPolls; ++polls) {
+            if (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= want) break;
+            __builtin_amdgcn_s_sleep(2);
+        }
+    }
+}
+// by the wave that has just stored a row block of y
+__device__ __forceinline__ void chain_announce(const ChainCtl &c, int stage, int lane) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    if (lane != 0) return;
+    int32_t MQ_GLOBAL *ctr = gl(c.counters);
+    __hip_atomic_fetch_add(ctr + stage, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // every row block of the launch is counted once more in the last counter; whoever completes it is the last to
+    // touch the counters (each waiter has contributed to a row block counted here, after its wait) and zeroes them
+    const int old = __hip_atomic_fetch_add(ctr + kSmallStackLayers, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old + 1 == c.total)
+        for (int i = 0; i < kChainCounters; ++i) __hip_atomic_store(ctr + i, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 template <int R, int M, int XP, bool SL>
 __device__ __forceinline__ void linear_rb_body(const LayerDesc &L, const int KS, const int blk, const int slot0,
-                                               float *part, int32_t *cnt, float (*red)[M][64], uint32_t *xlds_all) {
+                                               float *part, int32_t *cnt, float (*red)[M][64], uint32_t *xlds_all,
+                                               const ChainCtl chain = ChainCtl{nullptr, nullptr, 0}) {
     uint32_t *xlds = xlds_all + (XP == kXLds ? (threadIdx.x >> 6) * M * 64 : 0);
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6, W = blockDim.x >> 6;
@@ -245,9 +295,16 @@ __device__ __forceinline__ void linear_rb_body(const LayerDesc &L, const int KS,
 #pragma unroll
     for (int m = 0; m < M; ++m) yacc[m] = 0.f;
     int g = g_lo + w;
+    const bool waits = chain.counters && (L.chain & kChainWaits);
+    TileRegs<R, M> cur, nxt;
+    if (g < g_hi) load_tile_w<R, M>(cur, L, rb * L.G + g, lane);
+    if (waits) {  // uniform over the workgroup
+        if (w == 0) chain_wait(chain, L.chain & 0xFF);
+        __syncthreads();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    }
     if (g < g_hi) {
-        TileRegs<R, M> cur, nxt;
-        load_tile<R, M>(cur, L, rb * L.G + g, g, lane);
+        load_tile_x<R, M>(cur, L, g, lane);
         while (true) {
             const int g2 = g + W;
             if (g2 < g_hi) load_tile<R, M>(nxt, L, rb * L.G + g2, g2, lane);
@@ -300,6 +357,7 @@ __device__ __forceinline__ void linear_rb_body(const LayerDesc &L, const int KS,
 #pragma unroll
     for (int m = 0; m < M; ++m)
         if (row < L.N) store_y(L.y, (size_t)m * L.N + row, tot[m], L.flags);
+    if (chain.counters) chain_announce(chain, L.chain & 0xFF, lane);
 }
 
 template <int R, int M, int XP, bool SL = false>
@@ -385,15 +443,16 @@ __global__ __launch_bounds__(1024) void linear_rb_stack_kernel(const StackParams
     const LayerDesc L = t.d[li];
     const int KS = stack_k_slices(L, p.ks_cap);
     int32_t *cnt = p.cnt + L.cnt_off;
+    const ChainCtl chain{p.chain_total ? p.cnt + p.chain_off : nullptr, p.stage_rb, p.chain_total};
     if constexpr (SL) {
-        linear_rb_body<8, M, XP, true>(L, KS, blk, slot0, p.part, cnt, red, xlds_all);
+        linear_rb_body<8, M, XP, true>(L, KS, blk, slot0, p.part, cnt, red, xlds_all, chain);
     } else {
         switch (L.r) {
-            case 2: linear_rb_body<2, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all); break;
-            case 3: linear_rb_body<3, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all); break;
-            case 4: linear_rb_body<4, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all); break;
-            case 6: linear_rb_body<6, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all); break;
-            default: linear_rb_body<8, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all); break;
+            case 2: linear_rb_body<2, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all, chain); break;
+            case 3: linear_rb_body<3, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all, chain); break;
+            case 4: linear_rb_body<4, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all, chain); break;
+            case 6: linear_rb_body<6, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all, chain); break;
+            default: linear_rb_body<8, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all, chain); break;
         }
     }
 }
@@ -426,7 +485,7 @@ static int rb_stack_resident_m(int M, bool from_parent, int waves) {
 // and a launch this short then takes half as long again (three 4096 x 4096 layers: 768 workgroups of 8 waves where 512
 // fit).  Then first the waves per workgroup are halved (a wave takes more tiles), then the K slices.
 bool linear_rb_stack_shape(const LayerDesc *table, int n_layers, size_t part_bytes, bool from_parent, int *blocks,
-                           int *waves, int *ks_cap, int32_t *ll_start) {
+                           int *waves, int *ks_cap, int32_t *ll_start, bool *all_resident) {
     if (n_layers > kSmallStackLayers || table[0].M > kValuMaxM) return false;
     int64_t tiles = 0, slots = 0;
     for (int i = 0; i < n_layers; ++i) {
@@ -446,8 +505,10 @@ bool linear_rb_stack_shape(const LayerDesc *table, int n_layers, size_t part_byt
     };
     int nb = 0, W = 4, cap = 0;
     shape(0, &nb, &W);
+    *all_resident = false;
     for (;;) {
         const int fit = rb_stack_resident_m(table[0].M, from_parent, W);
+        if (fit > 0 && nb <= fit) *all_resident = true;
         if (fit <= 0 || nb <= fit) break;
         if (W > 4) { W /= 2; continue; }
         const int next = cap == 0 ? 4 : cap / 2;

@@ -285,8 +285,24 @@ def test_workspace_and_stack_validation():
     lay[0].from_parent = lay[1].from_parent = 2
     assert L.mq_stack_plan(p, 2, 1, FAKE, need, hp, None) == _st("MQ_ERR_UNSUPPORTED")
     lay[0].from_parent = lay[1].from_parent = 0
-    lay[1].flags = 4                              # only MQ_X_BF16 | MQ_Y_BF16 are flags
+    lay[1].flags = 8                              # only MQ_X_BF16 | MQ_Y_BF16 | MQ_X_AFTER_EARLIER are flags
     assert L.mq_stack_plan(p, 2, 1, FAKE, need, hp, None) == _st("MQ_ERR_UNSUPPORTED")
+    # a layer that waits for earlier layers: not the first one, not on bf16 activations, only in a stack that is
+    # launched for latency (M <= 4, at most 16 layers), never on its own
+    lay[1].flags = 0
+    lay[0].flags = mq.MQ_X_AFTER_EARLIER
+    assert L.mq_stack_plan(p, 2, 1, FAKE, need, hp, None) == _st("MQ_ERR_UNSUPPORTED")
+    lay[0].flags = 0
+    lay[1].flags = mq.MQ_X_AFTER_EARLIER | mq.MQ_X_BF16
+    assert L.mq_stack_plan(p, 2, 1, FAKE, need, hp, None) == _st("MQ_ERR_UNSUPPORTED")
+    lay[1].flags = mq.MQ_X_AFTER_EARLIER
+    assert L.mq_stack_plan(p, 2, 8, FAKE, 1 << 40, hp, None) == _st("MQ_ERR_UNSUPPORTED")
+    assert L.mq_stack_plan(p, 2, 4, FAKE, 1 << 40, hp, None) == _st("MQ_ERR_UNSUPPORTED")   # chained: M <= 3
+    many = (mq.MqLayer * 17)()
+    for i in range(17):
+        many[i] = mq.MqLayer(FAKE, FAKE, FAKE, FAKE, FAKE, 64, 128, 4, 128, 0, mq.MQ_X_AFTER_EARLIER if i == 5 else 0)
+    assert L.mq_stack_plan(ctypes.cast(many, ctypes.c_void_p), 17, 1, FAKE, 1 << 40, hp, None) == _st("MQ_ERR_UNSUPPORTED")
+    assert L.mq_stack_plan(p, 2, 1, FAKE, need - 1, hp, None) == _st("MQ_ERR_BUF_TOO_SMALL")   # a valid chain: judged on
     lay[1].flags = mq.MQ_X_BF16 | mq.MQ_Y_BF16
     assert L.mq_stack_plan(p, 2, 1, FAKE, need - 1, hp, None) == _st("MQ_ERR_BUF_TOO_SMALL")   # valid flags: judged on
     assert L.mq_linear_bf16(None, 1, FAKE, FAKE, FAKE, 64, 128, 4, 128, FAKE, FAKE, 1 << 30, None) == _st("MQ_ERR_NULL")
