@@ -355,6 +355,11 @@ def main() -> int:
         extras["decode_7b"] = {"workload": f"Llama-2-7B decoder blocks x32, M=1, per-layer r by seed (mean {dmean:.3f} bits), "
                                            "every block its own weights, HIP-graph replay", "table": res,
                                "frac": round(res["fused_qkv_and_gate_up"]["GBps"] / HBM_PEAK_GBPS, 4)}
+        del res
+        torch.cuda.empty_cache()
+        extras["chain_7b"] = {"workload": "three dependent 4096x4096 links (r = 3, 4, 8), M=1, 32 chains with their own weights, "
+                                          "HIP-graph replay: one chained launch (MQ_X_AFTER_EARLIER) against one launch per link",
+                              "table": measure_chain(mq, synth, torch, np, dev, 1, 32, max(5, args.steps // 2))}
 
     out = {
         "metric": "batch-1 sliced GEMV effective HBM GB/s (algorithmic bytes / time) over r in {2,3,4,6,8}",
@@ -715,6 +720,68 @@ def measure_decode_fusions(mq, synth, torch, np, dev, M, n_blocks, steps):
                       "launches_per_block": 7 if label.startswith("one") else 4}
         del g
     return res, nbytes, mean
+
+
+def measure_chain(mq, synth, torch, np, dev, M, n_chains, steps, widths=(3, 4, 8)):
+    """A chained small stack: three dependent 4096 x 4096 links (x -> y0 -> y1 -> y2) as ONE launch whose later layers
+    wait inside the launch for the earlier ones (MQ_X_AFTER_EARLIER), against the same links as three launches in stream
+    order.  Every chain has its own weights (cold), replayed from a HIP graph."""
+    proto = []
+    for i, r in enumerate(widths):
+        L = synth.make_layer_device(4096, 4096, M, seed=6100 + i, device=dev, want_x=False)
+        proto.append(mq.prepare_layer(L["parent"], L["scales"], L["zeros"], r))
+    chains, nbytes = [], 0.0
+    for c in range(n_chains):
+        x = torch.randn((M, 4096), device=dev, dtype=torch.float32).to(torch.float16)
+        lays = []
+        for i, r in enumerate(widths):
+            p = proto[i]
+            y = torch.empty((M, 4096), dtype=torch.float16, device=dev)
+            lays.append(dict(packed_W=p["packed_W"].clone(), scales_t=p["scales_t"].clone(), zeros_t=p["zeros_t"].clone(),
+                             N=4096, K=4096, r=r, x=x, y=y, flags=mq.MQ_X_AFTER_EARLIER if i else 0))
+            x = y
+            nbytes += algo_bytes(4096, 4096, r, M)
+        chains.append((lays, mq.mq_stack_plan(lays, M, device=dev)))
+    ws = torch.empty(max(mq.mq_workspace_bytes(M, 4096, 4096, r) for r in widths), dtype=torch.uint8, device=dev)
+    mq.mq_workspace_init(ws)
+
+    def chained():
+        for _, plan in chains:
+            mq.mq_linear_stack(plan)
+
+    def per_link():
+        for lays, _ in chains:
+            for L in lays:
+                mq.mq_linear(L["x"], L["packed_W"], L["scales_t"], L["zeros_t"], L["N"], L["K"], L["r"], 128, ws, y=L["y"])
+
+    res = {}
+    for label, fn in (("one_launch_per_link", per_link), ("chained_one_launch", chained)):
+        fn()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        t = e0.elapsed_time(e1) * 1e-3 / steps
+        res[label] = {"us_per_chain": round(t / n_chains * 1e6, 2), "GBps": round(nbytes / t / 1e9, 1),
+                      "launches_per_chain": len(widths) if label.startswith("one") else 1}
+        del g
+    # both ways compute the same chain (the launch shapes differ, so the sums are ordered differently: equal to rounding)
+    lays = chains[0][0]
+    chained()
+    torch.cuda.synchronize()
+    want = [L["y"].float().clone() for L in lays]
+    per_link()
+    torch.cuda.synchronize()
+    res["max_abs_diff_between_the_two"] = max(float((L["y"].float() - w).abs().max()) for L, w in zip(lays, want))
+    return res
 
 
 def bench_decode_fusions(args, mq, synth, torch, np, dev):

@@ -584,7 +584,7 @@ mq_status mq_stack_plan(const mq_layer *layers, int n_layers, int64_t M, void *p
         int nb = 0, nw = 0, kc = 0;
         bool all_resident = false;
         if (!use_mfma(Mp) && linear_rb_stack_shape(table.data(), n_layers, partial_bytes(Mp), layers[0].from_parent != 0,
-                                                   &nb, &nw, &kc, h.ll_start, &all_resident)) {
+                                                   chained, &nb, &nw, &kc, h.ll_start, &all_resident)) {
             h.ll_blocks = nb;
             h.ll_waves = nw;
             h.ll_ks_cap = kc;

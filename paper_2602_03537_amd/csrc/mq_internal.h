@@ -200,8 +200,8 @@ hipError_t launch_linear_rb(const LayerDesc &L, float *part, int32_t *cnt, hipSt
 // ks_cap: see StackParams.
 // ll_start: see StackParams (16 entries).
 // all_resident: the device holds every workgroup of that shape at one time (what a chained stack needs).
-bool linear_rb_stack_shape(const LayerDesc *table, int n_layers, size_t part_bytes, bool from_parent, int *blocks,
-                           int *waves, int *ks_cap, int32_t *ll_start, bool *all_resident);
+bool linear_rb_stack_shape(const LayerDesc *table, int n_layers, size_t part_bytes, bool from_parent, bool chained,
+                           int *blocks, int *waves, int *ks_cap, int32_t *ll_start, bool *all_resident);
 hipError_t launch_linear_rb_stack(const StackParams &p, const SmallTable &t, int blocks, int waves, bool from_parent,
                                   hipStream_t s);
 // MFMA path (M > kValuMaxM): activation prep kernel + persistent MFMA kernel.

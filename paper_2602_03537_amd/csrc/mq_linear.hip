@@ -44,12 +44,15 @@ __device__ __forceinline__ void load_tile_w(TileRegs<R, M> &t, const LayerDesc &
     // costs the ALU-bound 2-bit tiles and the mixed Llama-3-70B stack 3-9 % -- and an asymmetric layer pays one scalar AND.
     t.z = __builtin_nontemporal_load(gl(L.zt) + (size_t)(u & L.zmask) * 64 + lane);
 }
-// the lane's activation pair of group g, per batch row
+// the lane's activation pair of group g, per batch row.  fresh: x was written by other workgroups of this very launch
+// (a chained stack): the loads go to where the whole device sees memory, past whatever this compute die's caches hold.
 template <int R, int M>
-__device__ __forceinline__ void load_tile_x(TileRegs<R, M> &t, const LayerDesc &L, int g, int lane) {
+__device__ __forceinline__ void load_tile_x(TileRegs<R, M> &t, const LayerDesc &L, int g, int lane, bool fresh = false) {
 #pragma unroll
-    for (int m = 0; m < M; ++m)
-        t.xl[m] = gl(reinterpret_cast<const uint32_t *>(L.x + (size_t)m * L.K + (size_t)g * kGroup))[lane];
+    for (int m = 0; m < M; ++m) {
+        const uint32_t MQ_GLOBAL *src = gl(reinterpret_cast<const uint32_t *>(L.x + (size_t)m * L.K + (size_t)g * kGroup)) + lane;
+        t.xl[m] = fresh ? __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *src;
+    }
 }
 template <int R, int M>
 __device__ __forceinline__ void load_tile(TileRegs<R, M> &t, const LayerDesc &L, int u, int g, int lane) {
@@ -248,9 +251,10 @@ template <int M, int XP, bool SL = false> __global__ __launch_bounds__(256) void
 // their totals, and only then read activations.  Nobody can wait for ever: the launch shape keeps every workgroup of
 // the stack resident at one time (checked when the stack is planned), so the workgroups waited for are running, and
 // they wait for strictly earlier layers only; the number of polls is bounded on top of that (a wait that runs out goes
-// on with whatever x holds).  A finished row block is announced after its y has been written back device-wide
-// (release at agent scope), and a waiter drops what its caches hold of other compute dies' memory (acquire at agent
-// scope) before its first activation load.
+// on with whatever x holds).  Visibility follows the split-K hand-over's protocol: in a chained stack every y is stored
+// through to device-wide memory and acknowledged before its row block is counted, and a layer that has waited reads
+// its activations with device-scope loads -- no cache-wide write-back or invalidation anywhere (one per row block and
+// one per waiting wave made the chained launch 2.6 times slower than the launches it replaces).
 constexpr int kChainPolls = 1 << 20;
 // What a workgroup of a chained small stack needs besides its descriptor (all of it uniform over the launch and held
 // in scalar registers): the counters, the totals of the stages before the layer's own, and the launch's total.
@@ -271,7 +275,9 @@ __device__ __forceinline__ void chain_wait(const ChainCtl &c, int stage) {
 }
 // by the wave that has just stored a row block of y
 __device__ __forceinline__ void chain_announce(const ChainCtl &c, int stage, int lane) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    // the write-through stores of y must have been acknowledged before the counters move
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if (lane != 0) return;
     int32_t MQ_GLOBAL *ctr = gl(c.counters);
     __hip_atomic_fetch_add(ctr + stage, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -282,7 +288,8 @@ __device__ __forceinline__ void chain_announce(const ChainCtl &c, int stage, int
         for (int i = 0; i < kChainCounters; ++i) __hip_atomic_store(ctr + i, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-template <int R, int M, int XP, bool SL>
+// CH: the launch is a chained small stack (`chain` is live); the plain variants carry none of its code
+template <int R, int M, int XP, bool SL, bool CH = false>
 __device__ __forceinline__ void linear_rb_body(const LayerDesc &L, const int KS, const int blk, const int slot0,
                                                float *part, int32_t *cnt, float (*red)[M][64], uint32_t *xlds_all,
                                                const ChainCtl chain = ChainCtl{nullptr, nullptr, 0}) {
@@ -295,19 +302,30 @@ __device__ __forceinline__ void linear_rb_body(const LayerDesc &L, const int KS,
 #pragma unroll
     for (int m = 0; m < M; ++m) yacc[m] = 0.f;
     int g = g_lo + w;
-    const bool waits = chain.counters && (L.chain & kChainWaits);
+    const bool waits = CH && (L.chain & kChainWaits);
     TileRegs<R, M> cur, nxt;
     if (g < g_hi) load_tile_w<R, M>(cur, L, rb * L.G + g, lane);
-    if (waits) {  // uniform over the workgroup
-        if (w == 0) chain_wait(chain, L.chain & 0xFF);
-        __syncthreads();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    bool have_nxt = false;  // a waiting layer has the weights of its second tile on their way, too, before it waits
+    if constexpr (CH) {
+        if (waits) {  // uniform over the workgroup
+            if (g + W < g_hi) {
+                load_tile_w<R, M>(nxt, L, rb * L.G + g + W, lane);
+                have_nxt = true;
+            }
+            if (w == 0) chain_wait(chain, L.chain & 0xFF);
+            __syncthreads();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        }
     }
     if (g < g_hi) {
-        load_tile_x<R, M>(cur, L, g, lane);
+        load_tile_x<R, M>(cur, L, g, lane, waits);
         while (true) {
             const int g2 = g + W;
-            if (g2 < g_hi) load_tile<R, M>(nxt, L, rb * L.G + g2, g2, lane);
+            if (g2 < g_hi) {
+                if (!have_nxt) load_tile_w<R, M>(nxt, L, rb * L.G + g2, lane);
+                have_nxt = false;
+                load_tile_x<R, M>(nxt, L, g2, lane, waits);
+            }
             tile_math<R, M, XP, SL>(cur, L, g, lane, xlds, yacc);
             if (g2 >= g_hi) break;
             cur = nxt;
@@ -354,10 +372,18 @@ __device__ __forceinline__ void linear_rb_body(const LayerDesc &L, const int KS,
         }
         if (lane == 0) __hip_atomic_store(gl(cnt + rb), 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    if constexpr (CH) {
+#pragma unroll
+        for (int m = 0; m < M; ++m)
+            if (row < L.N)
+                __hip_atomic_store(gl(reinterpret_cast<uint16_t *>(L.y)) + (size_t)m * L.N + row, y_bits(tot[m], L.flags),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        chain_announce(chain, L.chain & 0xFF, lane);
+        return;
+    }
 #pragma unroll
     for (int m = 0; m < M; ++m)
         if (row < L.N) store_y(L.y, (size_t)m * L.N + row, tot[m], L.flags);
-    if (chain.counters) chain_announce(chain, L.chain & 0xFF, lane);
 }
 
 template <int R, int M, int XP, bool SL = false>
@@ -428,7 +454,7 @@ hipError_t launch_linear_rb(const LayerDesc &L, float *part, int32_t *cnt, hipSt
 
 // The same shape for a SMALL stack (the linears of a decoder block that share their input, say): the workgroups of all
 // layers in one launch; a workgroup finds its layer and its descriptor in the kernel arguments (at most 16 layers).
-template <int M, int XP, bool SL>
+template <int M, int XP, bool SL, bool CH = false>
 __global__ __launch_bounds__(1024) void linear_rb_stack_kernel(const StackParams p, const SmallTable t) {
     __shared__ float red[16][M][64];
     __shared__ __attribute__((aligned(16))) uint32_t xlds_all[XP == kXLds ? 16 * M * 64 : 4];
@@ -443,39 +469,46 @@ __global__ __launch_bounds__(1024) void linear_rb_stack_kernel(const StackParams
     const LayerDesc L = t.d[li];
     const int KS = stack_k_slices(L, p.ks_cap);
     int32_t *cnt = p.cnt + L.cnt_off;
-    const ChainCtl chain{p.chain_total ? p.cnt + p.chain_off : nullptr, p.stage_rb, p.chain_total};
+    const ChainCtl chain{CH ? p.cnt + p.chain_off : nullptr, p.stage_rb, p.chain_total};
     if constexpr (SL) {
-        linear_rb_body<8, M, XP, true>(L, KS, blk, slot0, p.part, cnt, red, xlds_all, chain);
+        linear_rb_body<8, M, XP, true, CH>(L, KS, blk, slot0, p.part, cnt, red, xlds_all, chain);
     } else {
         switch (L.r) {
-            case 2: linear_rb_body<2, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all, chain); break;
-            case 3: linear_rb_body<3, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all, chain); break;
-            case 4: linear_rb_body<4, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all, chain); break;
-            case 6: linear_rb_body<6, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all, chain); break;
-            default: linear_rb_body<8, M, XP, false>(L, KS, blk, slot0, p.part, cnt, red, xlds_all, chain); break;
+            case 2: linear_rb_body<2, M, XP, false, CH>(L, KS, blk, slot0, p.part, cnt, red, xlds_all, chain); break;
+            case 3: linear_rb_body<3, M, XP, false, CH>(L, KS, blk, slot0, p.part, cnt, red, xlds_all, chain); break;
+            case 4: linear_rb_body<4, M, XP, false, CH>(L, KS, blk, slot0, p.part, cnt, red, xlds_all, chain); break;
+            case 6: linear_rb_body<6, M, XP, false, CH>(L, KS, blk, slot0, p.part, cnt, red, xlds_all, chain); break;
+            default: linear_rb_body<8, M, XP, false, CH>(L, KS, blk, slot0, p.part, cnt, red, xlds_all, chain); break;
         }
     }
 }
 
 // workgroups of `waves` waves of the small-stack kernel that the device holds at one time
-template <int M, bool SL> static int rb_stack_resident(int waves) {
+template <int M, bool SL, bool CH = false> static int rb_stack_resident(int waves) {
     static int cached[3] = {0, 0, 0};
     const int slot = waves == 16 ? 0 : waves == 8 ? 1 : 2;
     if (cached[slot]) return cached[slot];
     int dev = 0, cus = 0, b = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&b, linear_rb_stack_kernel<M, kXLds, SL>, 64 * waves, 0) != hipSuccess)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&b, linear_rb_stack_kernel<M, kXLds, SL, CH>, 64 * waves, 0) != hipSuccess)
         return 0;
     cached[slot] = cus * (b < 1 ? 1 : b);
     return cached[slot];
 }
-static int rb_stack_resident_m(int M, bool from_parent, int waves) {
+template <int M> static int rb_stack_resident_v(bool from_parent, bool chained, int waves) {
+    if constexpr (M <= kChainMaxM) {
+        if (chained) return from_parent ? rb_stack_resident<M, true, true>(waves) : rb_stack_resident<M, false, true>(waves);
+    }
+    return from_parent ? rb_stack_resident<M, true>(waves) : rb_stack_resident<M, false>(waves);
+}
+// chained: the variant of the kernel whose layers may wait for each other (it is the one whose residency matters then)
+static int rb_stack_resident_m(int M, bool from_parent, bool chained, int waves) {
     switch (M) {
-        case 1: return from_parent ? rb_stack_resident<1, true>(waves) : rb_stack_resident<1, false>(waves);
-        case 2: return from_parent ? rb_stack_resident<2, true>(waves) : rb_stack_resident<2, false>(waves);
-        case 3: return from_parent ? rb_stack_resident<3, true>(waves) : rb_stack_resident<3, false>(waves);
-        default: return from_parent ? rb_stack_resident<4, true>(waves) : rb_stack_resident<4, false>(waves);
+        case 1: return rb_stack_resident_v<1>(from_parent, chained, waves);
+        case 2: return rb_stack_resident_v<2>(from_parent, chained, waves);
+        case 3: return rb_stack_resident_v<3>(from_parent, chained, waves);
+        default: return rb_stack_resident_v<4>(from_parent, false, waves);
     }
 }
 
@@ -484,8 +517,8 @@ static int rb_stack_resident_m(int M, bool from_parent, int waves) {
 // device cannot hold all those workgroups at one time: the ones left over would start when the first have finished,
 // and a launch this short then takes half as long again (three 4096 x 4096 layers: 768 workgroups of 8 waves where 512
 // fit).  Then first the waves per workgroup are halved (a wave takes more tiles), then the K slices.
-bool linear_rb_stack_shape(const LayerDesc *table, int n_layers, size_t part_bytes, bool from_parent, int *blocks,
-                           int *waves, int *ks_cap, int32_t *ll_start, bool *all_resident) {
+bool linear_rb_stack_shape(const LayerDesc *table, int n_layers, size_t part_bytes, bool from_parent, bool chained,
+                           int *blocks, int *waves, int *ks_cap, int32_t *ll_start, bool *all_resident) {
     if (n_layers > kSmallStackLayers || table[0].M > kValuMaxM) return false;
     int64_t tiles = 0, slots = 0;
     for (int i = 0; i < n_layers; ++i) {
@@ -503,11 +536,13 @@ bool linear_rb_stack_shape(const LayerDesc *table, int n_layers, size_t part_byt
             if (w > *W) *W = w;
         }
     };
-    int nb = 0, W = 4, cap = 0;
-    shape(0, &nb, &W);
+    // A chained stack is a chain of dependent steps: what counts is the length of one step, and a row block that is
+    // not cut along K needs no hand-over through device memory (three round trips) before its y can be announced.
+    int nb = 0, W = 4, cap = chained ? 1 : 0;
+    shape(cap, &nb, &W);
     *all_resident = false;
     for (;;) {
-        const int fit = rb_stack_resident_m(table[0].M, from_parent, W);
+        const int fit = rb_stack_resident_m(table[0].M, from_parent, chained, W);
         if (fit > 0 && nb <= fit) *all_resident = true;
         if (fit <= 0 || nb <= fit) break;
         if (W > 4) { W /= 2; continue; }
@@ -529,6 +564,14 @@ bool linear_rb_stack_shape(const LayerDesc *table, int n_layers, size_t part_byt
 
 template <int M> static hipError_t launch_linear_rb_stack_m(const StackParams &p, const SmallTable &t, int blocks, int waves,
                                                             bool from_parent, hipStream_t s) {
+    if constexpr (M <= kChainMaxM) {
+        if (p.chain_total) {
+            if (from_parent)
+                return launch((linear_rb_stack_kernel<M, kXLds, true, true>), dim3((unsigned)blocks), dim3(64 * waves), 0, s, p, t);
+            return launch((linear_rb_stack_kernel<M, kXLds, false, true>), dim3((unsigned)blocks), dim3(64 * waves), 0, s, p, t);
+        }
+    }
+    if (p.chain_total) return hipErrorInvalidValue;  // refused when the stack was planned
     if (from_parent)
         return launch((linear_rb_stack_kernel<M, kXLds, true>), dim3((unsigned)blocks), dim3(64 * waves), 0, s, p, t);
     return launch((linear_rb_stack_kernel<M, kXLds, false>), dim3((unsigned)blocks), dim3(64 * waves), 0, s, p, t);
