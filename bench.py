@@ -345,6 +345,20 @@ def main() -> int:
                               "algorithmic_GB": round(m["bytes"] / 1e9, 3)}
         del m
         torch.cuda.empty_cache()
+        # a cut of configs[4]: the first 16 blocks of the Llama-3-70B-shaped stack (widths drawn for those blocks), at the
+        # batch sizes of the three kernel families (vector ALUs, narrow and wide matrix-core kernels)
+        cut70 = {}
+        for Mb in (1, 8, 64):
+            m = measure_mixed_stack(mq, synth, torch, np, dev, True, 16, Mb, max(4, args.steps // 4), 2)
+            gb = m["bytes"] / float(np.median(m["us"])) / 1e3
+            cut70["M%d" % Mb] = {"us_median": round(float(np.median(m["us"])), 1), "GBps": round(gb, 1),
+                                 "frac": round(gb / HBM_PEAK_GBPS, 4), "kernel": m["kernel"],
+                                 "mean_bits": round(m["mean_bits"], 3), "algorithmic_GB": round(m["bytes"] / 1e9, 3),
+                                 "TFLOPs": round(2.0 * Mb * m["weights"] / float(np.median(m["us"])) / 1e6, 1)}
+            del m
+            torch.cuda.empty_cache()
+        extras["mixed_70b_cut"] = {"workload": "Llama-3-70B-shaped stack, first 16 blocks (112 linears, 8-bit parent resident), per-layer "
+                                               "r by seed, one persistent launch, M in {1, 8, 64}", "table": cut70}
         cut = measure_mlp(mq, synth, torch, dev, (("up", 28672, 8192),), (4,), (1, 4, 16, 64, 256), max(2, args.steps // 4))
         for v in cut.values():
             v.pop("bytes")
@@ -394,8 +408,9 @@ def measure_mixed_stack(mq, synth, torch, np, dev, big, n_blocks, M, steps, warm
     target = 4.0 if big else 3.5
     shapes = synth.stack_shapes(block, n_blocks)
     widths, mean = synth.draw_bitwidths([N * K for (_, _, N, K) in shapes], target, seed=0)
-    layers, nbytes, keep = [], 0.0, []
+    layers, nbytes, keep, weights = [], 0.0, [], 0
     for i, ((_, _, N, K), r) in enumerate(zip(shapes, widths)):
+        weights += N * K
         L = synth.make_layer_device(N, K, M, seed=7000 + i, device=dev)
         lay = mq.prepare_layer(L["parent"], L["scales"], L["zeros"], int(r))
         lay.update(x=L["x"], y=torch.empty((M, N), dtype=torch.float16, device=dev))
@@ -419,7 +434,7 @@ def measure_mixed_stack(mq, synth, torch, np, dev, big, n_blocks, M, steps, warm
     kernel = ("mq::stack_kernel<%d, 1, false>" % M if M <= 3 else "mq::gemm_stack_kernel" if M <= 16
               else "mq::wide_stack_kernel")
     return {"ms_wall": ms, "us": us, "bytes": nbytes, "mean_bits": mean, "n_linears": len(layers), "n_blocks": n_blocks,
-            "kernel": kernel}
+            "kernel": kernel, "weights": weights}
 
 
 def bench_mixed_stack(args, mq, synth, torch, np, dev):

@@ -48,8 +48,8 @@ inline int wide_passes(int64_t M) { return (wide_chunks(M) + kWideMaxChunks - 1)
 // chunks per pass (the kernel variant, 1..4); the chunk count is padded to passes * chunks per pass
 inline int wide_chunks_per_pass(int64_t M) { return (wide_chunks(M) + wide_passes(M) - 1) / wide_passes(M); }
 inline int wide_chunks_padded(int64_t M) { return wide_passes(M) * wide_chunks_per_pass(M); }
-// workgroups a wide launch may use (sizes the partial-sum slots): one per compute unit
-inline int wide_max_groups(int) { return 256; }
+// workgroups a wide launch may use (sizes the partial-sum slots): one per compute unit, two up to two chunks per pass
+inline int wide_max_groups(int C) { return C <= 2 ? 512 : 256; }
 
 // One layer as the persistent kernels see it.
 struct LayerDesc {

@@ -350,47 +350,65 @@ __device__ __forceinline__ void finish_row_block_blocked(const LayerDesc &L, con
 // LDS reads and from operands finished a tile earlier, the result is read at the end of a row block only.
 // (No wait states needed here: the A operand comes from LDS behind a counter wait, the B operand was
 // formed by vector instructions at least one slot earlier.)
-__device__ __forceinline__ void mfma_acc(float16_t &acc, const u32x4 &a, const u32x4 &b) {
-    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+// AG = false (the variants that share a compute unit between two workgroups): the accumulators are pinned to ordinary
+// vector registers instead -- a kernel that names accumulation registers anywhere is given only half of a wave's
+// registers as vector registers, and with 256 in all that half does not hold the working set.
+template <bool AG> __device__ __forceinline__ void mfma_acc(float16_t &acc, const u32x4 &a, const u32x4 &b) {
+    if constexpr (AG)
+        asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+    else
+        asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
 }
 // acc = 0, also from the matrix core (0 * 0 + 0), so that the accumulators are never defined by a vector instruction
-__device__ __forceinline__ void mfma_zero(float16_t &acc) {
+template <bool AG> __device__ __forceinline__ void mfma_zero(float16_t &acc) {
     const u32x4 z = {0u, 0u, 0u, 0u};
     // the wait states are for the vector writes that have just made z: inside inline assembly the
     // compiler does not see a matrix instruction and inserts none
-    asm volatile("s_nop 4\n\tv_mfma_f32_32x32x16_f16 %0, %1, %1, 0" : "=a"(acc) : "v"(z));
+    if constexpr (AG)
+        asm volatile("s_nop 4\n\tv_mfma_f32_32x32x16_f16 %0, %1, %1, 0" : "=a"(acc) : "v"(z));
+    else
+        asm volatile("s_nop 4\n\tv_mfma_f32_32x32x16_f16 %0, %1, %1, 0" : "=&v"(acc) : "v"(z));
 }
 // One accumulator block out of the accumulation registers, at this point of the program and not earlier
 // (the compiler would otherwise fetch all C * 64 accumulators into vector registers ahead of the hand-over).
-__device__ __forceinline__ float16_t read_acc(const float16_t &acc) {
+template <bool AG> __device__ __forceinline__ float16_t read_acc(const float16_t &acc) {
     float16_t r;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         float x;
-        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(acc[v]) : "memory");
+        if constexpr (AG)
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(acc[v]) : "memory");
+        else
+            asm volatile("v_mov_b32 %0, %1" : "=v"(x) : "v"(acc[v]) : "memory");
         r[v] = x;
     }
     return r;
 }
-constexpr int kWideLdsBytes = 160 * 1024;
+// LDS a workgroup may take.  Up to two chunks per pass the tile body is bound by the vector work of unpacking, which one
+// wave per SIMD issues at about one instruction in five cycles: two workgroups share a compute unit there (two waves per
+// SIMD, half the LDS each; the accumulators are 64 registers at most, so a wave fits 256 registers).
+// (TWO = that variant of the kernel; it exists up to kWideTwoPerCuMaxC chunks and runs stacks.)
+constexpr int kWideTwoPerCuMaxC = 2;
+constexpr int wide_lds_budget(bool TWO) { return (TWO ? 80 : 160) * 1024; }
 constexpr int wide_slot_bytes(int R) { return R * 1024 + 256; }  // lane dwords of a tile + its 64 scales + 64 zeros
 // LDS plan of a workgroup: NST activation stages (one being read, the others landing) and per wave a
 // ring of NBR weight tiles.  The activations of a group are re-read for every row block, long after the
 // weight stream has pushed them out of the caches, so they need about as much lead as the weights.
 struct WidePlan { int nst, nbr; };
 constexpr int wide_plan_bytes(int R, int C, WidePlan q) { return q.nst * C * kWideBlockBytes + 4 * q.nbr * wide_slot_bytes(R); }
-constexpr WidePlan wide_plan(int R, int C) {
-    for (WidePlan q : {WidePlan{4, 3}, WidePlan{3, 3}, WidePlan{4, 2}, WidePlan{3, 2}, WidePlan{2, 2}})
-        if (wide_plan_bytes(R, C, q) <= kWideLdsBytes) return q;
-    return {2, 2};
+constexpr WidePlan wide_plan(int R, int C, bool TWO) {
+    for (WidePlan q : {WidePlan{4, 3}, WidePlan{3, 3}, WidePlan{4, 2}, WidePlan{3, 2}, WidePlan{2, 2}, WidePlan{2, 1}})
+        if (wide_plan_bytes(R, C, q) <= wide_lds_budget(TWO)) return q;
+    return {2, 1};
 }
-constexpr int wide_lds_bytes(int R, int C) { return wide_plan_bytes(R, C, wide_plan(R, C)); }
-constexpr int wide_lds_bytes_max(int C) {
+constexpr int wide_lds_bytes(int R, int C, bool TWO) { return wide_plan_bytes(R, C, wide_plan(R, C, TWO)); }
+constexpr int wide_lds_bytes_max(int C, bool TWO) {
     int m = 0;
-    for (int r : {2, 3, 4, 6, 8}) m = wide_lds_bytes(r, C) > m ? wide_lds_bytes(r, C) : m;
+    for (int r : {2, 3, 4, 6, 8}) m = wide_lds_bytes(r, C, TWO) > m ? wide_lds_bytes(r, C, TWO) : m;
     return m;
 }
-static_assert(wide_lds_bytes_max(4) <= kWideLdsBytes, "LDS plan does not fit");
+static_assert(wide_lds_bytes_max(4, false) <= wide_lds_budget(false) && wide_lds_bytes_max(kWideTwoPerCuMaxC, true) <= wide_lds_budget(true),
+              "LDS plan does not fit");
 
 // Super-tiles [u_begin, u_end) of pass `pass` of one layer (u = srb * G + g), for the whole workgroup.
 // C = chunks of 32 batch columns per pass (the layer's chunk count is padded to passes * C; padding
@@ -402,11 +420,12 @@ static_assert(wide_lds_bytes_max(4) <= kWideLdsBytes, "LDS plan does not fit");
 // the operands of the NEXT spec (the matrix core needs 32 cycles per MFMA, a vector instruction 4),
 // fixed with scheduling barriers.  So only two specs' operands are ever held in registers, and the next
 // tile is pulled out of the LDS ring while the last spec of the current one is multiplied.
-template <int R, int C>
+template <int R, int C, bool TWO>
 __device__ __forceinline__ void run_wide_units(const LayerDesc &L, const StackParams &p, int pass, int u_begin,
                                                int u_end, int worker, int wv, int lane, MQ_LDS uint8_t *lds) {
     using W = Wide<R>;
-    constexpr int NBR = wide_plan(R, C).nbr, NST = wide_plan(R, C).nst;
+    constexpr int NBR = wide_plan(R, C, TWO).nbr, NST = wide_plan(R, C, TWO).nst;
+    constexpr bool AG = !TWO;  // accumulators in the accumulation registers
     constexpr int kStage = C * kWideBlockBytes;
     constexpr int kSlot = wide_slot_bytes(R);
     constexpr int kSpecSlots = 2 * C;       // MFMAs per spec
@@ -427,7 +446,7 @@ __device__ __forceinline__ void run_wide_units(const LayerDesc &L, const StackPa
 #pragma unroll
         for (int c = 0; c < C; ++c)
 #pragma unroll
-            for (int h = 0; h < 2; ++h) mfma_zero(acc[c][h]);
+            for (int h = 0; h < 2; ++h) mfma_zero<AG>(acc[c][h]);
     };
     clear_acc();
 
@@ -530,7 +549,7 @@ __device__ __forceinline__ void run_wide_units(const LayerDesc &L, const StackPa
                 static_for<2>([&](auto h) {
                     constexpr int pos = s * C + c, slot = 2 * c + h;
                     const u32x4 bw = {Wq[SP][4 * h], Wq[SP][4 * h + 1], Wq[SP][4 * h + 2], Wq[SP][4 * h + 3]};
-                    mfma_acc(acc[c][h], aq[pos % kAhead], bw);
+                    mfma_acc<AG>(acc[c][h], aq[pos % kAhead], bw);
                     __builtin_amdgcn_sched_barrier(0);
                     // this slot's share of the next spec's operands (after the last spec: spec 0 of tile u+1)
                     constexpr int j_lo = slot * 8 / kSpecSlots, j_hi = (slot + 1) * 8 / kSpecSlots;
@@ -578,7 +597,7 @@ __device__ __forceinline__ void run_wide_units(const LayerDesc &L, const StackPa
                 asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // the last MFMA's result must have left the matrix pipe
                 finish_row_block_blocked<2 * C>(
                     L, pw, p.cnt + L.cnt_off + pass * rb_real + rb, a, ga, g,
-                    [&](auto b) { return read_acc(acc[b / 2][b % 2]); }, worker, lane,
+                    [&](auto b) { return read_acc<AG>(acc[b / 2][b % 2]); }, worker, lane,
                     [&](auto b, const float(&tot)[16]) {
                         // register v of lane l: batch column 8*(v/4) + 4*(l/32) + v%4 of the chunk, weight row l%32 of the half
                         constexpr int c = b / 2, hrow = b % 2;
@@ -611,7 +630,7 @@ __device__ __forceinline__ void run_wide_units(const LayerDesc &L, const StackPa
     wait_transfers<0>();  // nothing of this run may land in LDS after the next run has started
 }
 
-template <int C> __global__ __launch_bounds__(256, 1) void wide_stack_kernel(const StackParams p) {
+template <int C, bool TWO = false> __global__ __launch_bounds__(256, TWO ? 2 : 1) void wide_stack_kernel(const StackParams p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_generic[];
     MQ_LDS uint8_t *lds = (MQ_LDS uint8_t *)lds_generic;
     const int lane = threadIdx.x & 63;
@@ -624,51 +643,52 @@ template <int C> __global__ __launch_bounds__(256, 1) void wide_stack_kernel(con
             const int hi = (u_end < (pass + 1) * per_pass ? u_end : (pass + 1) * per_pass) - pass * per_pass;
             if (lo >= hi) continue;
             switch (L.r) {
-                case 2: run_wide_units<2, C>(L, p, pass, lo, hi, worker, wv, lane, lds); break;
-                case 3: run_wide_units<3, C>(L, p, pass, lo, hi, worker, wv, lane, lds); break;
-                case 4: run_wide_units<4, C>(L, p, pass, lo, hi, worker, wv, lane, lds); break;
-                case 6: run_wide_units<6, C>(L, p, pass, lo, hi, worker, wv, lane, lds); break;
-                default: run_wide_units<8, C>(L, p, pass, lo, hi, worker, wv, lane, lds); break;
+                case 2: run_wide_units<2, C, TWO>(L, p, pass, lo, hi, worker, wv, lane, lds); break;
+                case 3: run_wide_units<3, C, TWO>(L, p, pass, lo, hi, worker, wv, lane, lds); break;
+                case 4: run_wide_units<4, C, TWO>(L, p, pass, lo, hi, worker, wv, lane, lds); break;
+                case 6: run_wide_units<6, C, TWO>(L, p, pass, lo, hi, worker, wv, lane, lds); break;
+                default: run_wide_units<8, C, TWO>(L, p, pass, lo, hi, worker, wv, lane, lds); break;
             }
         }
     });
 }
 
 // workgroups the device keeps resident for a launch with lds_bytes of LDS per workgroup
-template <int C> static int wide_resident_groups(int lds_bytes) {
+template <int C, bool TWO> static int wide_resident_groups(int lds_bytes) {
     static int cached_bytes[2] = {0, 0}, cached[2] = {0, 0};
     for (int i = 0; i < 2; ++i)
         if (cached_bytes[i] == lds_bytes) return cached[i];
     int dev = 0, cus = 0, blocks = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&wide_stack_kernel<C>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, wide_lds_bytes_max(C)) != hipSuccess)
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&wide_stack_kernel<C, TWO>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, wide_lds_bytes_max(C, TWO)) != hipSuccess)
         return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, wide_stack_kernel<C>, 256, lds_bytes) != hipSuccess)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, wide_stack_kernel<C, TWO>, 256, lds_bytes) != hipSuccess)
         return 0;
     if (blocks < 1) blocks = 1;
     int w = cus * blocks;
     if (w > wide_max_groups(C)) w = wide_max_groups(C);
+    if (!TWO && w > cus) w = cus;  // this variant is planned for a compute unit of its own
     const int slot = cached_bytes[0] == 0 ? 0 : 1;
     cached_bytes[slot] = lds_bytes;
     cached[slot] = w;
     return w;
 }
 
-template <int C> static hipError_t launch_wide_c(StackParams p, int max_cost, hipStream_t s) {
+template <int C, bool TWO> static hipError_t launch_wide_c(StackParams p, int max_cost, hipStream_t s) {
     // LDS per workgroup: a single layer takes the plan of its width, a stack the largest plan
-    int lds_bytes = wide_lds_bytes_max(C);
+    int lds_bytes = wide_lds_bytes_max(C, TWO);
     if (!p.table) {
         switch (p.single.r) {
-            case 2: lds_bytes = wide_lds_bytes(2, C); break;
-            case 3: lds_bytes = wide_lds_bytes(3, C); break;
-            case 4: lds_bytes = wide_lds_bytes(4, C); break;
-            case 6: lds_bytes = wide_lds_bytes(6, C); break;
-            default: lds_bytes = wide_lds_bytes(8, C); break;
+            case 2: lds_bytes = wide_lds_bytes(2, C, TWO); break;
+            case 3: lds_bytes = wide_lds_bytes(3, C, TWO); break;
+            case 4: lds_bytes = wide_lds_bytes(4, C, TWO); break;
+            case 6: lds_bytes = wide_lds_bytes(6, C, TWO); break;
+            default: lds_bytes = wide_lds_bytes(8, C, TWO); break;
         }
     }
-    const int hw = wide_resident_groups<C>(lds_bytes);
+    const int hw = wide_resident_groups<C, TWO>(lds_bytes);
     if (hw <= 0) return hipErrorUnknown;
     // shares of at least eight super-tiles: a small layer cut into more shares spends more on handing its row blocks
     // over than it gains in parallelism (Llama-2-7B shapes at M = 128: 52 -> 40 us per call)
@@ -694,15 +714,18 @@ template <int C> static hipError_t launch_wide_c(StackParams p, int max_cost, hi
     p.slot_floats = 4 * C * 32 * 64;
     const hipError_t e = launch(xprep_wide_kernel, dim3((unsigned)p.n_jobs), dim3(256), 0, s, p);
     if (e != hipSuccess) return e;
-    return launch(wide_stack_kernel<C>, dim3((unsigned)p.nworkers), dim3(256), (unsigned)lds_bytes, s, p);
+    return launch(wide_stack_kernel<C, TWO>, dim3((unsigned)p.nworkers), dim3(256), (unsigned)lds_bytes, s, p);
 }
 
 hipError_t launch_stack_wide(StackParams p, int max_cost, hipStream_t s) {
     switch (wide_chunks_per_pass(p.M)) {
-        case 1: return launch_wide_c<1>(p, max_cost, s);
-        case 2: return launch_wide_c<2>(p, max_cost, s);
-        case 3: return launch_wide_c<3>(p, max_cost, s);
-        default: return launch_wide_c<4>(p, max_cost, s);
+        // Two workgroups per compute unit pay off where shares are long (a stack: 16 Llama-3-70B blocks at M = 64 take
+        // 2.56 ms instead of 2.98).  A single layer cut into twice as many shares hands twice as many partial row
+        // blocks over (64 KB each) and gains nothing: it keeps one workgroup per compute unit and the deeper rings.
+        case 1: return p.table ? launch_wide_c<1, true>(p, max_cost, s) : launch_wide_c<1, false>(p, max_cost, s);
+        case 2: return p.table ? launch_wide_c<2, true>(p, max_cost, s) : launch_wide_c<2, false>(p, max_cost, s);
+        case 3: return launch_wide_c<3, false>(p, max_cost, s);
+        default: return launch_wide_c<4, false>(p, max_cost, s);
     }
 }
 
