@@ -1,6 +1,6 @@
 """GPU parity at full size for the batched regime (Section 4, the matrix-core kernel): both Llama-3-70B MLP shapes
 at the batches where the wide kernel runs in its real launch shape (several chunks per pass, two passes at M = 256,
-256 workgroups, long split-K hand-over chains on the down-projection), and a Llama-3-70B-shaped stack at M = 32.
+256 workgroups, long split-K hand-over chains on the down-projection), and a Llama-3-70B-shaped stack at M = 32, 64 and 96.
 The oracle computes sampled output rows (rows are independent); all of y is checked to be finite."""
 import numpy as np
 import pytest
@@ -61,9 +61,11 @@ def test_llama3_70b_down_projection_small_batches_sampled_rows():
             check_y(y[:, rt], ref, f"70B down r={r} M={M}", sub, r)
 
 
-def test_llama3_70b_shaped_stack_three_blocks_at_m32():
-    # 21 linears at the real shapes, widths by seed, one persistent launch on the wide matrix-core path
-    M, n_blocks = 32, 3
+@pytest.mark.parametrize("M", [32, 64, 96])
+def test_llama3_70b_shaped_stack_three_blocks(M):
+    # 21 linears at the real shapes, widths by seed, one persistent launch on the wide matrix-core path: one and two
+    # chunks per pass (two workgroups per compute unit, accumulators in vector registers) and three (one per unit)
+    n_blocks = 3
     shapes = synth.stack_shapes(synth.LLAMA3_70B_BLOCK, n_blocks)
     widths, _ = synth.draw_bitwidths([N * K for (_, _, N, K) in shapes], 4.0, seed=6, tol=0.3)
     gen, layers = [], []
@@ -84,7 +86,7 @@ def test_llama3_70b_shaped_stack_three_blocks_at_m32():
         rt = torch.from_numpy(rows).to(DEV)
         sub = dict(x=G["x"].cpu().numpy(), parent=G["parent"][rt].cpu().numpy(), scales=G["scales"][rt].cpu().numpy(),
                    zeros=G["zeros"][rt].cpu().numpy())
-        check_layer(lay["y"][:, rt], sub, lay["r"], f"70B stack M=32 linear {i} r={lay['r']}")
+        check_layer(lay["y"][:, rt], sub, lay["r"], f"70B stack M={M} linear {i} r={lay['r']}")
     first = [lay["y"].clone() for lay in layers]
     mq.mq_linear_stack(plan)
     torch.cuda.synchronize()
