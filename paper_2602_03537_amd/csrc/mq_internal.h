@@ -136,10 +136,11 @@ inline int mfma_tile_cost(int r) {
 }
 
 // Wide MFMA path: cost of a super-tile (256 rows x one group) per pass with C chunks of 32 columns, again the measured
-// times of uniform stacks (12 Llama-3-70B blocks at M = 32, 64, 96, 128; units of 10 us).  The matrix-core work grows
-// with C, the unpacking with r; bytes matter least.
+// times of uniform stacks (12 Llama-3-70B blocks at M = 32, 64, 96, 128; units of 10 us; the first two rows with two
+// workgroups per compute unit, as stacks run there).  The matrix-core work grows with C, the unpacking with r; bytes
+// matter least.
 inline int wide_tile_cost(int r, int C) {
-    static const int t[4][5] = {{146, 160, 164, 191, 213}, {194, 204, 212, 247, 272},
+    static const int t[4][5] = {{130, 141, 147, 178, 199}, {173, 186, 191, 222, 239},
                                 {239, 252, 262, 306, 323}, {293, 308, 318, 358, 377}};
     const int ri = r == 2 ? 0 : r == 3 ? 1 : r == 4 ? 2 : r == 6 ? 3 : 4;
     return t[(C < 1 ? 1 : C > 4 ? 4 : C) - 1][ri];
