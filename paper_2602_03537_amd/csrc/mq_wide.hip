@@ -414,7 +414,9 @@ static_assert(wide_lds_bytes_max(4, false) <= wide_lds_budget(false) && wide_lds
 // C = chunks of 32 batch columns per pass (the layer's chunk count is padded to passes * C; padding
 // chunks hold zeros).
 //
-// A wave is alone on its SIMD here, so nothing but the instruction order hides latencies.  MFMAs run
+// TWO: the variant whose workgroups share a compute unit in pairs (two waves per SIMD, half the LDS, accumulators in
+// vector registers); otherwise a wave is alone on its SIMD.  The schedule is written for the wave that is alone, where
+// nothing but the instruction order hides latencies, and a second wave only adds to what it hides.  MFMAs run
 // spec by spec: the two weight operands of spec s (rows 0..31 and 32..63 of the tile) meet the C chunks
 // in 2C consecutive "slots"; each slot is one MFMA followed by a share of the vector work that forms
 // the operands of the NEXT spec (the matrix core needs 32 cycles per MFMA, a vector instruction 4),
