@@ -1162,8 +1162,9 @@ def test_bf16_activations_and_outputs(r, shape_m):
     assert np.array_equal(got, _bf16_round(got))
 
 
-def test_bf16_flags_in_a_mixed_stack():
-    M = 2
+@pytest.mark.parametrize("M", [2, 8, 40, 100])
+def test_bf16_flags_in_a_mixed_stack(M):
+    # vector ALUs, narrow matrix-core kernel, wide kernel with two workgroups per compute unit and with one
     shapes_r = [(256, 512, 2), (64, 128, 8), (200, 1280, 3), (512, 256, 6)]
     host, layers = [], []
     for i, (N, K, r) in enumerate(shapes_r):
@@ -1182,6 +1183,6 @@ def test_bf16_flags_in_a_mixed_stack():
         ref = oracle.linear(L["x"], L["parent"], L["scales"], L["zeros"], C, L["r"], 128)
         got = lay["y"].float().cpu().numpy().astype(np.float64)
         if L["flags"] & mq.MQ_Y_BF16:
-            assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 3e-3), i
+            assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 3e-3), (M, i)
         else:
-            check_layer(lay["y"], L, L["r"], f"mixed flags layer {i}")
+            check_layer(lay["y"], L, L["r"], f"mixed flags M={M} layer {i}")
