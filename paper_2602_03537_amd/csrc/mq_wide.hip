@@ -560,7 +560,10 @@ __device__ __forceinline__ void run_wide_units(const LayerDesc &L, const StackPa
                         constexpr int q0 = ((s + 1) % kWideSpecs) * 8 + 2 * pr;
                         if constexpr (kJobStage[j] == 1) {
                             uint32_t a = wide_operand_s1<R, q0>(e), b = wide_operand_s1<R, q0 + 1>(e);
-                            asm volatile("" : "+v"(a), "+v"(b));  // keeps the work in this slot
+                            // Keeps the work in this slot.  Needed for correctness, not only for the schedule: the
+                            // compiler places no wait states between these vector writes and an MFMA it cannot see
+                            // inside inline assembly, so the operands must be formed a slot ahead of their use.
+                            asm volatile("" : "+v"(a), "+v"(b));
                             half_done[pr][0] = a;
                             half_done[pr][1] = b;
                         } else {
